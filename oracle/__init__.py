@@ -1,0 +1,202 @@
+"""ctypes front-end of the CPU oracle (``des_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: importable from ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py``; never from the HIP path.  Everything here is argument
+marshalling; the arithmetic is in the C file, in double precision.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "des_oracle.c")
+_LIB = os.path.join(_HERE, "libdes_oracle.so")
+
+SHARD_KEY_HASH, SHARD_FIELD_MOD = 0, 1
+OPT_NONE, OPT_SGD, OPT_ADAGRAD = 0, 1, 2
+OK, ERR_INVALID_ARG, ERR_INVALID_KEY, ERR_FULL = 0, 1, 2, 3
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (-O2, no FMA contraction so fp32 steps round as written)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-std=c11", "-shared", "-fPIC",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(_LIB)
+        vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
+        L.oracle_mix64.restype = u64; L.oracle_mix64.argtypes = [u64]
+        L.oracle_shard.restype = C.c_int; L.oracle_shard.argtypes = [u64, i32, C.c_int, C.c_int]
+        L.oracle_init_value.restype = f32; L.oracle_init_value.argtypes = [u64, C.c_int, u64, f32]
+        L.oracle_table_create.restype = vp; L.oracle_table_create.argtypes = [C.c_int, i64, u64, f32]
+        L.oracle_table_destroy.restype = None; L.oracle_table_destroy.argtypes = [vp]
+        L.oracle_table_size.restype = i64; L.oracle_table_size.argtypes = [vp]
+        for name in ("row_keys", "emb", "w", "acc_emb", "acc_w"):
+            fn = getattr(L, "oracle_table_" + name); fn.restype = vp; fn.argtypes = [vp]
+        L.oracle_table_insert.restype = C.c_int; L.oracle_table_insert.argtypes = [vp, vp, i64, vp, vp]
+        L.oracle_table_find.restype = C.c_int; L.oracle_table_find.argtypes = [vp, vp, i64, C.c_int, vp]
+        L.oracle_partial_forward.restype = None
+        L.oracle_partial_forward.argtypes = [vp, i64, i32, vp, vp, vp, vp, C.c_int, C.c_int, vp, vp, vp, vp]
+        L.oracle_aggregate.restype = None; L.oracle_aggregate.argtypes = [vp, C.c_int, i64, vp]
+        L.oracle_fm_finalize.restype = None; L.oracle_fm_finalize.argtypes = [vp, vp, i64, C.c_int, vp]
+        L.oracle_backward_update.restype = i64
+        L.oracle_backward_update.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, C.c_int, f32, f32,
+                                             vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dtype):
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def mix64(z: int) -> int:
+    return int(lib().oracle_mix64(C.c_uint64(int(z) & 0xFFFFFFFFFFFFFFFF)))
+
+
+def shard(key: int, field: int, K: int, policy: int = SHARD_KEY_HASH) -> int:
+    return int(lib().oracle_shard(C.c_uint64(int(key)), int(field), int(K), int(policy)))
+
+
+def init_value(key: int, column: int, seed: int, init_scale: float) -> float:
+    return float(lib().oracle_init_value(C.c_uint64(int(key)), int(column), C.c_uint64(int(seed)),
+                                         C.c_float(init_scale)))
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code):
+        super().__init__(f"oracle status {code}")
+        self.code = code
+
+
+class Table:
+    """Key -> row map plus fp32 weights and optimizer state; see ``des_oracle.c``."""
+
+    def __init__(self, D: int, capacity: int, seed: int = 0, init_scale: float = 0.01):
+        self.D, self.capacity = int(D), int(capacity)
+        self._h = lib().oracle_table_create(self.D, self.capacity, C.c_uint64(seed), C.c_float(init_scale))
+        if not self._h:
+            raise OracleError(ERR_INVALID_ARG)
+
+    def close(self):
+        if self._h:
+            lib().oracle_table_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def n_rows(self) -> int:
+        return int(lib().oracle_table_size(self._h))
+
+    def _view(self, name, ctype, shape):
+        ptr = getattr(lib(), "oracle_table_" + name)(self._h)
+        n = int(np.prod(shape))
+        if n == 0:
+            return np.zeros(shape, dtype=np.dtype(ctype))
+        return np.ctypeslib.as_array(C.cast(ptr, C.POINTER(ctype)), shape=(n,)).reshape(shape)
+
+    # views of the live rows (no copy)
+    @property
+    def row_keys(self): return self._view("row_keys", C.c_uint64, (self.n_rows,))
+    @property
+    def emb(self): return self._view("emb", C.c_float, (self.n_rows, self.D))
+    @property
+    def w(self): return self._view("w", C.c_float, (self.n_rows,))
+    @property
+    def acc_emb(self): return self._view("acc_emb", C.c_float, (self.n_rows, self.D))
+    @property
+    def acc_w(self): return self._view("acc_w", C.c_float, (self.n_rows,))
+
+    def insert(self, keys, values=None) -> np.ndarray:
+        keys = _c(keys, np.uint64)
+        values = _c(values, np.float32)
+        if values is not None and values.shape != (keys.shape[0], self.D + 1):
+            raise ValueError("values must be [n, D+1]")
+        rows = np.empty(keys.shape[0], dtype=np.int32)
+        rc = lib().oracle_table_insert(self._h, _p(keys), keys.shape[0], _p(values), _p(rows))
+        if rc:
+            raise OracleError(rc)
+        return rows
+
+    def find(self, keys, insert_missing: bool = False) -> np.ndarray:
+        keys = _c(keys, np.uint64)
+        rows = np.empty(keys.shape[0], dtype=np.int32)
+        rc = lib().oracle_table_find(self._h, _p(keys), keys.shape[0], int(insert_missing), _p(rows))
+        if rc:
+            raise OracleError(rc)
+        return rows
+
+    def partial_forward(self, B, F, keys, offsets, rows, K, policy=SHARD_KEY_HASH, vals=None,
+                        lr=True, fm=True, pool=True):
+        """Double-precision partials: dict with P_lr[K,B], P_sum[K,B,D], P_sq[K,B], P_pool[K,B,F,D]."""
+        keys, offsets, rows = _c(keys, np.uint64), _c(offsets, np.int32), _c(rows, np.int32)
+        vals = _c(vals, np.float32)
+        D = self.D
+        out = {
+            "P_lr": np.empty((K, B), np.float64) if lr else None,
+            "P_sum": np.empty((K, B, D), np.float64) if fm else None,
+            "P_sq": np.empty((K, B), np.float64) if fm else None,
+            "P_pool": np.empty((K, B, F, D), np.float64) if pool else None,
+        }
+        lib().oracle_partial_forward(self._h, B, F, _p(keys), _p(offsets), _p(vals), _p(rows), K, policy,
+                                     _p(out["P_lr"]), _p(out["P_sum"]), _p(out["P_sq"]), _p(out["P_pool"]))
+        return out
+
+    def backward_update(self, B, F, offsets, rows, g_lr=None, g_fm=None, A_sum=None, g_pool=None,
+                        opt=OPT_NONE, lr=0.0, eps=0.0, vals=None):
+        """Merge duplicate-row gradients (ascending row order) and apply the optimizer in place.
+        Returns dict(uniq_rows, uniq_keys, counts, merged[U,D+1] float64)."""
+        offsets, rows = _c(offsets, np.int32), _c(rows, np.int32)
+        vals = _c(vals, np.float32)
+        g_lr, g_fm, A_sum, g_pool = (_c(a, np.float32) for a in (g_lr, g_fm, A_sum, g_pool))
+        if (g_fm is None) != (A_sum is None):
+            raise ValueError("g_fm and A_sum go together")
+        nnz = int(offsets[B * F])
+        uniq_rows = np.empty(nnz, np.int32); uniq_keys = np.empty(nnz, np.uint64)
+        counts = np.empty(nnz, np.int32); merged = np.empty((nnz, self.D + 1), np.float64)
+        U = int(lib().oracle_backward_update(self._h, B, F, _p(offsets), _p(vals), _p(rows), _p(g_lr), _p(g_fm),
+                                             _p(A_sum), _p(g_pool), opt, C.c_float(lr), C.c_float(eps),
+                                             _p(uniq_rows), _p(uniq_keys), _p(counts), _p(merged)))
+        return {"uniq_rows": uniq_rows[:U].copy(), "uniq_keys": uniq_keys[:U].copy(),
+                "counts": counts[:U].copy(), "merged": merged[:U].copy()}
+
+
+def aggregate(P: np.ndarray) -> np.ndarray:
+    """Sum over the leading (shard) axis in double: the on-device stand-in of the collective."""
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    K = P.shape[0]
+    n = int(np.prod(P.shape[1:]))
+    out = np.empty(P.shape[1:], np.float64)
+    lib().oracle_aggregate(_p(P), K, n, _p(out))
+    return out
+
+
+def fm_finalize(A_sum: np.ndarray, A_sq: np.ndarray) -> np.ndarray:
+    A_sum = np.ascontiguousarray(A_sum, np.float64); A_sq = np.ascontiguousarray(A_sq, np.float64)
+    B, D = A_sum.shape
+    out = np.empty(B, np.float64)
+    lib().oracle_fm_finalize(_p(A_sum), _p(A_sq), B, D, _p(out))
+    return out

@@ -1,0 +1,316 @@
+/*
+ * CPU oracle for the sparse hot path of Distributed Equivalent Substitution (DES) training.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the HIP library is
+ * checked against.  It shares no code with the HIP path and must never be called from it;
+ * only tests, the smoke check and the CPU-baseline leg of the benchmark may use it.
+ *
+ * All floating-point accumulation is done in double from fp32 inputs.  Where a result is
+ * stored in the table (weights, optimizer state) it is rounded to fp32 once.
+ *
+ * What each function follows in the paper (arXiv 1909.04823):
+ *   table insert / find / update ....... Section 5, "Dynamic Hash Table" (lookup, insert of an
+ *                                        initialized weight for a new feature ID, update)
+ *   shard routing ...................... Section 5, "Large-scale Sparse Features" (i = f mod N)
+ *                                        and Section 4.2 (any balanced partition of V)
+ *   LR partial M1 ...................... Section 4.1, Eq. (lr_m1)
+ *   FM partials M1, M2 and F ........... Section 4.2, Eq. (fm_m1m2), Eq. (des_fm2)
+ *   per-field pooling .................. Section 4.3 (latent vectors aggregated by field)
+ *   aggregation (+) .................... Section 3.2.1, Eq. (1); Algorithm 1
+ *   backward ........................... Section 3.2.2, "Back-propagation Phase": the gradient
+ *                                        of the aggregate reaches every sub-operator unchanged
+ *
+ * Conventions the paper leaves open and this build fixes (the HIP library implements the same
+ * text independently): the 64-bit mixer, the row initialiser, the row-assignment order, the
+ * merged-key order and the placement of eps in Adagrad.  These are "parity unpinned": nothing
+ * in the paper can confirm them, the two implementations merely have to agree.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_INVALID_ARG 1
+#define ORACLE_ERR_INVALID_KEY 2
+#define ORACLE_ERR_FULL 3
+
+#define ORACLE_EMPTY_KEY 0xFFFFFFFFFFFFFFFFull
+
+enum { SHARD_KEY_HASH = 0, SHARD_FIELD_MOD = 1 };
+enum { OPT_NONE = 0, OPT_SGD = 1, OPT_ADAGRAD = 2 };
+
+/* ------------------------------------------------------------------ conventions ---------- */
+
+/* 64-bit finalizer of the SplitMix64 generator (Steele, Lea, Flood 2014). */
+uint64_t oracle_mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+/* Which of the K logical shards owns an entry. */
+int oracle_shard(uint64_t key, int32_t field, int K, int policy) {
+  if (policy == SHARD_FIELD_MOD) return (int)(field % K);
+  return (int)((uint32_t)(oracle_mix64(key) >> 32) % (uint32_t)K);
+}
+
+/* Initial value of column c (c < D: latent, c == D: LR weight) of a row inserted without
+ * host values: uniform on [-sqrt(3) s, sqrt(3) s) (standard deviation s), a pure function of
+ * (key, column, seed).  The 24-bit fraction and the subtraction are exact in fp32, so the
+ * value is one correctly rounded fp32 product. */
+float oracle_init_value(uint64_t key, int c, uint64_t seed, float init_scale) {
+  uint64_t h = oracle_mix64(key ^ oracle_mix64(seed + (uint64_t)c));
+  float u = (float)(h >> 40) * (1.0f / 16777216.0f);
+  float width = (float)(2.0 * sqrt(3.0) * (double)init_scale);
+  volatile float centred = u - 0.5f;
+  return centred * width;
+}
+
+/* ------------------------------------------------------------------ table ---------------- */
+
+typedef struct oracle_table {
+  int D;
+  int64_t capacity, n_rows;
+  uint64_t seed;
+  float init_scale;
+  uint64_t *row_keys;           /* [capacity] row -> key                                   */
+  float *emb, *w, *acc_emb, *acc_w;
+  uint64_t *skeys;              /* keys in ascending order                                  */
+  int32_t *srows;               /* row of skeys[i]                                          */
+} oracle_table;
+
+oracle_table *oracle_table_create(int D, int64_t capacity, uint64_t seed, float init_scale) {
+  if (D <= 0 || capacity <= 0 || capacity > 2147483646ll) return NULL;
+  oracle_table *t = (oracle_table *)calloc(1, sizeof(*t));
+  if (!t) return NULL;
+  t->D = D; t->capacity = capacity; t->seed = seed; t->init_scale = init_scale;
+  t->row_keys = (uint64_t *)calloc((size_t)capacity, sizeof(uint64_t));
+  t->emb = (float *)calloc((size_t)capacity * D, sizeof(float));
+  t->w = (float *)calloc((size_t)capacity, sizeof(float));
+  t->acc_emb = (float *)calloc((size_t)capacity * D, sizeof(float));
+  t->acc_w = (float *)calloc((size_t)capacity, sizeof(float));
+  t->skeys = (uint64_t *)calloc((size_t)capacity, sizeof(uint64_t));
+  t->srows = (int32_t *)calloc((size_t)capacity, sizeof(int32_t));
+  if (!t->row_keys || !t->emb || !t->w || !t->acc_emb || !t->acc_w || !t->skeys || !t->srows) return NULL;
+  return t;
+}
+
+void oracle_table_destroy(oracle_table *t) {
+  if (!t) return;
+  free(t->row_keys); free(t->emb); free(t->w); free(t->acc_emb); free(t->acc_w);
+  free(t->skeys); free(t->srows); free(t);
+}
+
+int64_t oracle_table_size(const oracle_table *t) { return t->n_rows; }
+uint64_t *oracle_table_row_keys(oracle_table *t) { return t->row_keys; }
+float *oracle_table_emb(oracle_table *t) { return t->emb; }
+float *oracle_table_w(oracle_table *t) { return t->w; }
+float *oracle_table_acc_emb(oracle_table *t) { return t->acc_emb; }
+float *oracle_table_acc_w(oracle_table *t) { return t->acc_w; }
+
+/* Row of a key, or -1: binary search in the ascending key list. */
+static int32_t lookup(const oracle_table *t, uint64_t key) {
+  int64_t lo = 0, hi = t->n_rows;
+  while (lo < hi) {
+    int64_t mid = lo + (hi - lo) / 2;
+    if (t->skeys[mid] < key) lo = mid + 1; else hi = mid;
+  }
+  return (lo < t->n_rows && t->skeys[lo] == key) ? t->srows[lo] : -1;
+}
+
+typedef struct { uint64_t key; int64_t first; } newkey_t;
+
+static int cmp_newkey(const void *a, const void *b) {
+  const newkey_t *x = (const newkey_t *)a, *y = (const newkey_t *)b;
+  if (x->key != y->key) return x->key < y->key ? -1 : 1;
+  return x->first < y->first ? -1 : (x->first > y->first);
+}
+
+/* Insert-if-absent.  The distinct keys of this call that the table does not hold yet receive
+ * the next consecutive rows in ascending unsigned key order.  Their weights are the host
+ * values of the key's first occurrence in the call, or the initialiser; optimizer state is
+ * zero.  Keys already present are left untouched.  rows_out[i] = row of keys[i]. */
+int oracle_table_insert(oracle_table *t, const uint64_t *keys, int64_t n, const float *values,
+                        int32_t *rows_out) {
+  if (!t || n < 0 || (n > 0 && !keys)) return ORACLE_ERR_INVALID_ARG;
+  for (int64_t i = 0; i < n; ++i) if (keys[i] == ORACLE_EMPTY_KEY) return ORACLE_ERR_INVALID_KEY;
+  newkey_t *cand = (newkey_t *)malloc(sizeof(newkey_t) * (size_t)(n > 0 ? n : 1));
+  int64_t m = 0;
+  for (int64_t i = 0; i < n; ++i)
+    if (lookup(t, keys[i]) < 0) { cand[m].key = keys[i]; cand[m].first = i; ++m; }
+  qsort(cand, (size_t)m, sizeof(newkey_t), cmp_newkey);
+  int64_t u = 0;                                   /* distinct new keys, first occurrence kept */
+  for (int64_t i = 0; i < m; ++i)
+    if (i == 0 || cand[i].key != cand[i - 1].key) cand[u++] = cand[i];
+  if (t->n_rows + u > t->capacity) { free(cand); return ORACLE_ERR_FULL; }
+  const int D = t->D;
+  for (int64_t j = 0; j < u; ++j) {
+    int64_t row = t->n_rows + j;
+    uint64_t k = cand[j].key;
+    t->row_keys[row] = k;
+    for (int c = 0; c < D; ++c)
+      t->emb[row * D + c] = values ? values[cand[j].first * (D + 1) + c]
+                                   : oracle_init_value(k, c, t->seed, t->init_scale);
+    t->w[row] = values ? values[cand[j].first * (D + 1) + D]
+                       : oracle_init_value(k, D, t->seed, t->init_scale);
+    for (int c = 0; c < D; ++c) t->acc_emb[row * D + c] = 0.0f;
+    t->acc_w[row] = 0.0f;
+  }
+  /* merge the new (ascending) keys into the ascending key list, back to front */
+  int64_t a = t->n_rows - 1, b = u - 1, o = t->n_rows + u - 1;
+  while (b >= 0) {
+    if (a >= 0 && t->skeys[a] > cand[b].key) { t->skeys[o] = t->skeys[a]; t->srows[o] = t->srows[a]; --a; }
+    else { t->skeys[o] = cand[b].key; t->srows[o] = (int32_t)(t->n_rows + b); --b; }
+    --o;
+  }
+  t->n_rows += u;
+  free(cand);
+  if (rows_out) for (int64_t i = 0; i < n; ++i) rows_out[i] = lookup(t, keys[i]);
+  return ORACLE_OK;
+}
+
+/* Lookup; with insert_missing the absent keys are inserted first (initialiser weights), so one
+ * call both looks up and grows the table.  Absent keys otherwise map to -1. */
+int oracle_table_find(oracle_table *t, const uint64_t *keys, int64_t n, int insert_missing,
+                      int32_t *rows_out) {
+  if (!t || n < 0 || (n > 0 && (!keys || !rows_out))) return ORACLE_ERR_INVALID_ARG;
+  if (insert_missing) return oracle_table_insert(t, keys, n, NULL, rows_out);
+  for (int64_t i = 0; i < n; ++i) if (keys[i] == ORACLE_EMPTY_KEY) return ORACLE_ERR_INVALID_KEY;
+  for (int64_t i = 0; i < n; ++i) rows_out[i] = lookup(t, keys[i]);
+  return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ forward -------------- */
+
+/* Per-shard partial results of every sample.  Each CSR entry is one feature term, also when
+ * a key repeats inside a sample.  Entries whose row is -1 contribute nothing.
+ *   P_lr  [K,B]      sum of x*w over the shard's entries of the sample        (LR  M1)
+ *   P_sum [K,B,D]    sum of x*v                                               (FM  M1)
+ *   P_sq  [K,B]      sum of <x*v, x*v>                                        (FM  M2)
+ *   P_pool[K,B,F,D]  sum of x*v over the shard's entries of bag (b,f)         (pooling)
+ * Any output pointer may be NULL. */
+void oracle_partial_forward(const oracle_table *t, int64_t B, int32_t F, const uint64_t *keys,
+                            const int32_t *offsets, const float *vals, const int32_t *rows,
+                            int K, int policy, double *P_lr, double *P_sum, double *P_sq,
+                            double *P_pool) {
+  const int D = t->D;
+  if (P_lr) memset(P_lr, 0, sizeof(double) * (size_t)K * B);
+  if (P_sum) memset(P_sum, 0, sizeof(double) * (size_t)K * B * D);
+  if (P_sq) memset(P_sq, 0, sizeof(double) * (size_t)K * B);
+  if (P_pool) memset(P_pool, 0, sizeof(double) * (size_t)K * B * F * D);
+  for (int64_t b = 0; b < B; ++b)
+    for (int32_t f = 0; f < F; ++f)
+      for (int32_t e = offsets[b * F + f]; e < offsets[b * F + f + 1]; ++e) {
+        int32_t r = rows[e];
+        if (r < 0) continue;
+        int s = oracle_shard(keys[e], f, K, policy);
+        double x = vals ? (double)vals[e] : 1.0;
+        if (P_lr) P_lr[(int64_t)s * B + b] += x * (double)t->w[r];
+        for (int d = 0; d < D; ++d) {
+          double xv = x * (double)t->emb[(int64_t)r * D + d];
+          if (P_sum) P_sum[((int64_t)s * B + b) * D + d] += xv;
+          if (P_sq) P_sq[(int64_t)s * B + b] += xv * xv;
+          if (P_pool) P_pool[(((int64_t)s * B + b) * F + f) * D + d] += xv;
+        }
+      }
+}
+
+/* Aggregation over the K shards: out[i] = sum_s P[s][i]. */
+void oracle_aggregate(const double *P, int K, int64_t n, double *out) {
+  for (int64_t i = 0; i < n; ++i) {
+    double a = 0.0;
+    for (int s = 0; s < K; ++s) a += P[(int64_t)s * n + i];
+    out[i] = a;
+  }
+}
+
+/* Substitution operator of FM order 2: half of (<A_sum, A_sum> - A_sq) per sample. */
+void oracle_fm_finalize(const double *A_sum, const double *A_sq, int64_t B, int D, double *fm2) {
+  for (int64_t b = 0; b < B; ++b) {
+    double q = 0.0;
+    for (int d = 0; d < D; ++d) q += A_sum[b * D + d] * A_sum[b * D + d];
+    fm2[b] = 0.5 * (q - A_sq[b]);
+  }
+}
+
+/* ------------------------------------------------------------------ backward ------------- */
+
+typedef struct { int32_t row; int32_t e; } rowent_t;
+
+static int cmp_rowent(const void *a, const void *b) {
+  const rowent_t *x = (const rowent_t *)a, *y = (const rowent_t *)b;
+  if (x->row != y->row) return x->row < y->row ? -1 : 1;
+  return x->e < y->e ? -1 : (x->e > y->e);
+}
+
+/* Backward of the three sparse operators, duplicate-key merge and optimizer update.
+ *
+ * With upstream gradients g_lr[B] (of the aggregated LR sum), g_fm[B] (of the FM order-2
+ * value), g_pool[B,F,D] (of the pooled embeddings) and the aggregated FM vector A_sum[B,D]
+ * that the forward pass returned (fp32), entry e of bag (b,f) with value x and row r gets
+ *     d/dw_r   : x * g_lr[b]
+ *     d/dv_r,d : x * ( g_fm[b] * (A_sum[b,d] - x * v[r,d]) + g_pool[b,f,d] )
+ * (the FM term is the derivative of Eq. (des_fm2)).  Gradients of entries that share a row
+ * are summed; distinct rows are emitted in ascending row order.  The update then touches
+ * exactly those rows, reading the pre-update weights:
+ *     SGD      theta <- theta - lr*G
+ *     Adagrad  a <- a + G^2 ;  theta <- theta - lr*G / (sqrt(a) + eps)   (a already updated)
+ * Any of g_lr, g_fm (with A_sum), g_pool may be NULL (term absent).  opt = OPT_NONE only
+ * merges.  Returns the number U of distinct rows; outputs (all nullable) hold U entries:
+ * uniq_rows, uniq_keys, counts, merged[U, D+1] (D latent columns then the LR weight). */
+int64_t oracle_backward_update(oracle_table *t, int64_t B, int32_t F, const int32_t *offsets,
+                               const float *vals, const int32_t *rows, const float *g_lr,
+                               const float *g_fm, const float *A_sum, const float *g_pool,
+                               int opt, float lr, float eps, int32_t *uniq_rows,
+                               uint64_t *uniq_keys, int32_t *counts, double *merged) {
+  const int D = t->D;
+  const int64_t nnz = offsets[B * F];
+  rowent_t *ent = (rowent_t *)malloc(sizeof(rowent_t) * (size_t)(nnz > 0 ? nnz : 1));
+  int32_t *bag_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nnz > 0 ? nnz : 1));
+  int64_t m = 0;
+  for (int64_t bag = 0; bag < B * F; ++bag)
+    for (int32_t e = offsets[bag]; e < offsets[bag + 1]; ++e) {
+      bag_of[e] = (int32_t)bag;
+      if (rows[e] >= 0) { ent[m].row = rows[e]; ent[m].e = e; ++m; }
+    }
+  qsort(ent, (size_t)m, sizeof(rowent_t), cmp_rowent);
+  double *G = (double *)malloc(sizeof(double) * (size_t)(D + 1));
+  int64_t U = 0;
+  for (int64_t i = 0; i < m;) {
+    int64_t j = i;
+    const int32_t r = ent[i].row;
+    for (int c = 0; c <= D; ++c) G[c] = 0.0;
+    for (; j < m && ent[j].row == r; ++j) {
+      const int32_t e = ent[j].e;
+      const int64_t bag = bag_of[e], b = bag / F;
+      const double x = vals ? (double)vals[e] : 1.0;
+      if (g_lr) G[D] += x * (double)g_lr[b];
+      for (int d = 0; d < D; ++d) {
+        double g = 0.0;
+        if (g_fm) g += (double)g_fm[b] * ((double)A_sum[b * D + d] - x * (double)t->emb[(int64_t)r * D + d]);
+        if (g_pool) g += (double)g_pool[bag * D + d];
+        G[d] += x * g;
+      }
+    }
+    if (uniq_rows) uniq_rows[U] = r;
+    if (uniq_keys) uniq_keys[U] = t->row_keys[r];
+    if (counts) counts[U] = (int32_t)(j - i);
+    if (merged) for (int c = 0; c <= D; ++c) merged[U * (D + 1) + c] = G[c];
+    for (int c = 0; c <= D; ++c) {
+      float *theta = c < D ? &t->emb[(int64_t)r * D + c] : &t->w[r];
+      float *acc = c < D ? &t->acc_emb[(int64_t)r * D + c] : &t->acc_w[r];
+      if (opt == OPT_SGD) {
+        *theta = (float)((double)*theta - (double)lr * G[c]);
+      } else if (opt == OPT_ADAGRAD) {
+        double a = (double)*acc + G[c] * G[c];
+        *theta = (float)((double)*theta - (double)lr * G[c] / (sqrt(a) + (double)eps));
+        *acc = (float)a;
+      }
+    }
+    ++U;
+    i = j;
+  }
+  free(G); free(bag_of); free(ent);
+  return U;
+}

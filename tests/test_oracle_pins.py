@@ -1,0 +1,404 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Every check here compares the oracle with something that is not the oracle: a brute-force
+double loop written in this file, a closed form, a value printed in the paper, a Python dict,
+or a finite difference.  None of them needs a GPU.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from paper_1909_04823_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------- helpers -------
+def random_batch(rng, B, F, max_len, n_vocab, with_vals=False, min_len=0):
+    lens = rng.integers(min_len, max_len + 1, size=B * F)
+    offsets = np.zeros(B * F + 1, np.int32)
+    offsets[1:] = np.cumsum(lens)
+    vocab = rng.integers(0, 2**63, size=n_vocab, dtype=np.uint64) * np.uint64(2) + np.uint64(1)
+    vocab = np.unique(vocab)
+    keys = vocab[rng.integers(0, vocab.shape[0], size=int(offsets[-1]))]
+    vals = rng.uniform(0.25, 2.0, size=keys.shape[0]).astype(np.float32) if with_vals else None
+    return vocab, keys, offsets, vals
+
+
+def make_table(oracle, rng, vocab, D, scale=0.1):
+    t = oracle.Table(D, capacity=vocab.shape[0] + 8, seed=1)
+    values = (rng.standard_normal((vocab.shape[0], D + 1)) * scale).astype(np.float32)
+    t.insert(vocab, values)
+    return t
+
+
+# --------------------------------------------------------------------------- conventions ---
+def test_mix64_matches_published_splitmix64_stream(oracle):
+    # SplitMix64 seeded with 0 produces these first three outputs (reference values quoted with
+    # the generator's public-domain description); output i is mix64(i * golden-gamma).
+    gamma = 0x9E3779B97F4A7C15
+    expect = [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    for i, e in enumerate(expect, start=1):
+        assert oracle.mix64((i * gamma) & (2**64 - 1)) == e
+
+
+def test_init_value_is_uniform_with_requested_std(oracle):
+    scale = 0.01
+    v = np.array([oracle.init_value(k, c, 77, scale) for k in range(1, 3001) for c in range(5)])
+    half = np.sqrt(3.0) * scale
+    assert v.min() >= -half * (1 + 1e-6) and v.max() < half * (1 + 1e-6)
+    assert abs(v.mean()) < 4 * scale / np.sqrt(v.size)
+    assert abs(v.std() - scale) < 0.02 * scale
+    # columns and keys decorrelate, seed matters, and the function is pure
+    assert oracle.init_value(5, 0, 77, scale) != oracle.init_value(5, 1, 77, scale)
+    assert oracle.init_value(5, 0, 77, scale) != oracle.init_value(5, 0, 78, scale)
+    assert oracle.init_value(5, 0, 77, scale) == oracle.init_value(5, 0, 77, scale)
+    # exact rational form: (u24/2^24 - 1/2) * width rounded once to fp32
+    u24 = oracle.mix64(5 ^ oracle.mix64(77 + 3)) >> 40
+    width = np.float32(2.0 * np.sqrt(3.0) * np.float64(np.float32(scale)))
+    assert np.float32(oracle.init_value(5, 3, 77, scale)) == np.float32((np.float32(u24) / np.float32(2**24) - np.float32(0.5)) * width)
+
+
+def test_shard_policies(oracle):
+    K = 7
+    for f in range(20):
+        assert oracle.shard(12345, f, K, oracle.SHARD_FIELD_MOD) == f % K   # Section 5: i = f mod N
+    counts = np.bincount([oracle.shard(k, 0, K, oracle.SHARD_KEY_HASH) for k in range(1, 7001)], minlength=K)
+    assert counts.min() > 850 and counts.max() < 1150                      # balanced partition (Section 4.2)
+    assert oracle.shard(99, 3, K, oracle.SHARD_KEY_HASH) == oracle.shard(99, 11, K, oracle.SHARD_KEY_HASH)
+    assert oracle.shard(99, 0, K) == (oracle.mix64(99) >> 32) % K
+
+
+# --------------------------------------------------------------------------- hash table ----
+def test_table_against_python_dict(oracle):
+    rng = np.random.default_rng(0)
+    t = oracle.Table(4, capacity=5000, seed=3)
+    ref = {}
+    for call in range(6):
+        if call == 0:      # adversarial: consecutive integers and keys that differ only in high bits
+            keys = np.concatenate([np.arange(0, 300, dtype=np.uint64),
+                                   (np.arange(1, 200, dtype=np.uint64) << np.uint64(40)),
+                                   np.array([2**64 - 2, 2**63, 2**63 - 1], dtype=np.uint64)])
+        else:
+            keys = rng.integers(0, 3000, size=700, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15)
+        keys = keys[rng.permutation(keys.shape[0])]
+        rows = t.insert(keys)
+        new = sorted(set(int(k) for k in keys) - set(ref))          # ascending unsigned order
+        for k in new:
+            ref[k] = len(ref)
+        assert t.n_rows == len(ref)
+        assert [ref[int(k)] for k in keys] == rows.tolist()
+    assert sorted(ref.values()) == list(range(len(ref)))              # bijection onto 0..n-1
+    rk = t.row_keys
+    assert all(rk[r] == k for k, r in ref.items())
+    probe = np.array(list(ref)[:50] + [7_000_001, 7_000_002], dtype=np.uint64)
+    got = t.find(probe)
+    assert got[:50].tolist() == [ref[int(k)] for k in probe[:50]] and got[50:].tolist() == [-1, -1]
+    n0 = t.n_rows
+    t.insert(probe[:50])                                              # idempotent
+    assert t.n_rows == n0
+    got = t.find(probe, insert_missing=True)                          # one call looks up and grows
+    assert got[50:].tolist() == [n0, n0 + 1] and t.n_rows == n0 + 2
+
+
+def test_table_values_first_occurrence_and_init(oracle):
+    t = oracle.Table(2, capacity=16, seed=9, init_scale=0.5)
+    keys = np.array([50, 40, 50, 60], dtype=np.uint64)
+    vals = np.arange(12, dtype=np.float32).reshape(4, 3)
+    rows = t.insert(keys, vals)
+    assert rows.tolist() == [1, 0, 1, 2]
+    np.testing.assert_array_equal(t.emb, [[3, 4], [0, 1], [9, 10]])   # key 50 keeps its first values
+    np.testing.assert_array_equal(t.w, [5, 2, 11])
+    t.insert(np.array([50], dtype=np.uint64), np.full((1, 3), 99, np.float32))
+    np.testing.assert_array_equal(t.w, [5, 2, 11])                    # existing keys untouched
+    r = t.insert(np.array([7], dtype=np.uint64))
+    assert r.tolist() == [3]
+    assert t.emb[3, 1] == np.float32(oracle.init_value(7, 1, 9, 0.5)) and t.w[3] == np.float32(oracle.init_value(7, 2, 9, 0.5))
+    assert not t.acc_emb.any() and not t.acc_w.any()
+
+
+def test_table_errors(oracle):
+    t = oracle.Table(2, capacity=3)
+    with pytest.raises(oracle.OracleError) as e:
+        t.insert(np.array([1, 2, 3, 4], dtype=np.uint64))
+    assert e.value.code == oracle.ERR_FULL and t.n_rows == 0
+    with pytest.raises(oracle.OracleError) as e:
+        t.insert(np.array([1, 2**64 - 1], dtype=np.uint64))
+    assert e.value.code == oracle.ERR_INVALID_KEY
+
+
+# --------------------------------------------------------------------------- forward -------
+def brute_force(t, B, F, keys, offsets, vals):
+    """LR sum, FM order 2 by explicit pairs i<j over the entries of a sample (first line of
+    Eq. (fm_linear)), and per-bag sums, all written as plain loops over a key -> weights dict."""
+    rk, emb, w = t.row_keys, t.emb.astype(np.float64), t.w.astype(np.float64)
+    of = {int(k): i for i, k in enumerate(rk)}
+    D = emb.shape[1]
+    lr = np.zeros(B); fm = np.zeros(B); pool = np.zeros((B, F, D))
+    for b in range(B):
+        terms = []
+        for f in range(F):
+            for e in range(offsets[b * F + f], offsets[b * F + f + 1]):
+                if int(keys[e]) not in of:
+                    continue
+                r = of[int(keys[e])]
+                x = 1.0 if vals is None else float(vals[e])
+                lr[b] += w[r] * x
+                pool[b, f] += emb[r] * x
+                terms.append((emb[r], x))
+        for i in range(len(terms)):
+            for j in range(i + 1, len(terms)):
+                fm[b] += float(terms[i][0] @ terms[j][0]) * terms[i][1] * terms[j][1]
+    return lr, fm, pool
+
+
+@pytest.mark.parametrize("K,policy", [(1, 0), (2, 0), (3, 1), (8, 0), (64, 0), (5, 1)])
+@pytest.mark.parametrize("with_vals", [False, True])
+def test_forward_equals_unsharded_operators(oracle, K, policy, with_vals):
+    """DES equivalence (Algorithm 1): aggregating the K shards' partials and applying F gives
+    the original operators, here computed by brute force; FM identity Eq. (fm_linear)."""
+    rng = np.random.default_rng(10 + K)
+    B, F, D = 7, 4, 6
+    vocab, keys, offsets, vals = random_batch(rng, B, F, 4, 40, with_vals)
+    t = make_table(oracle, rng, vocab[:-3], D)              # three keys stay absent -> row -1
+    rows = t.find(keys)
+    assert (rows < 0).any()
+    P = t.partial_forward(B, F, keys, offsets, rows, K, policy, vals)
+    A_lr, A_sum, A_sq, A_pool = (oracle.aggregate(P[n]) for n in ("P_lr", "P_sum", "P_sq", "P_pool"))
+    fm2 = oracle.fm_finalize(A_sum, A_sq)
+    lr, fm, pool = brute_force(t, B, F, keys, offsets, vals)
+    np.testing.assert_allclose(A_lr, lr, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(fm2, fm, rtol=1e-10, atol=1e-14)
+    np.testing.assert_allclose(A_pool, pool, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(A_sum, pool.sum(axis=1), rtol=1e-12, atol=1e-15)
+    # every entry lands in exactly the shard the policy names
+    for s in range(K):
+        mask = np.array([oracle.shard(int(keys[e]), f, K, policy) == s
+                         for b in range(B) for f in range(F) for e in range(offsets[b * F + f], offsets[b * F + f + 1])])
+        sub_rows = np.where(mask, rows, -1).astype(np.int32)
+        Q = t.partial_forward(B, F, keys, offsets, sub_rows, 1, policy, vals)
+        np.testing.assert_allclose(Q["P_sum"][0], P["P_sum"][s], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(Q["P_lr"][0], P["P_lr"][s], rtol=1e-12, atol=1e-15)
+
+
+def test_forward_closed_forms(oracle):
+    """All-ones weights: lr = n, fm2 = D n (n-1) / 2, pooled = bag length; a single entry has
+    no pair; two entries give <v1,v2>; one key twice in a sample counts as two features."""
+    D, B, F = 8, 5, 3
+    lens = np.array([[1, 0, 0], [1, 1, 0], [2, 3, 4], [0, 0, 0], [300, 200, 100]])
+    offsets = np.zeros(B * F + 1, np.int32); offsets[1:] = np.cumsum(lens.ravel())
+    keys = (np.arange(offsets[-1], dtype=np.uint64) % np.uint64(17)) + np.uint64(100)
+    t = oracle.Table(D, 64)
+    t.insert(np.unique(keys), np.ones((17, D + 1), np.float32))
+    rows = t.find(keys)
+    P = t.partial_forward(B, F, keys, offsets, rows, 4)
+    n = lens.sum(axis=1).astype(np.float64)
+    A_sum = oracle.aggregate(P["P_sum"])
+    np.testing.assert_array_equal(oracle.aggregate(P["P_lr"]), n)
+    np.testing.assert_array_equal(oracle.fm_finalize(A_sum, oracle.aggregate(P["P_sq"])), D * n * (n - 1) / 2)
+    np.testing.assert_array_equal(oracle.aggregate(P["P_pool"]), np.broadcast_to(lens[:, :, None], (B, F, D)))
+    # two entries / the same key twice
+    v = np.array([[1, 2, 3, 0.5], [-1, 0.5, 2, 4]], np.float32)
+    t2 = oracle.Table(3, 4); t2.insert(np.array([5, 9], np.uint64), v)
+    for ks, expect in (([5, 9], float(v[0, :3] @ v[1, :3])), ([9, 9], float(v[1, :3] @ v[1, :3])), ([5], 0.0)):
+        ks = np.array(ks, np.uint64); off = np.array([0, len(ks)], np.int32)
+        Q = t2.partial_forward(1, 1, ks, off, t2.find(ks), 2)
+        got = oracle.fm_finalize(oracle.aggregate(Q["P_sum"]), oracle.aggregate(Q["P_sq"]))[0]
+        assert got == pytest.approx(expect, rel=1e-14, abs=1e-15)
+
+
+def test_partial_sizes_reproduce_printed_comm_saving_table(oracle):
+    """The partial-result shapes (one scalar per sample for LR M1 and FM M2, a D-vector for FM
+    M1) reproduce the paper's printed communication-saving ratios to every digit:
+    R = 1 - 2 S_M / (S_k + S_w) with S_M the bytes one shard contributes for the batch."""
+    d = 8
+    vocab = np.arange(1, 5, dtype=np.uint64)
+    t = oracle.Table(d, 8); t.insert(vocab)
+    for line in open(os.path.join(GOLDEN, "table2_comm_saving.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        B, U, r_lr, r_fm, _ = line.split()
+        B, U = int(B), int(U)
+        keys = np.ones(B, np.uint64); off = np.arange(B + 1, dtype=np.int32)
+        P = t.partial_forward(B, 1, keys, off, t.find(keys), 4, pool=False)
+        s_lr = P["P_lr"][0].size * 4
+        s_fm = (P["P_sum"][0].size + P["P_sq"][0].size) * 4
+        assert f"{100 * (1 - 2 * s_lr / (U * (8 + 4))):.3f}" == r_lr
+        assert f"{100 * (1 - 2 * s_fm / (U * (8 + 4 * d))):.3f}" == r_fm
+
+
+# --------------------------------------------------------------------------- backward ------
+def scalar_objective(oracle, t, B, F, keys, offsets, vals, rows, c_lr, c_fm, c_pool):
+    P = t.partial_forward(B, F, keys, offsets, rows, 3, 0, vals)
+    A_sum = oracle.aggregate(P["P_sum"])
+    fm2 = oracle.fm_finalize(A_sum, oracle.aggregate(P["P_sq"]))
+    return float(c_lr @ oracle.aggregate(P["P_lr"]) + c_fm @ fm2 + (c_pool * oracle.aggregate(P["P_pool"])).sum()), A_sum
+
+
+def test_backward_matches_finite_differences(oracle):
+    """Merged gradients equal central finite differences of the oracle's own forward, including
+    rows that occur in several samples and twice inside one bag, with non-unit feature values."""
+    rng = np.random.default_rng(5)
+    B, F, D = 6, 3, 4
+    vocab, keys, offsets, vals = random_batch(rng, B, F, 3, 12, with_vals=True, min_len=2)
+    keys[1] = keys[0]                                   # same key twice in bag (0,0)
+    t = make_table(oracle, rng, vocab, D, scale=0.5)
+    rows = t.find(keys)
+    c_lr, c_fm = rng.standard_normal(B), rng.standard_normal(B)
+    c_pool = rng.standard_normal((B, F, D))
+    _, A_sum = scalar_objective(oracle, t, B, F, keys, offsets, vals, rows, c_lr, c_fm, c_pool)
+    out = t.backward_update(B, F, offsets, rows, c_lr, c_fm, A_sum, c_pool, oracle.OPT_NONE, vals=vals)
+    assert out["uniq_rows"].tolist() == sorted(set(rows.tolist()))
+    h = 1e-3
+    emb, w = t.emb, t.w
+    for i, r in enumerate(out["uniq_rows"]):
+        for c in range(D + 1):
+            ref = emb[r, c:c + 1] if c < D else w[r:r + 1]
+            old = ref[0]
+            ref[0] = np.float32(old + h); up = float(ref[0]) - float(old)
+            Lp, _ = scalar_objective(oracle, t, B, F, keys, offsets, vals, rows, c_lr, c_fm, c_pool)
+            ref[0] = np.float32(old - h); dn = float(old) - float(ref[0])
+            Lm, _ = scalar_objective(oracle, t, B, F, keys, offsets, vals, rows, c_lr, c_fm, c_pool)
+            ref[0] = old
+            fd = (Lp - Lm) / (up + dn)
+            # the FM value is quadratic in each weight, so the central difference is exact up to rounding
+            assert out["merged"][i, c] == pytest.approx(fd, rel=2e-6, abs=2e-6), (r, c)
+
+
+def test_merge_is_a_reordered_scatter_add(oracle):
+    rng = np.random.default_rng(8)
+    B, F, D = 40, 5, 4
+    vocab, keys, offsets, vals = random_batch(rng, B, F, 6, 30, with_vals=True)
+    t = make_table(oracle, rng, vocab[:-2], D)
+    rows = t.find(keys)
+    g_lr, g_fm = rng.standard_normal(B).astype(np.float32), rng.standard_normal(B).astype(np.float32)
+    g_pool = rng.standard_normal((B, F, D)).astype(np.float32)
+    A_sum = rng.standard_normal((B, D)).astype(np.float32)
+    out = t.backward_update(B, F, offsets, rows, g_lr, g_fm, A_sum, g_pool, oracle.OPT_NONE, vals=vals)
+    # independent evaluation: per-entry gradients with numpy, scatter-added in reverse entry order
+    bag = np.repeat(np.arange(B * F), np.diff(offsets)); b = bag // F
+    x = vals.astype(np.float64)[:, None]
+    live = rows >= 0
+    v = t.emb.astype(np.float64)[np.where(live, rows, 0)]
+    gv = x * (g_fm.astype(np.float64)[b][:, None] * (A_sum.astype(np.float64)[b] - x * v) + g_pool.reshape(B * F, D).astype(np.float64)[bag])
+    gw = x[:, 0] * g_lr.astype(np.float64)[b]
+    G = np.zeros((t.n_rows, D + 1))
+    order = np.flatnonzero(live)[::-1]
+    np.add.at(G, rows[order], np.concatenate([gv, gw[:, None]], axis=1)[order])
+    assert np.all(np.diff(out["uniq_rows"]) > 0)                       # strictly ascending rows
+    assert out["counts"].sum() == live.sum()
+    np.testing.assert_array_equal(out["counts"], np.bincount(rows[live], minlength=t.n_rows)[out["uniq_rows"]])
+    np.testing.assert_array_equal(out["uniq_keys"], t.row_keys[out["uniq_rows"]])
+    np.testing.assert_allclose(out["merged"], G[out["uniq_rows"]], rtol=1e-12, atol=1e-14)
+    untouched = np.setdiff1d(np.arange(t.n_rows), out["uniq_rows"])
+    assert not G[untouched].any()
+    # dropping a term really drops it
+    o2 = t.backward_update(B, F, offsets, rows, g_lr, None, None, None, oracle.OPT_NONE, vals=vals)
+    assert not o2["merged"][:, :D].any()
+    np.testing.assert_allclose(o2["merged"][:, D], G[out["uniq_rows"], D], rtol=1e-12)
+
+
+def test_sgd_and_adagrad_closed_forms(oracle):
+    rng = np.random.default_rng(2)
+    D, B, F = 3, 4, 2
+    keys = np.array([11, 22, 11, 33, 22, 11, 44, 44], np.uint64)
+    offsets = np.arange(B * F + 1, dtype=np.int32)
+    vals0 = (rng.standard_normal((4, D + 1))).astype(np.float32)
+    g_lr = rng.standard_normal(B).astype(np.float32); g_pool = rng.standard_normal((B, F, D)).astype(np.float32)
+
+    def fresh():
+        t = oracle.Table(D, 8); t.insert(np.array([11, 22, 33, 44], np.uint64), vals0)
+        return t, t.find(keys)
+
+    t, rows = fresh()
+    G = t.backward_update(B, F, offsets, rows, g_lr, None, None, g_pool, oracle.OPT_NONE)["merged"]
+    theta0 = np.concatenate([vals0[:, :D], vals0[:, D:]], axis=1).astype(np.float64)
+    # SGD: theta' = theta - lr G
+    t, rows = fresh()
+    t.backward_update(B, F, offsets, rows, g_lr, None, None, g_pool, oracle.OPT_SGD, lr=0.1)
+    got = np.concatenate([t.emb, t.w[:, None]], axis=1)
+    np.testing.assert_array_equal(got, (theta0 - np.float64(np.float32(0.1)) * G).astype(np.float32))
+    assert not t.acc_emb.any()
+    # Adagrad, first step from a zero accumulator: every touched element moves by
+    # lr*G/(|G|+eps), i.e. by lr in the direction of -sign(G); the accumulator becomes G^2
+    t, rows = fresh()
+    lr, eps = np.float32(0.05), np.float32(1e-8)
+    t.backward_update(B, F, offsets, rows, g_lr, None, None, g_pool, oracle.OPT_ADAGRAD, lr=lr, eps=eps)
+    got = np.concatenate([t.emb, t.w[:, None]], axis=1)
+    np.testing.assert_allclose(got, theta0 - float(lr) * np.sign(G), rtol=0, atol=1e-6)
+    np.testing.assert_array_equal(got, (theta0 - float(lr) * G / (np.abs(G) + float(eps))).astype(np.float32))
+    acc1 = np.concatenate([t.acc_emb, t.acc_w[:, None]], axis=1)
+    np.testing.assert_array_equal(acc1, (G * G).astype(np.float32))
+    # second step, hand-computed from the stored fp32 state
+    theta1 = got.astype(np.float64)
+    G2 = t.backward_update(B, F, offsets, rows, g_lr, None, None, g_pool, oracle.OPT_ADAGRAD, lr=lr, eps=eps)["merged"]
+    np.testing.assert_allclose(G2, G, rtol=1e-15)                      # no FM term: gradient independent of weights
+    a2 = acc1.astype(np.float64) + G2 * G2
+    got2 = np.concatenate([t.emb, t.w[:, None]], axis=1)
+    np.testing.assert_array_equal(got2, (theta1 - float(lr) * G2 / (np.sqrt(a2) + float(eps))).astype(np.float32))
+    np.testing.assert_array_equal(np.concatenate([t.acc_emb, t.acc_w[:, None]], axis=1), a2.astype(np.float32))
+
+
+def test_backward_uses_pre_update_weights_and_skips_absent_rows(oracle):
+    D = 2
+    t = oracle.Table(D, 4)
+    t.insert(np.array([1, 2], np.uint64), np.array([[1, 2, 0.5], [3, 4, 0.25]], np.float32))
+    keys = np.array([1, 2, 9, 1], np.uint64)              # one sample, one bag, key 9 absent, key 1 twice
+    offsets = np.array([0, 4], np.int32)
+    rows = t.find(keys)
+    assert rows.tolist() == [0, 1, -1, 0]
+    P = t.partial_forward(1, 1, keys, offsets, rows, 1)
+    A_sum = oracle.aggregate(P["P_sum"]).astype(np.float32)
+    np.testing.assert_array_equal(A_sum, [[5, 8]])
+    out = t.backward_update(1, 1, offsets, rows, np.array([2], np.float32), np.array([3], np.float32), A_sum,
+                            None, oracle.OPT_SGD, lr=1.0)
+    # d fm2 / d v_r = sum over the row's entries of (A_sum - v_r): row 0 occurs twice
+    np.testing.assert_array_equal(out["merged"], [[2 * 3 * (5 - 1), 2 * 3 * (8 - 2), 2 * 2], [3 * (5 - 3), 3 * (8 - 4), 2]])
+    np.testing.assert_array_equal(out["counts"], [2, 1])
+    np.testing.assert_array_equal(t.emb, [[1 - 24, 2 - 36], [3 - 6, 4 - 12]])
+    np.testing.assert_array_equal(t.w, [0.5 - 4, 0.25 - 2])
+    assert t.n_rows == 2
+
+
+# --------------------------------------------------------------------------- generator -----
+def test_generator_shapes_and_determinism():
+    w = synth.workload(1, scale=1 / 64)
+    a, b = synth.gen_batch(w, 3), synth.gen_batch(w, 3)
+    np.testing.assert_array_equal(a.keys, b.keys); np.testing.assert_array_equal(a.offsets, b.offsets)
+    assert a.offsets.shape == (w.B * w.F + 1,) and a.offsets[0] == 0 and a.offsets[-1] == a.nnz
+    lens = np.diff(a.offsets)
+    assert lens.min() >= 1 and lens.max() <= 20 and abs(lens.mean() - 10.5) < 0.5
+    assert not (a.keys == synth.RESERVED_KEY).any()
+    assert not np.array_equal(a.keys[:100], synth.gen_batch(w, 4).keys[:100])
+    # scramblers are bijections on a sample of ranks
+    r = np.arange(1, 200001, dtype=np.uint64)
+    assert np.unique(synth.scramble64(r)).size == r.size
+    k63 = synth.scramble63(r)
+    assert np.unique(k63).size == r.size and k63.max() < 2**63
+    # Poisson bags are max(1, Poisson): mean lam + exp(-lam)
+    w2 = synth.workload(2, scale=1 / 256)
+    lens = np.diff(synth.gen_batch(w2).offsets)
+    assert lens.min() == 1 and abs(lens.mean() - (5 + np.exp(-5))) < 0.1
+    # Zipf head: rank 1 takes about 1/H(n, a) of the draws
+    rng = np.random.default_rng(0)
+    z = synth.zipf_truncated(rng, 1.2, 1000, 200000)
+    assert z.min() == 1 and z.max() <= 1000
+    H = (np.arange(1, 1001) ** -1.2).sum()
+    assert abs((z == 1).mean() - 1 / H) < 0.01
+
+
+def test_streaming_generator_mirrors_row_assignment(oracle):
+    w = synth.workload(3, scale=1 / 512)
+    gen = synth.StreamingGenerator(w)
+    t = oracle.Table(4, w.capacity, seed=1)
+    t.insert(gen.initial_keys())
+    fresh_fraction = []
+    for _ in range(3):
+        n0 = t.n_rows
+        batch = gen.next_batch()
+        rows = t.find(batch.keys, insert_missing=True)
+        assert rows.min() >= 0
+        np.testing.assert_array_equal(t.row_keys, gen.row_keys)      # generator's mirror == table
+        fresh_fraction.append((t.n_rows - n0) / np.unique(batch.keys).size)
+    assert 0.05 < np.mean(fresh_fraction) < 0.6
