@@ -1,0 +1,192 @@
+/*
+ * libdes -- sparse hot path of Distributed Equivalent Substitution (DES) training
+ * (arXiv 1909.04823) for one AMD MI355X (gfx950).  Plain C interface.
+ *
+ * A DES worker owns one shard of the sparse weights of a CTR model and replaces each
+ * weights-rich operator by a sub-operator on its shard whose small result is aggregated
+ * across workers (Algorithm 1).  On one GPU the K workers are K logical partitions of one
+ * table in HBM and the aggregation is an on-device sum over K.
+ *
+ * Conventions for every entry point
+ *   - C linkage, returns des_status_t, never throws.
+ *   - Every pointer named "device" is a device (HBM) pointer owned by the caller; it must
+ *     stay valid until the stream the call was given has drained.  Pointers named "host"
+ *     are ordinary host pointers.  The library allocates no device memory: all storage,
+ *     including scratch, is handed over in des_table_config_t.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
+ *     enqueue work and return, except des_table_create/size/status/destroy and
+ *     des_profile_read, which synchronise.
+ *   - Errors the host can see (null pointers, bad sizes, buffers too small) return at once
+ *     and enqueue nothing.  Errors only the device can see (table full, reserved key) set a
+ *     sticky status word in device memory: des_table_status returns it, and every later
+ *     table-modifying call on that table becomes a no-op.
+ *   - Calls on one table must be ordered (same stream, or externally synchronised); two
+ *     tables are independent.
+ *   - Supported shapes: dim a power of two in [4, 256]; 1 <= num_shards <= 256;
+ *     capacity_rows <= 2^31 - 2; nnz < 2^31; B*F < 2^31.
+ *
+ * Conventions the paper leaves open, fixed here (the CPU oracle implements the same text):
+ *   mix64(z)      finalizer of SplitMix64: z=(z^(z>>30))*0xBF58476D1CE4E5B9;
+ *                 z=(z^(z>>27))*0x94D049BB133111EB; z^(z>>31).
+ *   shard         DES_SHARD_KEY_HASH: (uint32)(mix64(key)>>32) mod K;
+ *                 DES_SHARD_FIELD_MOD: field mod K (Section 5, "i = f mod N").
+ *   row numbers   dense 0..n_rows-1; the distinct unseen keys of one insert/find call get
+ *                 consecutive rows in ascending unsigned key order.
+ *   initialiser   column c of a row inserted without values is
+ *                 ((mix64(key ^ mix64(seed+c)) >> 40) * 2^-24 - 0.5) * (float)(2*sqrt(3)*init_scale)
+ *                 (c < dim latent, c == dim the LR weight); optimizer state starts at 0.
+ *   reserved key  0xFFFFFFFFFFFFFFFF marks an empty slot and is rejected.
+ */
+#ifndef DES_H_
+#define DES_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct des_table des_table_t;   /* opaque host handle */
+
+typedef enum {
+  DES_OK = 0,
+  DES_ERR_INVALID_ARG = 1,   /* null / negative / unsupported shape / misaligned            */
+  DES_ERR_INVALID_KEY = 2,   /* the reserved key was passed (device-detected, sticky)       */
+  DES_ERR_FULL = 3,          /* capacity_rows or the slot array exhausted (sticky)          */
+  DES_ERR_WORKSPACE = 4,     /* slots or workspace smaller than des_table_query_bytes says  */
+  DES_ERR_DEVICE = 5         /* a HIP runtime call failed                                   */
+} des_status_t;
+
+typedef enum { DES_SHARD_KEY_HASH = 0, DES_SHARD_FIELD_MOD = 1 } des_shard_policy_t;
+typedef enum { DES_OPT_NONE = 0, DES_OPT_SGD = 1, DES_OPT_ADAGRAD = 2 } des_opt_t;
+typedef enum { DES_MISS_ZERO = 0, DES_MISS_INSERT = 1 } des_miss_t;
+
+/* Table description.  The caller allocates every buffer (16-byte aligned). */
+typedef struct {
+  int32_t dim;                 /* D, latent dimension                                        */
+  int64_t capacity_rows;       /* the table never rehashes or grows beyond this              */
+  int32_t num_shards;          /* K logical DES workers                                      */
+  int32_t shard_policy;        /* des_shard_policy_t                                         */
+  int32_t opt;                 /* des_opt_t; ADAGRAD requires acc_emb and acc_w              */
+  uint64_t init_seed;
+  float init_scale;            /* standard deviation of the initialiser                      */
+  float *emb;                  /* device [capacity, D]   latent vectors v                    */
+  float *w;                    /* device [capacity]      LR (first-order) weights            */
+  float *acc_emb;              /* device [capacity, D]   Adagrad accumulators (or NULL)      */
+  float *acc_w;                /* device [capacity]                                          */
+  uint64_t *row_keys;          /* device [capacity]      row -> key                          */
+  void *slots;                 /* device, slots_bytes from des_table_query_bytes             */
+  size_t slots_bytes;
+  void *workspace;             /* device scratch for sort / scan / merge                     */
+  size_t workspace_bytes;
+} des_table_config_t;
+
+/* One batch in CSR form (Section 3.2.1: input X; variable-length multi-hot fields).
+ * Bag (b,f) holds entries offsets[b*F+f] .. offsets[b*F+f+1]-1; every entry is one feature
+ * term, also when a key repeats.  vals are the feature values x (NULL: all 1). */
+typedef struct {
+  int64_t B;
+  int32_t F;
+  int64_t nnz;
+  const uint64_t *keys;        /* device [nnz]                                               */
+  const int32_t *offsets;      /* device [B*F+1], offsets[0]=0, offsets[B*F]=nnz             */
+  const float *vals;           /* device [nnz] or NULL                                       */
+} des_batch_t;
+
+/* Bytes needed for `slots` (depends on capacity_rows) and for `workspace` so that calls with
+ * up to max_n keys per insert/find and up to max_n entries per batch fit. */
+des_status_t des_table_query_bytes(const des_table_config_t *cfg, int64_t max_n,
+                                   size_t *slots_bytes, size_t *workspace_bytes);
+
+/* Dynamic hash table, Section 5 "Dynamic Hash Table": lookup, insert of an initialized
+ * weight for a new feature ID (update is des_backward_update_*).
+ * create: validates cfg, empties the slot array (synchronises the null stream). */
+des_status_t des_table_create(const des_table_config_t *cfg, des_table_t **out);
+des_status_t des_table_destroy(des_table_t *t);
+
+/* Insert-if-absent of n keys (device).  values: device [n, D+1] (D latent then LR weight) or
+ * NULL for the initialiser; a repeated new key takes the values of its first occurrence; keys
+ * already present keep their weights.  rows_out: device [n] or NULL.  0 <= n <= max_n. */
+des_status_t des_table_insert(des_table_t *t, const uint64_t *keys, int64_t n,
+                              const float *values, int32_t *rows_out, void *stream);
+
+/* rows_out[i] = row of keys[i]; absent keys give -1 (DES_MISS_ZERO) or are inserted with
+ * initialiser weights first (DES_MISS_INSERT), so one call looks up and grows the table. */
+des_status_t des_table_find(des_table_t *t, const uint64_t *keys, int64_t n, int32_t miss,
+                            int32_t *rows_out, void *stream);
+
+des_status_t des_table_size(des_table_t *t, int64_t *n_rows_host);   /* synchronises */
+des_status_t des_table_status(des_table_t *t);                       /* synchronises; sticky device status */
+
+/* Sub-operators (Algorithm 1: M_j(w_i, x_i) for every shard i), rows from des_table_find.
+ * Entries with row -1 contribute nothing.  Outputs are fully overwritten.
+ *   lr   Eq. (lr_m1), Section 4.1:      P_lr [K,B]     sum of x*w over the shard's entries
+ *   fm   Eq. (fm_m1m2), Section 4.2:    P_sum[K,B,D]   sum of x*v ;  P_sq[K,B] sum of <x*v,x*v>
+ *   pool Section 4.3 (latent vectors aggregated by field before concatenation):
+ *        dense_k=1: P_pool[K,B,F,D] per-shard bag sums;
+ *        dense_k=0: P_pool[B,F,D], the K shards' bag sums already added on chip.
+ * des_partial_forward computes all of them in one pass over the rows (any output NULL to
+ * skip; pool in the dense_k=0 form). */
+des_status_t des_partial_forward_lr(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                    float *P_lr, void *stream);
+des_status_t des_partial_forward_fm(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                    float *P_sum, float *P_sq, void *stream);
+des_status_t des_partial_forward_pool(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                      float *P_pool, int32_t dense_k, void *stream);
+des_status_t des_partial_forward(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                 float *P_lr, float *P_sum, float *P_sq, float *pool, void *stream);
+
+/* Aggregation over the K shards, Eq. (1) with AllReduce-sum: out[i] = sum_s P[s*n + i].
+ * P device [K,n], out device [n]. */
+des_status_t des_aggregate_partials(const float *P, int32_t K, int64_t n, float *out, void *stream);
+
+/* Substitution operator of FM order 2, Eq. (des_fm2): fm2[b] = (<A_sum[b],A_sum[b]> - A_sq[b])/2. */
+des_status_t des_fm_finalize(const float *A_sum, const float *A_sq, int64_t B, int32_t D,
+                             float *fm2, void *stream);
+
+/* Backward (Section 3.2.2, back-propagation phase: the gradient of each aggregate goes
+ * unchanged to every shard's sub-operator; no exchange), duplicate-key merge and optimizer
+ * update (Section 5: "given the gradient of a weight, we apply it locally, and then update").
+ * Entry e of bag (b,f), value x, row r:   d/dw_r = x*g_lr[b]
+ *     d/dv_r = x*( g_fm[b]*(A_sum[b,:] - x*v_r) + g_pool[b,f,:] )
+ * summed over the entries of a row; rows are visited in ascending row order; the update reads
+ * pre-update weights.   SGD: theta -= lr*G.   Adagrad: a += G*G; theta -= lr*G/(sqrt(a)+eps).
+ * Inputs (device; NULL = term absent; g_fm and A_sum go together).  Optional outputs for
+ * inspection (device; NULL to skip, then nothing is materialised): uniq_rows[<=nnz] ascending,
+ * uniq_keys, counts, merged[U, D+1] (D latent then LR weight), n_uniq (int64 scalar). */
+typedef struct {
+  const float *g_lr;       /* [B]       */
+  const float *g_fm;       /* [B]       */
+  const float *A_sum;      /* [B,D]  aggregated FM vector returned by the forward pass */
+  const float *g_pool;     /* [B,F,D]   */
+  int32_t *uniq_rows_out;
+  uint64_t *uniq_keys_out;
+  int32_t *counts_out;
+  float *merged_out;
+  int64_t *n_uniq_out;
+} des_backward_io_t;
+
+des_status_t des_backward_update_sgd(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                     const des_backward_io_t *io, float lr, void *stream);
+des_status_t des_backward_update_adagrad(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                         const des_backward_io_t *io, float lr, float eps, void *stream);
+/* Merge only (no weight changes); fills the optional outputs. */
+des_status_t des_backward_merge(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                const des_backward_io_t *io, void *stream);
+
+/* Per-kernel timing with HIP events recorded on the caller's stream around every launch.
+ * enable != 0 starts collecting and clears earlier records.  des_profile_read synchronises,
+ * then fills up to `max` records (kernel name, launches, total milliseconds) and returns the
+ * number of distinct kernels through n_out.  Names are static strings.  The collector is
+ * process-wide and not thread-safe; it is meant for benchmarks. */
+typedef struct { const char *name; int64_t launches; double total_ms; } des_kernel_time_t;
+des_status_t des_profile_enable(int32_t enable);
+des_status_t des_profile_read(des_kernel_time_t *host_out, int32_t max, int32_t *n_out);
+
+const char *des_status_string(des_status_t s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DES_H_ */

@@ -1,0 +1,522 @@
+// Backward of the sparse operators, duplicate-key merge and fused optimizer update.
+//
+// Section 3.2.2 (back-propagation phase): the gradient of each aggregate is handed unchanged to
+// every shard's sub-operator, so the backward pass needs no exchange.  Section 5: the merged
+// gradient of a weight is applied locally and the table row is updated.
+//
+// Steps: (1) expand the CSR batch to (row, bag) pairs, (2) stable radix sort by row, (3) mark
+// segment heads and compact them (ascending row order), (4) one lane group per short segment
+// reduces its entries in registers and updates the row in the same kernel; segments longer
+// than kChunk entries are cut into chunks that are reduced in parallel and combined by one
+// workgroup per segment, which then updates the row.
+//
+// Per entry e of bag (b,f) with value x:  d/dw += x*g_lr[b],
+//   d/dv += x*(g_fm[b]*A_sum[b,:] + g_pool[b,f,:]) - v * (x*x*g_fm[b])
+// i.e. the row's own vector v enters only through one scalar per segment, so v is read once.
+#include "des_internal.h"
+
+namespace des {
+namespace {
+
+constexpr int kChunk = 32;                 // entries per chunk; segments up to this long are "short"
+constexpr int kHeadItems = 8;
+constexpr int kHeadTile = kBlock * kHeadItems;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+struct BwdArgs {
+  // batch and upstream gradients
+  const int32_t *offsets;
+  const float *vals;
+  const int32_t *rows;
+  const float *g_lr, *g_fm, *A_sum, *g_pool;
+  int64_t n;            // nnz
+  int64_t nbags;
+  int F;
+  uint32_t missing;     // sort key of entries without a row (= capacity, sorts last)
+  // table
+  float *emb, *w, *acc_emb, *acc_w;
+  const uint64_t *row_keys;
+  Ctrl *ctrl;
+  // workspace
+  uint32_t *key_sorted, *pay_sorted;
+  int32_t *bag_of;      // entry -> bag, only with vals
+  int32_t *seg_off;     // [n+1]
+  int32_t *uniq_rows;   // [n]
+  uint32_t *head_sums;
+  int32_t *long_seg;    // [n/kChunk+1]  segment index of long segment j
+  uint32_t *long_c0;    // [n/kChunk+1]  first chunk of long segment j
+  int32_t *chunk_owner; // [2n/kChunk+2] long segment index of chunk c
+  double *partials;     // [2n/kChunk+2][D+4]
+  // optimizer
+  int opt;
+  float lr, eps;
+  // optional outputs
+  int32_t *uniq_rows_out;
+  uint64_t *uniq_keys_out;
+  int32_t *counts_out;
+  float *merged_out;
+  int64_t *n_uniq_out;
+};
+
+__device__ inline float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ inline void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ inline float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ inline float4 f4add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+
+// (1) one thread per bag: sort key = row (or `missing`), payload = bag (or entry index with vals)
+template <bool kHasVals>
+__global__ __launch_bounds__(kBlock) void k_expand(const BwdArgs a, uint32_t *__restrict__ key_out,
+                                                    uint32_t *__restrict__ pay_out) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t bag = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; bag < a.nbags; bag += stride) {
+    const int e0 = a.offsets[bag], e1 = a.offsets[bag + 1];
+    for (int e = e0; e < e1; ++e) {
+      const int r = a.rows[e];
+      key_out[e] = r >= 0 ? (uint32_t)r : a.missing;
+      pay_out[e] = kHasVals ? (uint32_t)e : (uint32_t)bag;
+      if (kHasVals) a.bag_of[e] = (int32_t)bag;
+    }
+  }
+}
+
+// (3) segment heads.  flag(i) = key[i] is a row and differs from key[i-1].
+__device__ inline uint32_t wave_incl_scan_u32(uint32_t v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t o = __shfl_up(v, off, kWave);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
+__device__ inline uint32_t block_excl_scan_u32(uint32_t v, uint32_t *lds, uint32_t &total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const uint32_t inc = wave_incl_scan_u32(v);
+  if (lane == kWave - 1) lds[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    const uint32_t x = lds[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  __syncthreads();
+  total = tot;
+  return base + inc - v;
+}
+
+__global__ __launch_bounds__(kBlock) void k_heads_count(const BwdArgs a) {
+  __shared__ uint32_t lds[kWavesPerBlock];
+  const int64_t base = (int64_t)blockIdx.x * kHeadTile + (int64_t)threadIdx.x * kHeadItems;
+  uint32_t cnt = 0;
+  uint32_t prev = base > 0 && base <= a.n ? a.key_sorted[base - 1] : 0xFFFFFFFFu;
+#pragma unroll
+  for (int i = 0; i < kHeadItems; ++i) {
+    if (base + i < a.n) {
+      const uint32_t k = a.key_sorted[base + i];
+      cnt += (k != a.missing && (base + i == 0 || k != prev)) ? 1u : 0u;
+      prev = k;
+    }
+  }
+  uint32_t total;
+  block_excl_scan_u32(cnt, lds, total);
+  if (threadIdx.x == 0) a.head_sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kBlock) void k_heads_sums(const BwdArgs a, int64_t nb) {
+  __shared__ uint32_t lds[kWavesPerBlock];
+  uint32_t carry = 0;
+  for (int64_t base = 0; base < nb; base += kBlock) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = i < nb ? a.head_sums[i] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_excl_scan_u32(v, lds, total);
+    if (i < nb) a.head_sums[i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    a.ctrl->n_uniq = carry;
+    a.ctrl->n_long = 0;
+    a.ctrl->n_chunks = 0;
+    if (a.n_uniq_out) *a.n_uniq_out = carry;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
+  __shared__ uint32_t lds[kWavesPerBlock];
+  const int64_t base = (int64_t)blockIdx.x * kHeadTile + (int64_t)threadIdx.x * kHeadItems;
+  uint32_t key[kHeadItems];
+  bool flag[kHeadItems];
+  uint32_t cnt = 0;
+  uint32_t prev = base > 0 && base <= a.n ? a.key_sorted[base - 1] : 0xFFFFFFFFu;
+  const uint32_t first_prev = prev;
+#pragma unroll
+  for (int i = 0; i < kHeadItems; ++i) {
+    flag[i] = false;
+    key[i] = a.missing;
+    if (base + i < a.n) {
+      key[i] = a.key_sorted[base + i];
+      flag[i] = key[i] != a.missing && (base + i == 0 || key[i] != prev);
+      cnt += flag[i] ? 1u : 0u;
+      prev = key[i];
+    }
+  }
+  uint32_t total;
+  uint32_t u = a.head_sums[blockIdx.x] + block_excl_scan_u32(cnt, lds, total);
+  prev = first_prev;
+#pragma unroll
+  for (int i = 0; i < kHeadItems; ++i) {
+    const int64_t idx = base + i;
+    if (idx < a.n) {
+      if (flag[i]) {
+        a.uniq_rows[u] = (int32_t)key[i];
+        a.seg_off[u] = (int32_t)idx;
+        ++u;
+      }
+      // end of the last segment: first entry without a row, or the end of the array
+      if (key[i] == a.missing && (idx == 0 || prev != a.missing)) a.seg_off[u] = (int32_t)idx;
+      if (idx == a.n - 1 && key[i] != a.missing) a.seg_off[u] = (int32_t)a.n;
+      prev = key[i];
+    }
+  }
+}
+
+// long segments get a chunk range; the order of the list is irrelevant to the results
+__global__ __launch_bounds__(kBlock) void k_classify(const BwdArgs a) {
+  const long long U = a.ctrl->n_uniq;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < U; u += stride) {
+    const int len = a.seg_off[u + 1] - a.seg_off[u];
+    if (len > kChunk) {
+      const unsigned long long j = atomicAdd(reinterpret_cast<unsigned long long *>(&a.ctrl->n_long), 1ull);
+      const unsigned long long c0 = atomicAdd(reinterpret_cast<unsigned long long *>(&a.ctrl->n_chunks),
+                                              (unsigned long long)((len + kChunk - 1) / kChunk));
+      a.long_seg[j] = (int32_t)u;
+      a.long_c0[j] = (uint32_t)c0;
+    }
+  }
+}
+
+// one workgroup per long segment writes the owner of each of its chunks
+__global__ __launch_bounds__(kBlock) void k_chunk_owner(const BwdArgs a) {
+  const long long NL = a.ctrl->n_long;
+  for (int64_t j = blockIdx.x; j < NL; j += gridDim.x) {
+    const int u = a.long_seg[j];
+    const int nch = (a.seg_off[u + 1] - a.seg_off[u] + kChunk - 1) / kChunk;
+    const uint32_t c0 = a.long_c0[j];
+    for (int i = threadIdx.x; i < nch; i += blockDim.x) a.chunk_owner[c0 + i] = (int32_t)j;
+  }
+}
+
+// Gradient sums of the sorted entries [i0, i1) seen by the lane holding columns 4*sub..4*sub+3:
+//   s1 = sum x*(g_fm[b]*A_sum[b,:] + g_pool[bag,:]),  s2 = sum x*x*g_fm[b],  gw = sum x*g_lr[b]
+// Accumulated in double: the first Adagrad step divides the merged gradient by |G| + eps, so a
+// gradient that cancels to the order of eps must keep an absolute accuracy far below fp32's.
+struct Acc {
+  double v[4];
+  double s2, gw;
+};
+__device__ inline Acc acc_zero() { Acc r; r.v[0] = r.v[1] = r.v[2] = r.v[3] = 0.0; r.s2 = 0.0; r.gw = 0.0; return r; }
+
+template <int D, bool kHasVals>
+__device__ inline void reduce_entries(const BwdArgs &a, int i0, int i1, int sub, Acc &acc) {
+  constexpr int U = 4;
+  for (int i = i0; i < i1; i += U) {
+    uint32_t bag[U];
+    bool live[U];
+    float x[U], gf[U], gl[U];
+    float4 gp[U], as[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      live[k] = i + k < i1;
+      uint32_t p = live[k] ? a.pay_sorted[i + k] : 0u;
+      x[k] = 1.f;
+      if (kHasVals) {
+        if (live[k]) x[k] = a.vals[p];
+        p = live[k] ? (uint32_t)a.bag_of[p] : 0u;
+      }
+      bag[k] = p;
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const uint32_t b = bag[k] / (uint32_t)a.F;
+      gp[k] = (live[k] && a.g_pool) ? ld4(a.g_pool + (int64_t)bag[k] * D + sub * 4) : f4zero();
+      as[k] = (live[k] && a.g_fm) ? ld4(a.A_sum + (int64_t)b * D + sub * 4) : f4zero();
+      gf[k] = (live[k] && a.g_fm) ? a.g_fm[b] : 0.f;
+      gl[k] = (live[k] && a.g_lr) ? a.g_lr[b] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      if (!live[k]) continue;
+      const double xd = (double)x[k];
+      const double xg = xd * (double)gf[k];
+      acc.v[0] += xd * (double)gp[k].x + xg * (double)as[k].x;
+      acc.v[1] += xd * (double)gp[k].y + xg * (double)as[k].y;
+      acc.v[2] += xd * (double)gp[k].z + xg * (double)as[k].z;
+      acc.v[3] += xd * (double)gp[k].w + xg * (double)as[k].w;
+      acc.s2 += xd * xg;
+      acc.gw += xd * (double)gl[k];
+    }
+  }
+}
+
+// Apply the merged gradient of one row.  Lane `sub` owns columns 4*sub..4*sub+3; sub 0 also owns
+// the LR weight.  Reads the pre-update weights.  The merged gradient is formed in double and
+// rounded once; the optimizer arithmetic itself is well conditioned and runs in fp32.
+template <int D>
+__device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, const Acc &acc) {
+  float *vp = a.emb + (int64_t)row * D + sub * 4;
+  const float4 v = ld4(vp);
+  const float4 G = make_float4((float)(acc.v[0] - (double)v.x * acc.s2), (float)(acc.v[1] - (double)v.y * acc.s2),
+                               (float)(acc.v[2] - (double)v.z * acc.s2), (float)(acc.v[3] - (double)v.w * acc.s2));
+  const float gw = (float)acc.gw;
+  if (a.merged_out) {
+    float *m = a.merged_out + u * (D + 1) + sub * 4;
+    m[0] = G.x; m[1] = G.y; m[2] = G.z; m[3] = G.w;
+    if (sub == 0) a.merged_out[u * (D + 1) + D] = gw;
+  }
+  if (a.opt == DES_OPT_SGD) {
+    st4(vp, make_float4(v.x - a.lr * G.x, v.y - a.lr * G.y, v.z - a.lr * G.z, v.w - a.lr * G.w));
+    if (sub == 0) a.w[row] = a.w[row] - a.lr * gw;
+  } else if (a.opt == DES_OPT_ADAGRAD) {
+    float *ap = a.acc_emb + (int64_t)row * D + sub * 4;
+    float4 s = ld4(ap);
+    s.x += G.x * G.x; s.y += G.y * G.y; s.z += G.z * G.z; s.w += G.w * G.w;
+    st4(ap, s);
+    st4(vp, make_float4(v.x - a.lr * G.x / (sqrtf(s.x) + a.eps), v.y - a.lr * G.y / (sqrtf(s.y) + a.eps),
+                        v.z - a.lr * G.z / (sqrtf(s.z) + a.eps), v.w - a.lr * G.w / (sqrtf(s.w) + a.eps)));
+    if (sub == 0) {
+      const float aw = a.acc_w[row] + gw * gw;
+      a.acc_w[row] = aw;
+      a.w[row] = a.w[row] - a.lr * gw / (sqrtf(aw) + a.eps);
+    }
+  }
+}
+
+// (4a) one lane group per segment; long segments are left to the chunked path
+template <int D, bool kHasVals>
+__global__ __launch_bounds__(kBlock) void k_short_update(const BwdArgs a) {
+  constexpr int G = D / 4;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t u = gid / G;
+  const int sub = (int)(gid % G);
+  if (u >= a.ctrl->n_uniq) return;
+  const int i0 = a.seg_off[u], i1 = a.seg_off[u + 1];
+  if (i1 - i0 > kChunk) return;
+  Acc acc = acc_zero();
+  reduce_entries<D, kHasVals>(a, i0, i1, sub, acc);
+  apply_row<D>(a, u, a.uniq_rows[u], sub, acc);
+}
+
+// (4b) one lane group per chunk of a long segment -> partials[c] = (s1[D], s2, gw, 0, 0) in double
+template <int D, bool kHasVals>
+__global__ __launch_bounds__(kBlock) void k_long_partial(const BwdArgs a) {
+  constexpr int G = D / 4;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t c = gid / G;
+  const int sub = (int)(gid % G);
+  if (c >= a.ctrl->n_chunks) return;
+  const int j = a.chunk_owner[c];
+  const int u = a.long_seg[j];
+  const int i0 = a.seg_off[u] + (int)(c - a.long_c0[j]) * kChunk;
+  const int i1 = min(i0 + kChunk, a.seg_off[u + 1]);
+  Acc acc = acc_zero();
+  reduce_entries<D, kHasVals>(a, i0, i1, sub, acc);
+  double *p = a.partials + c * (D + 4);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) p[sub * 4 + k] = acc.v[k];
+  if (sub == 0) { p[D] = acc.s2; p[D + 1] = acc.gw; }
+}
+
+// (4c) one workgroup per long segment: lane groups stride over the chunk partials, an LDS tree
+// combines the groups, group 0 updates the row
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_long_final(const BwdArgs a) {
+  constexpr int G = D / 4;
+  constexpr int NGB = kBlock / G;           // lane groups per workgroup
+  __shared__ double red[NGB][D + 4];
+  const int grp = threadIdx.x / G, sub = threadIdx.x % G;
+  const long long NL = a.ctrl->n_long;
+  for (int64_t j = blockIdx.x; j < NL; j += gridDim.x) {
+    const int u = a.long_seg[j];
+    const int nch = (a.seg_off[u + 1] - a.seg_off[u] + kChunk - 1) / kChunk;
+    const double *p0 = a.partials + (int64_t)a.long_c0[j] * (D + 4);
+    Acc acc = acc_zero();
+    for (int c = grp; c < nch; c += NGB) {
+      const double *p = p0 + (int64_t)c * (D + 4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc.v[k] += p[sub * 4 + k];
+      if (sub == 0) { acc.s2 += p[D]; acc.gw += p[D + 1]; }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) red[grp][sub * 4 + k] = acc.v[k];
+    if (sub == 0) { red[grp][D] = acc.s2; red[grp][D + 1] = acc.gw; }
+    __syncthreads();
+    for (int h = NGB / 2; h >= 1; h >>= 1) {
+      if (grp < h) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) red[grp][sub * 4 + k] += red[grp + h][sub * 4 + k];
+        if (sub == 0) { red[grp][D] += red[grp + h][D]; red[grp][D + 1] += red[grp + h][D + 1]; }
+      }
+      __syncthreads();
+    }
+    if (grp == 0) {
+      Acc tot;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) tot.v[k] = red[0][sub * 4 + k];
+      tot.s2 = red[0][D];
+      tot.gw = red[0][D + 1];
+      apply_row<D>(a, u, a.uniq_rows[u], sub, tot);
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_export(const BwdArgs a) {
+  const long long U = a.ctrl->n_uniq;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < U; u += stride) {
+    const int row = a.uniq_rows[u];
+    if (a.uniq_rows_out) a.uniq_rows_out[u] = row;
+    if (a.uniq_keys_out) a.uniq_keys_out[u] = a.row_keys[row];
+    if (a.counts_out) a.counts_out[u] = a.seg_off[u + 1] - a.seg_off[u];
+  }
+}
+
+__global__ void k_set_i64(int64_t *p, int64_t v) { *p = v; }
+
+inline unsigned blocks_for(int64_t threads, int64_t cap = 1ll << 30) {
+  int64_t g = (threads + kBlock - 1) / kBlock;
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return (unsigned)g;
+}
+
+template <int D, bool kHasVals>
+void launch_update(const BwdArgs &a, hipStream_t s) {
+  constexpr int G = D / 4;
+  const int64_t max_chunks = 2 * (a.n / kChunk) + 2;
+  const int64_t max_long = a.n / kChunk + 1;
+  {
+    ProfScope ps(KID_SHORT_UPDATE, s);
+    hipLaunchKernelGGL((k_short_update<D, kHasVals>), dim3(blocks_for(a.n * G)), dim3(kBlock), 0, s, a);
+  }
+  {
+    ProfScope ps(KID_LONG_PARTIAL, s);
+    hipLaunchKernelGGL((k_long_partial<D, kHasVals>), dim3(blocks_for(max_chunks * G)), dim3(kBlock), 0, s, a);
+  }
+  {
+    ProfScope ps(KID_LONG_FINAL, s);
+    hipLaunchKernelGGL(k_long_final<D>, dim3((unsigned)(max_long < 65536 ? max_long : 65536)), dim3(kBlock), 0, s, a);
+  }
+}
+
+template <int D>
+void launch_update_v(const BwdArgs &a, hipStream_t s) {
+  if (a.vals) launch_update<D, true>(a, s); else launch_update<D, false>(a, s);
+}
+
+struct Layout {
+  size_t key_a, key_b, pay_a, pay_b, bag_of, seg_off, uniq_rows, head_sums, long_seg, long_c0, chunk_owner, partials,
+      sort_scratch, total;
+};
+
+Layout layout_for(int D, int64_t n) {
+  const size_t m = (size_t)(n > 0 ? n : 1);
+  const size_t max_long = m / kChunk + 1, max_chunks = 2 * (m / kChunk) + 2;
+  Layout L;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
+  L.key_a = take(m * 4); L.key_b = take(m * 4); L.pay_a = take(m * 4); L.pay_b = take(m * 4);
+  L.bag_of = take(m * 4);
+  L.seg_off = take((m + 1) * 4); L.uniq_rows = take(m * 4);
+  L.head_sums = take(((m + kHeadTile - 1) / kHeadTile + 1) * 4);
+  L.long_seg = take(max_long * 4); L.long_c0 = take(max_long * 4);
+  L.chunk_owner = take(max_chunks * 4);
+  L.partials = take(max_chunks * (size_t)(D + 4) * 8);
+  L.sort_scratch = take(sort_scratch_bytes(n));
+  L.total = o;
+  return L;
+}
+
+int bits_for(uint64_t max_value) {
+  int b = 1;
+  while (b < 32 && (max_value >> b) != 0) ++b;
+  return b;
+}
+
+}  // namespace
+
+size_t backward_ws_bytes(int D, int64_t max_n) { return layout_for(D, max_n).total; }
+
+des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *rows, const des_backward_io_t *io,
+                             int opt, float lr, float eps, hipStream_t s) {
+  const int64_t n = b->nnz;
+  const int D = t->cfg.dim;
+  if (n == 0) {
+    if (io->n_uniq_out) hipLaunchKernelGGL(k_set_i64, dim3(1), dim3(1), 0, s, io->n_uniq_out, (int64_t)0);
+    return DES_OK;
+  }
+  const Layout L = layout_for(D, n);
+  char *ws = t->ws;
+  BwdArgs a;
+  a.offsets = b->offsets; a.vals = b->vals; a.rows = rows;
+  a.g_lr = io->g_lr; a.g_fm = io->g_fm; a.A_sum = io->A_sum; a.g_pool = io->g_pool;
+  a.n = n; a.nbags = b->B * (int64_t)b->F; a.F = b->F;
+  a.missing = (uint32_t)t->cfg.capacity_rows;
+  a.emb = t->cfg.emb; a.w = t->cfg.w; a.acc_emb = t->cfg.acc_emb; a.acc_w = t->cfg.acc_w;
+  a.row_keys = t->cfg.row_keys; a.ctrl = t->ctrl;
+  a.bag_of = (int32_t *)(ws + L.bag_of);
+  a.seg_off = (int32_t *)(ws + L.seg_off); a.uniq_rows = (int32_t *)(ws + L.uniq_rows);
+  a.head_sums = (uint32_t *)(ws + L.head_sums);
+  a.long_seg = (int32_t *)(ws + L.long_seg); a.long_c0 = (uint32_t *)(ws + L.long_c0);
+  a.chunk_owner = (int32_t *)(ws + L.chunk_owner); a.partials = (double *)(ws + L.partials);
+  a.opt = opt; a.lr = lr; a.eps = eps;
+  a.uniq_rows_out = io->uniq_rows_out; a.uniq_keys_out = io->uniq_keys_out; a.counts_out = io->counts_out;
+  a.merged_out = io->merged_out; a.n_uniq_out = io->n_uniq_out;
+  a.key_sorted = nullptr; a.pay_sorted = nullptr;
+
+  uint32_t *key_a = (uint32_t *)(ws + L.key_a), *key_b = (uint32_t *)(ws + L.key_b);
+  uint32_t *pay_a = (uint32_t *)(ws + L.pay_a), *pay_b = (uint32_t *)(ws + L.pay_b);
+  {
+    ProfScope ps(KID_EXPAND, s);
+    if (a.vals) hipLaunchKernelGGL(k_expand<true>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);
+    else hipLaunchKernelGGL(k_expand<false>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);
+  }
+  SortBuffers sb{key_a, key_b, pay_a, pay_b};
+  const int side = radix_sort_u32_pairs(sb, n, bits_for((uint64_t)t->cfg.capacity_rows), ws + L.sort_scratch, s);
+  a.key_sorted = side ? key_b : key_a;
+  a.pay_sorted = side ? pay_b : pay_a;
+  {
+    ProfScope ps(KID_HEADS, s);
+    const int64_t nb = (n + kHeadTile - 1) / kHeadTile;
+    hipLaunchKernelGGL(k_heads_count, dim3((unsigned)nb), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL(k_heads_sums, dim3(1), dim3(kBlock), 0, s, a, nb);
+    hipLaunchKernelGGL(k_heads_write, dim3((unsigned)nb), dim3(kBlock), 0, s, a);
+  }
+  {
+    ProfScope ps(KID_CLASSIFY, s);
+    hipLaunchKernelGGL(k_classify, dim3(blocks_for(n, 1 << 16)), dim3(kBlock), 0, s, a);
+    const int64_t max_long = n / kChunk + 1;
+    hipLaunchKernelGGL(k_chunk_owner, dim3((unsigned)(max_long < 65536 ? max_long : 65536)), dim3(kBlock), 0, s, a);
+  }
+  switch (D) {
+    case 4: launch_update_v<4>(a, s); break;
+    case 8: launch_update_v<8>(a, s); break;
+    case 16: launch_update_v<16>(a, s); break;
+    case 32: launch_update_v<32>(a, s); break;
+    case 64: launch_update_v<64>(a, s); break;
+    case 128: launch_update_v<128>(a, s); break;
+    case 256: launch_update_v<256>(a, s); break;
+    default: return DES_ERR_INVALID_ARG;
+  }
+  if (io->uniq_rows_out || io->uniq_keys_out || io->counts_out) {
+    ProfScope ps(KID_EXPORT, s);
+    hipLaunchKernelGGL(k_export, dim3(blocks_for(n, 1 << 16)), dim3(kBlock), 0, s, a);
+  }
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+}  // namespace des

@@ -1,0 +1,238 @@
+// Forward sub-operators of every logical shard in one pass over the batch:
+//   LR  M1 (Section 4.1, Eq. lr_m1), FM M1 and M2 (Section 4.2, Eq. fm_m1m2) and the per-field
+//   pooled embeddings (Section 4.3).
+//
+// Mapping: 1, 2 or 4 wave64s per sample.  A row of D floats is read by D/4 adjacent lanes as
+// one 16-byte load each, so a wave holds 64/(D/4) "lane groups" that each fetch a different
+// row at the same time.  Every group owns a contiguous range of the sample's bags, walks its
+// entries in CSR order and keeps the running bag sum in registers (the pooled output is
+// written once per bag, already summed over shards).  The per-shard FM / LR partials of the
+// sample live in LDS ([K][D] + 2 [K] doubles per sample) and are updated with LDS atomics,
+// because the entries of one shard are scattered over all groups.
+//
+// Accumulation is in double, inputs and outputs are fp32: a sample's sum of several hundred
+// signed terms cancels, and fp32 accumulation alone would exceed the 1e-5 relative bound
+// against an exact reference.
+#include "des_internal.h"
+
+namespace des {
+namespace {
+
+struct FwdArgs {
+  const float *emb, *w;
+  const uint64_t *keys;
+  const int32_t *offsets;
+  const float *vals;
+  const int32_t *rows;
+  float *P_lr, *P_sum, *P_sq, *pool;
+  int64_t B;
+  int F, K, policy;
+  int lds_per_sample;   // doubles
+  int wps;              // waves per sample: 1, 2 or 4
+};
+
+__device__ inline float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ inline void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+
+template <int D, int U>
+__global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
+  extern __shared__ __align__(16) double lds[];
+  constexpr int G = D / 4;            // lanes per row
+  constexpr int NG = kWave / G;       // lane groups per wave
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / G, sub = lane % G;
+  const int K = a.K, F = a.F, wps = a.wps;
+  const int local = wave / wps, wis = wave % wps;         // sample slot in the workgroup, wave in sample
+  double *sum = lds + (size_t)local * a.lds_per_sample;   // [K][D]
+  double *sq = sum + (size_t)K * D;                       // [K]
+  double *lrp = sq + K;                                   // [K]
+  const int64_t b = (int64_t)blockIdx.x * (kBlock / kWave / wps) + local;
+  const bool active = b < a.B;
+  const bool need_fm = a.P_sum != nullptr, need_lr = a.P_lr != nullptr, need_pool = a.pool != nullptr;
+  const bool need_v = need_fm || need_pool;
+  const bool by_key = a.policy == DES_SHARD_KEY_HASH;
+  const int tis = wis * kWave + lane, nts = wps * kWave;  // thread in sample, threads per sample
+
+  for (int i = tis; i < a.lds_per_sample; i += nts) sum[i] = 0.0;
+  __syncthreads();
+
+  if (active) {
+    const int32_t *off = a.offsets + b * F;
+    const int gg = wis * NG + g, ngt = wps * NG;
+    const int f0 = (int)(((int64_t)F * gg) / ngt), f1 = (int)(((int64_t)F * (gg + 1)) / ngt);
+    int e = off[f0];
+    const int e1 = off[f1];
+    int f = f0;
+    int bag_end = f < f1 ? off[f + 1] : e1;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    float *pool_row = need_pool ? a.pool + (b * F) * (int64_t)D + sub * 4 : nullptr;
+    while (e < e1) {
+      int r[U];
+      float x[U], wv[U];
+      float4 v[U];
+      int sh[U];
+#pragma unroll
+      for (int i = 0; i < U; ++i) r[i] = (e + i < e1) ? a.rows[e + i] : -1;
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        wv[i] = 0.f;
+        x[i] = 1.f;
+        sh[i] = 0;
+        if (r[i] >= 0) {
+          if (need_v) v[i] = ld4(a.emb + (int64_t)r[i] * D + sub * 4);
+          if (need_lr && sub == 0) wv[i] = a.w[r[i]];
+          if (a.vals) x[i] = a.vals[e + i];
+          if (by_key) sh[i] = (int)((uint32_t)(mix64(a.keys[e + i]) >> 32) % (uint32_t)K);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        const int ee = e + i;
+        if (ee < e1) {
+          while (ee >= bag_end) {                       // close finished (possibly empty) bags
+            if (need_pool)
+              st4(pool_row + (int64_t)f * D, make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
+            acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
+            ++f;
+            bag_end = off[f + 1];
+          }
+          if (r[i] >= 0) {
+            const int s = by_key ? sh[i] : f % K;
+            const double xd = (double)x[i];
+            const double xv[4] = {xd * (double)v[i].x, xd * (double)v[i].y, xd * (double)v[i].z, xd * (double)v[i].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[k] += xv[k];
+            if (need_fm) {
+              double *dst = sum + s * D + sub * 4;
+#pragma unroll
+              for (int k = 0; k < 4; ++k) atomicAdd(dst + k, xv[k]);
+              double q = xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
+#pragma unroll
+              for (int m = G / 2; m >= 1; m >>= 1) q += __shfl_xor(q, m, kWave);
+              if (sub == 0) atomicAdd(sq + s, q);
+            }
+            if (need_lr && sub == 0) atomicAdd(lrp + s, xd * (double)wv[i]);
+          }
+        }
+      }
+      e += U;
+    }
+    while (f < f1) {                                    // last bag of the range and empty ones after it
+      if (need_pool)
+        st4(pool_row + (int64_t)f * D, make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
+      acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
+      ++f;
+    }
+  }
+  __syncthreads();
+
+  if (active) {
+    if (need_fm) {
+      for (int idx = tis * 4; idx < K * D; idx += nts * 4) {
+        const int s = idx / D, d = idx % D;
+        st4(a.P_sum + ((int64_t)s * a.B + b) * D + d,
+            make_float4((float)sum[idx], (float)sum[idx + 1], (float)sum[idx + 2], (float)sum[idx + 3]));
+      }
+      for (int s = tis; s < K; s += nts) a.P_sq[(int64_t)s * a.B + b] = (float)sq[s];
+    }
+    if (need_lr)
+      for (int s = tis; s < K; s += nts) a.P_lr[(int64_t)s * a.B + b] = (float)lrp[s];
+  }
+}
+
+// Per-shard pooled partials [K,B,F,D] (small shapes only): one lane group per bag, one pass
+// over the bag per shard.
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_pool_dense(const FwdArgs a, float *__restrict__ P_pool) {
+  constexpr int G = D / 4;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t bag = gid / G;
+  const int sub = (int)(gid % G);
+  const int64_t nbags = a.B * a.F;
+  if (bag >= nbags) return;
+  const int f = (int)(bag % a.F);
+  const int e0 = a.offsets[bag], e1 = a.offsets[bag + 1];
+  for (int s = 0; s < a.K; ++s) {
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int e = e0; e < e1; ++e) {
+      const int r = a.rows[e];
+      if (r < 0) continue;
+      const int sh = a.policy == DES_SHARD_KEY_HASH ? (int)((uint32_t)(mix64(a.keys[e]) >> 32) % (uint32_t)a.K)
+                                                     : f % a.K;
+      if (sh != s) continue;
+      const double x = a.vals ? (double)a.vals[e] : 1.0;
+      const float4 v = ld4(a.emb + (int64_t)r * D + sub * 4);
+      acc[0] += x * (double)v.x; acc[1] += x * (double)v.y; acc[2] += x * (double)v.z; acc[3] += x * (double)v.w;
+    }
+    st4(P_pool + ((int64_t)s * nbags + bag) * D + sub * 4,
+        make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
+  }
+}
+
+FwdArgs make_args(des_table *t, const des_batch_t *b, const int32_t *rows) {
+  FwdArgs a;
+  a.emb = t->cfg.emb; a.w = t->cfg.w;
+  a.keys = b->keys; a.offsets = b->offsets; a.vals = b->vals; a.rows = rows;
+  a.P_lr = a.P_sum = a.P_sq = a.pool = nullptr;
+  a.B = b->B; a.F = b->F; a.K = t->cfg.num_shards; a.policy = t->cfg.shard_policy;
+  a.lds_per_sample = 0; a.wps = 1;
+  return a;
+}
+
+}  // namespace
+
+des_status_t forward_launch(des_table *t, const des_batch_t *b, const int32_t *rows, float *P_lr, float *P_sum,
+                            float *P_sq, float *pool, hipStream_t s) {
+  if (b->B == 0) return DES_OK;
+  FwdArgs a = make_args(t, b, rows);
+  a.P_lr = P_lr; a.P_sum = P_sum; a.P_sq = P_sq; a.pool = pool;
+  const int D = t->cfg.dim;
+  // LDS per sample: K*(D+2) doubles.  Fewer samples per workgroup (more waves per sample) when
+  // that is large, so that a CU still holds several workgroups.
+  const int64_t per_sample = (int64_t)align_up((size_t)a.K * (D + 2), 2);
+  if (per_sample * 8 > 65536) return DES_ERR_INVALID_ARG;   // num_shards*(dim+2) doubles must fit 64 KB of LDS
+  a.lds_per_sample = (int)per_sample;
+  int wps = 1;
+  while (wps < 4 && (kBlock / kWave / wps) * per_sample * 8 > 40 * 1024) wps *= 2;
+  const int64_t entries_per_sample = b->nnz / (b->B > 0 ? b->B : 1);
+  if (entries_per_sample >= 2048 && wps < 4) wps = 4;       // very long samples: spread over the workgroup
+  a.wps = wps;
+  const int spb = kBlock / kWave / wps;
+  const dim3 grid((unsigned)((b->B + spb - 1) / spb)), block(kBlock);
+  const size_t shmem = (size_t)per_sample * 8 * spb;
+  ProfScope ps(KID_FORWARD, s);
+  switch (D) {
+    case 4: hipLaunchKernelGGL((k_forward<4, 4>), grid, block, shmem, s, a); break;
+    case 8: hipLaunchKernelGGL((k_forward<8, 4>), grid, block, shmem, s, a); break;
+    case 16: hipLaunchKernelGGL((k_forward<16, 4>), grid, block, shmem, s, a); break;
+    case 32: hipLaunchKernelGGL((k_forward<32, 4>), grid, block, shmem, s, a); break;
+    case 64: hipLaunchKernelGGL((k_forward<64, 4>), grid, block, shmem, s, a); break;
+    case 128: hipLaunchKernelGGL((k_forward<128, 4>), grid, block, shmem, s, a); break;
+    case 256: hipLaunchKernelGGL((k_forward<256, 4>), grid, block, shmem, s, a); break;
+    default: return DES_ERR_INVALID_ARG;
+  }
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+des_status_t pool_dense_launch(des_table *t, const des_batch_t *b, const int32_t *rows, float *P_pool, hipStream_t s) {
+  if (b->B == 0) return DES_OK;
+  FwdArgs a = make_args(t, b, rows);
+  const int D = t->cfg.dim;
+  const int64_t threads = b->B * b->F * (D / 4);
+  const dim3 grid((unsigned)((threads + kBlock - 1) / kBlock)), block(kBlock);
+  ProfScope ps(KID_POOL_DENSE, s);
+  switch (D) {
+    case 4: hipLaunchKernelGGL(k_pool_dense<4>, grid, block, 0, s, a, P_pool); break;
+    case 8: hipLaunchKernelGGL(k_pool_dense<8>, grid, block, 0, s, a, P_pool); break;
+    case 16: hipLaunchKernelGGL(k_pool_dense<16>, grid, block, 0, s, a, P_pool); break;
+    case 32: hipLaunchKernelGGL(k_pool_dense<32>, grid, block, 0, s, a, P_pool); break;
+    case 64: hipLaunchKernelGGL(k_pool_dense<64>, grid, block, 0, s, a, P_pool); break;
+    case 128: hipLaunchKernelGGL(k_pool_dense<128>, grid, block, 0, s, a, P_pool); break;
+    case 256: hipLaunchKernelGGL(k_pool_dense<256>, grid, block, 0, s, a, P_pool); break;
+    default: return DES_ERR_INVALID_ARG;
+  }
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+}  // namespace des

@@ -1,0 +1,259 @@
+// Device-wide exclusive scan and stable LSD radix sort for gfx950 (wave64).
+//
+// Both are plain multi-kernel primitives without inter-workgroup waiting: every kernel's
+// workgroups are independent, so every wave reaches its exit whatever the dispatch order.
+#include "des_internal.h"
+
+namespace des {
+
+namespace {
+
+constexpr int kScanItems = 8;                       // items per thread in the scan kernels
+constexpr int kScanTile = kBlock * kScanItems;
+constexpr int kSortItems = 16;                      // items per thread in the sort kernels
+constexpr int kSortTile = kBlock * kSortItems;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+template <typename T>
+__device__ inline T wave_inclusive_scan(T v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    T o = __shfl_up(v, off, kWave);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
+// Exclusive prefix of v over the workgroup (thread order); total = sum over the workgroup.
+template <typename T>
+__device__ inline T block_exclusive_scan(T v, T *lds /*[kWavesPerBlock]*/, T &total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  T inc = wave_inclusive_scan(v);
+  if (lane == kWave - 1) lds[wave] = inc;
+  __syncthreads();
+  T base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    T x = lds[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  __syncthreads();
+  total = tot;
+  return base + inc - v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_scan_reduce(const T *__restrict__ data, int64_t n, T *__restrict__ sums) {
+  __shared__ T lds[kWavesPerBlock];
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  T v = 0;
+#pragma unroll
+  for (int i = 0; i < kScanItems; ++i)
+    if (base + i < n) v += data[base + i];
+  T total;
+  block_exclusive_scan(v, lds, total);
+  if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+// One workgroup scans the per-tile sums in place (exclusive) and stores the grand total.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_scan_sums(T *__restrict__ sums, int64_t nb, T *__restrict__ total_out) {
+  __shared__ T lds[kWavesPerBlock];
+  T carry = 0;
+  for (int64_t base = 0; base < nb; base += kBlock) {
+    const int64_t i = base + threadIdx.x;
+    T v = i < nb ? sums[i] : (T)0;
+    T total;
+    T ex = block_exclusive_scan(v, lds, total);
+    if (i < nb) sums[i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0 && total_out) *total_out = carry;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_scan_apply(T *__restrict__ data, int64_t n, const T *__restrict__ sums) {
+  __shared__ T lds[kWavesPerBlock];
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  T item[kScanItems];
+  T v = 0;
+#pragma unroll
+  for (int i = 0; i < kScanItems; ++i) {
+    item[i] = base + i < n ? data[base + i] : (T)0;
+    v += item[i];
+  }
+  T total;
+  T run = sums[blockIdx.x] + block_exclusive_scan(v, lds, total);
+#pragma unroll
+  for (int i = 0; i < kScanItems; ++i) {
+    if (base + i < n) data[base + i] = run;
+    run += item[i];
+  }
+}
+
+template <typename T>
+void exclusive_scan(T *data, int64_t n, T *total_out, void *scratch, hipStream_t s) {
+  if (n <= 0) return;
+  const int64_t nb = (n + kScanTile - 1) / kScanTile;
+  T *sums = (T *)scratch;
+  hipLaunchKernelGGL(k_scan_reduce<T>, dim3((unsigned)nb), dim3(kBlock), 0, s, data, n, sums);
+  hipLaunchKernelGGL(k_scan_sums<T>, dim3(1), dim3(kBlock), 0, s, sums, nb, total_out);
+  hipLaunchKernelGGL(k_scan_apply<T>, dim3((unsigned)nb), dim3(kBlock), 0, s, data, n, sums);
+}
+
+// ---------------------------------------------------------------------------------------
+// Radix sort.  One workgroup owns a tile of kSortTile consecutive items; wave w owns the w-th
+// quarter of the tile and walks it in rounds of 64, so "wave, round, lane" is item order.
+
+template <typename KeyT>
+__global__ __launch_bounds__(kBlock) void k_radix_hist(const KeyT *__restrict__ keys, int64_t n,
+                                                        const long long *__restrict__ n_dev, int shift, int bits,
+                                                        uint32_t *__restrict__ hist, int nblocks) {
+  __shared__ uint32_t cnt[256];
+  const int64_t n_eff = n_dev ? (int64_t)min((long long)n, *n_dev) : n;
+  cnt[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * kSortTile;
+  const uint32_t mask = (1u << bits) - 1u;
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int64_t idx = base + (int64_t)i * kBlock + threadIdx.x;
+    if (idx < n_eff) atomicAdd(&cnt[(uint32_t)(keys[idx] >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  if (threadIdx.x < (1u << bits)) hist[(size_t)threadIdx.x * nblocks + blockIdx.x] = cnt[threadIdx.x];
+}
+
+template <typename KeyT, bool kHasPayload>
+__global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict__ keys_in,
+                                                           const uint32_t *__restrict__ pay_in,
+                                                           KeyT *__restrict__ keys_out, uint32_t *__restrict__ pay_out,
+                                                           int64_t n, const long long *__restrict__ n_dev, int shift,
+                                                           int bits, const uint32_t *__restrict__ offsets, int nblocks) {
+  __shared__ uint32_t cnt[kWavesPerBlock][256];
+  const int64_t n_eff = n_dev ? (int64_t)min((long long)n, *n_dev) : n;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int64_t tile = (int64_t)blockIdx.x * kSortTile;
+  if (tile >= n_eff) return;                         // uniform per workgroup
+#pragma unroll
+  for (int w = 0; w < kWavesPerBlock; ++w) cnt[w][threadIdx.x] = 0;
+  __syncthreads();
+
+  const uint32_t mask = (1u << bits) - 1u;
+  const unsigned long long lane_lt = (1ull << lane) - 1ull;
+  const int64_t wbase = tile + (int64_t)wave * (kSortItems * kWave);
+  KeyT key[kSortItems];
+  uint32_t pay[kSortItems];
+  uint32_t rank[kSortItems];
+#pragma unroll
+  for (int r = 0; r < kSortItems; ++r) {
+    const int64_t idx = wbase + r * kWave + lane;
+    const bool live = idx < n_eff;
+    key[r] = live ? keys_in[idx] : (KeyT)0;
+    if (kHasPayload) pay[r] = live ? pay_in[idx] : 0u;
+    const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
+    // lanes of this wave holding the same digit
+    unsigned long long peers = __ballot(live);
+    for (int bit = 0; bit < bits; ++bit) {
+      const bool one = (d >> bit) & 1u;
+      const unsigned long long bal = __ballot(one);
+      peers &= one ? bal : ~bal;
+    }
+    const uint32_t before = (uint32_t)__popcll(peers & lane_lt);
+    uint32_t prev = 0;
+    if (live) prev = cnt[wave][d];
+    // every lane has read its counter before the group leaders below overwrite them:
+    // the wave executes the load and the store as two instructions in program order
+    __builtin_amdgcn_wave_barrier();
+    if (live && before == 0) cnt[wave][d] = prev + (uint32_t)__popcll(peers);
+    __builtin_amdgcn_wave_barrier();
+    rank[r] = prev + before;
+  }
+  __syncthreads();
+  // per digit: exclusive prefix over the waves, on top of the tile's global offset
+  if (threadIdx.x < (1u << bits)) {
+    uint32_t run = offsets[(size_t)threadIdx.x * nblocks + blockIdx.x];
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+      const uint32_t c = cnt[w][threadIdx.x];
+      cnt[w][threadIdx.x] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < kSortItems; ++r) {
+    const int64_t idx = wbase + r * kWave + lane;
+    if (idx < n_eff) {
+      const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
+      const uint32_t pos = cnt[wave][d] + rank[r];
+      keys_out[pos] = key[r];
+      if (kHasPayload) pay_out[pos] = pay[r];
+    }
+  }
+}
+
+inline int64_t sort_blocks(int64_t n) { return (n + kSortTile - 1) / kSortTile; }
+
+template <typename KeyT, bool kHasPayload>
+int radix_sort(SortBuffers buf, int64_t n, const long long *n_dev, int bits, void *scratch, hipStream_t s) {
+  if (n <= 0 || bits <= 0) return 0;
+  const int nblocks = (int)sort_blocks(n);
+  uint32_t *hist = (uint32_t *)scratch;
+  void *scan_scratch = (char *)scratch + align_up((size_t)256 * nblocks * sizeof(uint32_t), 256);
+  const int npass = (bits + 7) / 8;
+  const int per = (bits + npass - 1) / npass;
+  KeyT *kin = (KeyT *)buf.keys_a, *kout = (KeyT *)buf.keys_b;
+  uint32_t *pin = buf.pay_a, *pout = buf.pay_b;
+  int side = 0;
+  for (int p = 0; p < npass; ++p) {
+    const int shift = p * per;
+    const int b = (bits - shift) < per ? (bits - shift) : per;
+    {
+      ProfScope ps(KID_SORT_HIST, s);
+      hipLaunchKernelGGL(k_radix_hist<KeyT>, dim3(nblocks), dim3(kBlock), 0, s, kin, n, n_dev, shift, b, hist, nblocks);
+    }
+    {
+      ProfScope ps(KID_SORT_SCAN, s);
+      exclusive_scan<uint32_t>(hist, (int64_t)(1 << b) * nblocks, nullptr, scan_scratch, s);
+    }
+    {
+      ProfScope ps(KID_SORT_SCATTER, s);
+      hipLaunchKernelGGL((k_radix_scatter<KeyT, kHasPayload>), dim3(nblocks), dim3(kBlock), 0, s, kin, pin, kout, pout,
+                         n, n_dev, shift, b, hist, nblocks);
+    }
+    KeyT *tk = kin; kin = kout; kout = tk;
+    uint32_t *tp = pin; pin = pout; pout = tp;
+    side ^= 1;
+  }
+  return side;
+}
+
+}  // namespace
+
+size_t scan_scratch_bytes(int64_t n) {
+  const int64_t nb = (n + kScanTile - 1) / kScanTile;
+  return align_up((size_t)(nb + 1) * sizeof(unsigned long long), 256);
+}
+
+size_t sort_scratch_bytes(int64_t n) {
+  const int64_t nblocks = sort_blocks(n > 0 ? n : 1);
+  return align_up((size_t)256 * nblocks * sizeof(uint32_t), 256) + scan_scratch_bytes(256 * nblocks);
+}
+
+void exclusive_scan_u64(unsigned long long *data, int64_t n, unsigned long long *total_out, void *scratch,
+                        hipStream_t s) {
+  exclusive_scan<unsigned long long>(data, n, total_out, scratch, s);
+}
+
+int radix_sort_u32_pairs(SortBuffers buf, int64_t n, int bits, void *scratch, hipStream_t s) {
+  return radix_sort<uint32_t, true>(buf, n, nullptr, bits, scratch, s);
+}
+
+int radix_sort_u64_keys(SortBuffers buf, int64_t n, const long long *n_dev, void *scratch, hipStream_t s) {
+  return radix_sort<unsigned long long, false>(buf, n, n_dev, 64, scratch, s);
+}
+
+}  // namespace des

@@ -1,0 +1,606 @@
+// Dynamic hash table (Section 5, "Dynamic Hash Table"): open addressing with linear probing
+// over 16-byte slots, 64-bit keys claimed with a compare-and-swap, plus the C entry points
+// that do not belong to the forward or backward files.
+//
+// Row numbers must not depend on which thread wins a slot, so an insert is split in two:
+// claiming a slot (racy, unobservable) and numbering the claimed keys (sort the distinct new
+// keys of the call ascending, row = n_rows + rank).
+#include <math.h>
+#include <string.h>
+#include <new>
+#include <vector>
+#include "des_internal.h"
+
+using namespace des;
+
+namespace {
+
+__device__ inline void set_status(Ctrl *c, int st) { atomicCAS(&c->status, 0, st); }
+
+__device__ inline Slot load_slot(const Slot *p) {
+  const uint4 raw = *reinterpret_cast<const uint4 *>(p);
+  Slot s;
+  s.key = ((uint64_t)raw.y << 32) | raw.x;
+  s.row = (int32_t)raw.z;
+  s.pad = 0;
+  return s;
+}
+
+// Pass A.  rows[e] = row (>= 0), kRowAbsent, or kRowPending for keys claimed in this call.
+template <bool kInsert>
+__global__ __launch_bounds__(kBlock) void k_probe(Slot *__restrict__ slots, uint64_t slot_mask,
+                                                   const uint64_t *__restrict__ keys, int64_t n,
+                                                   int32_t *__restrict__ rows, Ctrl *__restrict__ ctrl,
+                                                   unsigned long long *__restrict__ new_keys) {
+  // after a sticky error the table no longer grows: the call degrades to a pure lookup, so
+  // rows[] is still fully written with valid rows or kRowAbsent
+  const bool can_insert = kInsert && ctrl->status == 0;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) {
+    const uint64_t key = keys[e];
+    int32_t out = kRowAbsent;
+    if (key == kEmptyKey) {
+      set_status(ctrl, DES_ERR_INVALID_KEY);
+      rows[e] = out;
+      continue;
+    }
+    uint64_t idx = mix64(key) & slot_mask;
+    bool done = false;
+    for (uint64_t probe = 0; probe <= slot_mask && !done; ++probe) {
+      const Slot s = load_slot(&slots[idx]);
+      if (s.key == key) {
+        // a negative row under a key is a claim of the running call, or the leftover of a
+        // call that failed: only a call that can insert will resolve it later
+        out = s.row >= 0 ? s.row : (can_insert ? kRowPending : kRowAbsent);
+        done = true;
+      } else if (s.key == kEmptyKey) {
+        if (!can_insert) {
+          done = true;
+        } else {
+          const unsigned long long old =
+              atomicCAS(reinterpret_cast<unsigned long long *>(&slots[idx].key), kEmptyKey, key);
+          if (old == kEmptyKey) {                 // this thread claimed the slot: a new distinct key
+            const unsigned long long pos = atomicAdd(reinterpret_cast<unsigned long long *>(&ctrl->n_new), 1ull);
+            new_keys[pos] = key;
+            out = kRowPending;
+            done = true;
+          } else if (old == key) {                // another thread claimed it for the same key
+            out = kRowPending;
+            done = true;
+          } else {
+            idx = (idx + 1) & slot_mask;          // lost the slot to a different key
+          }
+        }
+      } else {
+        idx = (idx + 1) & slot_mask;
+      }
+    }
+    if (!done) set_status(ctrl, DES_ERR_FULL);     // every slot visited
+    rows[e] = out;
+  }
+}
+
+// Pass C.  Sorted new key i gets row n_rows + i; its slot learns the row.
+__global__ __launch_bounds__(kBlock) void k_assign(Slot *__restrict__ slots, uint64_t slot_mask,
+                                                    const unsigned long long *__restrict__ sorted_keys,
+                                                    Ctrl *__restrict__ ctrl, int64_t capacity,
+                                                    uint64_t *__restrict__ row_keys, int32_t *__restrict__ first_idx) {
+  if (ctrl->status != 0) return;
+  const long long n_new = ctrl->n_new, n_rows = ctrl->n_rows;
+  if (n_rows + n_new > capacity) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) set_status(ctrl, DES_ERR_FULL);
+    return;
+  }
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_new; i += stride) {
+    const uint64_t key = sorted_keys[i];
+    uint64_t idx = mix64(key) & slot_mask;
+    for (uint64_t probe = 0; probe <= slot_mask; ++probe) {
+      if (slots[idx].key == key) { slots[idx].row = (int32_t)(n_rows + i); break; }
+      idx = (idx + 1) & slot_mask;
+    }
+    row_keys[n_rows + i] = key;
+    if (first_idx) first_idx[i] = 0x7FFFFFFF;
+  }
+}
+
+// Rows created by this call get initialiser weights and zero optimizer state.
+// One thread per group of four columns; the group with index D/4 holds the LR weight.
+__global__ __launch_bounds__(kBlock) void k_init_rows(const Ctrl *__restrict__ ctrl, int D, uint64_t seed,
+                                                       float width, const uint64_t *__restrict__ row_keys,
+                                                       float *__restrict__ emb, float *__restrict__ w,
+                                                       float *__restrict__ acc_emb, float *__restrict__ acc_w,
+                                                       int64_t capacity) {
+  if (ctrl->status != 0) return;
+  const long long n_new = ctrl->n_new, n_rows = ctrl->n_rows;
+  if (n_rows + n_new > capacity) return;
+  const int groups = D / 4 + 1;
+  const int64_t total = n_new * groups;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int64_t row = n_rows + i / groups;
+    const int g = (int)(i % groups);
+    const uint64_t key = row_keys[row];
+    if (g < D / 4) {
+      float v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint64_t h = mix64(key ^ mix64(seed + (uint64_t)(g * 4 + k)));
+        const float u = (float)(h >> 40) * (1.0f / 16777216.0f);
+        v[k] = __fmul_rn(__fsub_rn(u, 0.5f), width);
+      }
+      *reinterpret_cast<float4 *>(&emb[row * D + g * 4]) = make_float4(v[0], v[1], v[2], v[3]);
+      if (acc_emb) *reinterpret_cast<float4 *>(&acc_emb[row * D + g * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+      const uint64_t h = mix64(key ^ mix64(seed + (uint64_t)D));
+      const float u = (float)(h >> 40) * (1.0f / 16777216.0f);
+      w[row] = __fmul_rn(__fsub_rn(u, 0.5f), width);
+      if (acc_w) acc_w[row] = 0.f;
+    }
+  }
+}
+
+// Pass D.  Entries that saw a pending key read the row now; with host values every entry of a
+// new key competes for "first occurrence" with an atomic minimum on its index.
+__global__ __launch_bounds__(kBlock) void k_patch(const Slot *__restrict__ slots, uint64_t slot_mask,
+                                                   const uint64_t *__restrict__ keys, int64_t n,
+                                                   int32_t *__restrict__ rows, const Ctrl *__restrict__ ctrl,
+                                                   int32_t *__restrict__ first_idx) {
+  const long long n_rows = ctrl->n_rows;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) {
+    if (rows[e] != kRowPending) continue;
+    const uint64_t key = keys[e];
+    uint64_t idx = mix64(key) & slot_mask;
+    int32_t out = kRowAbsent;
+    for (uint64_t probe = 0; probe <= slot_mask; ++probe) {
+      const Slot s = load_slot(&slots[idx]);
+      if (s.key == key) { out = s.row >= 0 ? s.row : kRowAbsent; break; }
+      if (s.key == kEmptyKey) break;
+      idx = (idx + 1) & slot_mask;
+    }
+    rows[e] = out;
+    if (first_idx && out >= n_rows) atomicMin(&first_idx[out - n_rows], (int32_t)e);
+  }
+}
+
+// Pass E (host values given): new row j copies the values of its first occurrence.
+__global__ __launch_bounds__(kBlock) void k_copy_values(const Ctrl *__restrict__ ctrl, int D,
+                                                         const float *__restrict__ values,
+                                                         const int32_t *__restrict__ first_idx,
+                                                         float *__restrict__ emb, float *__restrict__ w,
+                                                         float *__restrict__ acc_emb, float *__restrict__ acc_w,
+                                                         int64_t capacity) {
+  if (ctrl->status != 0) return;
+  const long long n_new = ctrl->n_new, n_rows = ctrl->n_rows;
+  if (n_rows + n_new > capacity) return;
+  const int cols = D + 1;
+  const int64_t total = n_new * cols;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int64_t j = i / cols;
+    const int c = (int)(i % cols);
+    const int64_t row = n_rows + j;
+    const int32_t src = first_idx[j];
+    const float val = src == 0x7FFFFFFF ? 0.f : values[(int64_t)src * cols + c];
+    if (c < D) {
+      emb[row * D + c] = val;
+      if (acc_emb) acc_emb[row * D + c] = 0.f;
+    } else {
+      w[row] = val;
+      if (acc_w) acc_w[row] = 0.f;
+    }
+  }
+}
+
+__global__ void k_commit(Ctrl *ctrl, int64_t capacity) {
+  if (ctrl->status == 0 && ctrl->n_rows + ctrl->n_new <= capacity) ctrl->n_rows += ctrl->n_new;
+  ctrl->n_new = 0;
+}
+
+__global__ __launch_bounds__(kBlock) void k_fill_u64x2(uint4 *__restrict__ p, int64_t n16, uint4 v) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = v;
+}
+
+__global__ void k_zero_ctrl(Ctrl *ctrl) {
+  ctrl->n_rows = 0; ctrl->n_new = 0; ctrl->n_uniq = 0; ctrl->n_long = 0; ctrl->n_chunks = 0; ctrl->status = 0;
+}
+
+// out[i] = sum over the K shards of P[s*n + i], summed in double and rounded once
+template <bool kVec4>
+__global__ __launch_bounds__(kBlock) void k_aggregate(const float *__restrict__ P, int K, int64_t n,
+                                                       float *__restrict__ out) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  if (kVec4) {
+    const int64_t n4 = n / 4;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+      double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+      for (int s = 0; s < K; ++s) {
+        const float4 p = *reinterpret_cast<const float4 *>(&P[(int64_t)s * n + i * 4]);
+        a0 += (double)p.x; a1 += (double)p.y; a2 += (double)p.z; a3 += (double)p.w;
+      }
+      *reinterpret_cast<float4 *>(&out[i * 4]) = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
+    }
+  } else {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+      double a = 0.0;
+      for (int s = 0; s < K; ++s) a += (double)P[(int64_t)s * n + i];
+      out[i] = (float)a;
+    }
+  }
+}
+
+// fm2[b] = (<A_sum[b], A_sum[b]> - A_sq[b]) / 2, the two reductions in double: the inner
+// product is an order of magnitude larger than the result.  Eight lanes per sample.
+__global__ __launch_bounds__(kBlock) void k_fm_finalize(const float *__restrict__ A_sum,
+                                                         const float *__restrict__ A_sq, int64_t B, int D,
+                                                         float *__restrict__ fm2) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t b = gid / 8;
+  const int sub = (int)(gid % 8);
+  double q = 0.0;
+  if (b < B)
+    for (int d = sub; d < D; d += 8) {
+      const double a = (double)A_sum[b * D + d];
+      q += a * a;
+    }
+  q += __shfl_xor(q, 1, 8);
+  q += __shfl_xor(q, 2, 8);
+  q += __shfl_xor(q, 4, 8);
+  if (b < B && sub == 0) fm2[b] = (float)(0.5 * (q - (double)A_sq[b]));
+}
+
+inline unsigned grid_for(int64_t n, int per_block = kBlock, int64_t cap = 1 << 20) {
+  int64_t g = (n + per_block - 1) / per_block;
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return (unsigned)g;
+}
+
+bool pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+des_status_t validate_cfg(const des_table_config_t *c) {
+  if (!c) return DES_ERR_INVALID_ARG;
+  if (c->dim < 4 || c->dim > 256 || !pow2(c->dim)) return DES_ERR_INVALID_ARG;
+  if (c->capacity_rows < 1 || c->capacity_rows > 2147483646ll) return DES_ERR_INVALID_ARG;
+  if (c->num_shards < 1 || c->num_shards > 256) return DES_ERR_INVALID_ARG;
+  if (c->shard_policy != DES_SHARD_KEY_HASH && c->shard_policy != DES_SHARD_FIELD_MOD) return DES_ERR_INVALID_ARG;
+  if (c->opt != DES_OPT_NONE && c->opt != DES_OPT_SGD && c->opt != DES_OPT_ADAGRAD) return DES_ERR_INVALID_ARG;
+  if (!(c->init_scale >= 0.f)) return DES_ERR_INVALID_ARG;
+  return DES_OK;
+}
+
+uint64_t slots_for(int64_t capacity) {
+  uint64_t want = (uint64_t)capacity + (uint64_t)capacity / 3 + 1;   // load factor <= 0.75
+  uint64_t n = 1024;
+  while (n < want) n <<= 1;
+  return n;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+namespace des {
+
+size_t insert_ws_bytes(int64_t n) {
+  const size_t m = (size_t)(n > 0 ? n : 1);
+  return align_up(m * 4, 256)            // rows when the caller passes none
+         + 2 * align_up(m * 8, 256)      // new keys, two sides of the sort
+         + align_up(m * 4, 256)          // first-occurrence indices
+         + sort_scratch_bytes(n);
+}
+
+// ---- profiler ------------------------------------------------------------------------------
+namespace {
+struct ProfRec { int kid; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+hipEvent_t g_open[KID_COUNT];
+const char *kKernelNames[KID_COUNT] = {
+    "table_probe", "table_assign_rows", "table_patch_rows", "table_copy_values", "table_commit",
+    "forward_gather_pool", "forward_pool_dense", "aggregate_partials", "fm_finalize",
+    "backward_expand", "sort_histogram", "sort_scan", "sort_scatter",
+    "backward_segment_heads", "backward_classify", "backward_short_update", "backward_long_partial",
+    "backward_long_final", "backward_export", "fill"};
+}  // namespace
+
+void prof_begin(int kid, hipStream_t s) {
+  if (!g_prof_on) return;
+  hipEvent_t e;
+  if (hipEventCreate(&e) != hipSuccess) return;
+  (void)hipEventRecord(e, s);
+  g_open[kid] = e;
+}
+
+void prof_end(int kid, hipStream_t s) {
+  if (!g_prof_on || !g_open[kid]) return;
+  hipEvent_t e;
+  if (hipEventCreate(&e) != hipSuccess) return;
+  (void)hipEventRecord(e, s);
+  g_prof.push_back({kid, g_open[kid], e});
+  g_open[kid] = nullptr;
+}
+
+}  // namespace des
+
+extern "C" {
+
+const char *des_status_string(des_status_t s) {
+  switch (s) {
+    case DES_OK: return "ok";
+    case DES_ERR_INVALID_ARG: return "invalid argument";
+    case DES_ERR_INVALID_KEY: return "reserved key passed";
+    case DES_ERR_FULL: return "table full";
+    case DES_ERR_WORKSPACE: return "slots or workspace too small";
+    case DES_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown";
+}
+
+des_status_t des_profile_enable(int32_t enable) {
+  for (auto &r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  g_prof.clear();
+  for (int i = 0; i < KID_COUNT; ++i) g_open[i] = nullptr;
+  g_prof_on = enable != 0;
+  return DES_OK;
+}
+
+des_status_t des_profile_read(des_kernel_time_t *out, int32_t max, int32_t *n_out) {
+  if (!out || !n_out || max < 0) return DES_ERR_INVALID_ARG;
+  if (hipDeviceSynchronize() != hipSuccess) return DES_ERR_DEVICE;
+  double ms[KID_COUNT] = {0};
+  int64_t cnt[KID_COUNT] = {0};
+  for (auto &r : g_prof) {
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) { ms[r.kid] += t; cnt[r.kid]++; }
+  }
+  int k = 0;
+  for (int i = 0; i < KID_COUNT && k < max; ++i)
+    if (cnt[i]) { out[k].name = kKernelNames[i]; out[k].launches = cnt[i]; out[k].total_ms = ms[i]; ++k; }
+  *n_out = k;
+  return DES_OK;
+}
+
+des_status_t des_table_query_bytes(const des_table_config_t *cfg, int64_t max_n, size_t *slots_bytes,
+                                   size_t *workspace_bytes) {
+  des_status_t st = validate_cfg(cfg);
+  if (st != DES_OK) return st;
+  if (max_n < 0 || max_n >= 2147483647ll) return DES_ERR_INVALID_ARG;
+  if (slots_bytes) *slots_bytes = (size_t)slots_for(cfg->capacity_rows) * sizeof(Slot);
+  if (workspace_bytes) {
+    const size_t a = insert_ws_bytes(max_n), b = backward_ws_bytes(cfg->dim, max_n);
+    *workspace_bytes = 256 + (a > b ? a : b);
+  }
+  return DES_OK;
+}
+
+des_status_t des_table_create(const des_table_config_t *cfg, des_table_t **out) {
+  if (!out) return DES_ERR_INVALID_ARG;
+  *out = nullptr;
+  des_status_t st = validate_cfg(cfg);
+  if (st != DES_OK) return st;
+  if (!cfg->emb || !cfg->w || !cfg->row_keys || !cfg->slots || !cfg->workspace) return DES_ERR_INVALID_ARG;
+  if (cfg->opt == DES_OPT_ADAGRAD && (!cfg->acc_emb || !cfg->acc_w)) return DES_ERR_INVALID_ARG;
+  if (!aligned16(cfg->emb) || !aligned16(cfg->slots) || !aligned16(cfg->workspace) ||
+      (cfg->acc_emb && !aligned16(cfg->acc_emb)) || ((uintptr_t)cfg->row_keys & 7u) || ((uintptr_t)cfg->w & 3u))
+    return DES_ERR_INVALID_ARG;
+  const uint64_t n_slots = slots_for(cfg->capacity_rows);
+  if (cfg->slots_bytes < n_slots * sizeof(Slot)) return DES_ERR_WORKSPACE;
+  if (cfg->workspace_bytes < 256 + insert_ws_bytes(1)) return DES_ERR_WORKSPACE;
+  des_table *t = new (std::nothrow) des_table;
+  if (!t) return DES_ERR_DEVICE;
+  t->cfg = *cfg;
+  t->n_slots = n_slots;
+  t->slots = (Slot *)cfg->slots;
+  t->ctrl = (Ctrl *)cfg->workspace;
+  t->ws = (char *)cfg->workspace + 256;
+  t->ws_bytes = cfg->workspace_bytes - 256;
+  t->max_n = 0;
+  t->init_width = (float)(2.0 * sqrt(3.0) * (double)cfg->init_scale);
+  t->last_stream = nullptr;
+  // empty slot = all-ones key, row -1: one 16-byte pattern of 0xFF
+  const uint4 ones = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
+  hipLaunchKernelGGL(k_fill_u64x2, dim3(grid_for((int64_t)n_slots, kBlock, 65536)), dim3(kBlock), 0, nullptr,
+                     (uint4 *)t->slots, (int64_t)n_slots, ones);
+  hipLaunchKernelGGL(k_zero_ctrl, dim3(1), dim3(1), 0, nullptr, t->ctrl);
+  if (hipStreamSynchronize(nullptr) != hipSuccess || hipGetLastError() != hipSuccess) {
+    delete t;
+    return DES_ERR_DEVICE;
+  }
+  *out = t;
+  return DES_OK;
+}
+
+des_status_t des_table_destroy(des_table_t *t) {
+  if (!t) return DES_ERR_INVALID_ARG;
+  (void)hipStreamSynchronize(t->last_stream);
+  delete t;
+  return DES_OK;
+}
+
+static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n, const float *values,
+                                int32_t *rows_out, bool insert, hipStream_t s) {
+  if (!t || n < 0 || n >= 2147483647ll || (n > 0 && !keys)) return DES_ERR_INVALID_ARG;
+  if (((uintptr_t)keys & 7u) || ((uintptr_t)rows_out & 3u) || ((uintptr_t)values & 3u)) return DES_ERR_INVALID_ARG;
+  t->last_stream = s;
+  if (n == 0) return DES_OK;
+  if (insert && insert_ws_bytes(n) > t->ws_bytes) return DES_ERR_WORKSPACE;
+  const uint64_t mask = t->n_slots - 1;
+  if (!insert) {
+    if (!rows_out) return DES_ERR_INVALID_ARG;
+    ProfScope ps(KID_PROBE, s);
+    hipLaunchKernelGGL(k_probe<false>, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows_out,
+                       t->ctrl, (unsigned long long *)nullptr);
+    return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+  }
+  const size_t m = (size_t)n;
+  char *p = t->ws;
+  int32_t *tmp_rows = (int32_t *)p; p += align_up(m * 4, 256);
+  unsigned long long *nk_a = (unsigned long long *)p; p += align_up(m * 8, 256);
+  unsigned long long *nk_b = (unsigned long long *)p; p += align_up(m * 8, 256);
+  int32_t *first_idx = (int32_t *)p; p += align_up(m * 4, 256);
+  void *sort_scratch = p;
+  int32_t *rows = rows_out ? rows_out : tmp_rows;
+  const des_table_config_t &c = t->cfg;
+  {
+    ProfScope ps(KID_PROBE, s);
+    hipLaunchKernelGGL(k_probe<true>, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows, t->ctrl,
+                       nk_a);
+  }
+  SortBuffers sb{nk_a, nk_b, nullptr, nullptr};
+  const int side = radix_sort_u64_keys(sb, n, &t->ctrl->n_new, sort_scratch, s);
+  const unsigned long long *sorted = side ? nk_b : nk_a;
+  {
+    ProfScope ps(KID_ASSIGN, s);
+    hipLaunchKernelGGL(k_assign, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, sorted, t->ctrl,
+                       c.capacity_rows, c.row_keys, values ? first_idx : (int32_t *)nullptr);
+    if (!values)
+      hipLaunchKernelGGL(k_init_rows, dim3(grid_for(n * (c.dim / 4 + 1))), dim3(kBlock), 0, s, t->ctrl, c.dim,
+                         c.init_seed, t->init_width, c.row_keys, c.emb, c.w, c.acc_emb, c.acc_w, c.capacity_rows);
+  }
+  {
+    ProfScope ps(KID_PATCH, s);
+    hipLaunchKernelGGL(k_patch, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows, t->ctrl,
+                       values ? first_idx : (int32_t *)nullptr);
+  }
+  if (values) {
+    ProfScope ps(KID_COPY_VALUES, s);
+    hipLaunchKernelGGL(k_copy_values, dim3(grid_for(n * (c.dim + 1))), dim3(kBlock), 0, s, t->ctrl, c.dim, values,
+                       first_idx, c.emb, c.w, c.acc_emb, c.acc_w, c.capacity_rows);
+  }
+  {
+    ProfScope ps(KID_COMMIT, s);
+    hipLaunchKernelGGL(k_commit, dim3(1), dim3(1), 0, s, t->ctrl, c.capacity_rows);
+  }
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+des_status_t des_table_insert(des_table_t *t, const uint64_t *keys, int64_t n, const float *values,
+                              int32_t *rows_out, void *stream) {
+  return insert_impl(t, keys, n, values, rows_out, true, (hipStream_t)stream);
+}
+
+des_status_t des_table_find(des_table_t *t, const uint64_t *keys, int64_t n, int32_t miss, int32_t *rows_out,
+                            void *stream) {
+  if (miss != DES_MISS_ZERO && miss != DES_MISS_INSERT) return DES_ERR_INVALID_ARG;
+  if (n > 0 && !rows_out) return DES_ERR_INVALID_ARG;
+  return insert_impl(t, keys, n, nullptr, rows_out, miss == DES_MISS_INSERT, (hipStream_t)stream);
+}
+
+des_status_t des_table_size(des_table_t *t, int64_t *n_rows_host) {
+  if (!t || !n_rows_host) return DES_ERR_INVALID_ARG;
+  long long v = 0;
+  if (hipStreamSynchronize(t->last_stream) != hipSuccess) return DES_ERR_DEVICE;
+  if (hipMemcpy(&v, &t->ctrl->n_rows, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return DES_ERR_DEVICE;
+  *n_rows_host = v;
+  return DES_OK;
+}
+
+des_status_t des_table_status(des_table_t *t) {
+  if (!t) return DES_ERR_INVALID_ARG;
+  int v = 0;
+  if (hipStreamSynchronize(t->last_stream) != hipSuccess) return DES_ERR_DEVICE;
+  if (hipMemcpy(&v, &t->ctrl->status, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return DES_ERR_DEVICE;
+  return (des_status_t)v;
+}
+
+des_status_t des_aggregate_partials(const float *P, int32_t K, int64_t n, float *out, void *stream) {
+  if (K < 1 || n < 0 || (n > 0 && (!P || !out))) return DES_ERR_INVALID_ARG;
+  if (((uintptr_t)P & 3u) || ((uintptr_t)out & 3u)) return DES_ERR_INVALID_ARG;
+  if (n == 0) return DES_OK;
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope ps(KID_AGGREGATE, s);
+  const bool vec = (n % 4 == 0) && aligned16(P) && aligned16(out);
+  if (vec)
+    hipLaunchKernelGGL(k_aggregate<true>, dim3(grid_for(n / 4)), dim3(kBlock), 0, s, P, K, n, out);
+  else
+    hipLaunchKernelGGL(k_aggregate<false>, dim3(grid_for(n)), dim3(kBlock), 0, s, P, K, n, out);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+des_status_t des_fm_finalize(const float *A_sum, const float *A_sq, int64_t B, int32_t D, float *fm2, void *stream) {
+  if (B < 0 || D < 1 || (B > 0 && (!A_sum || !A_sq || !fm2))) return DES_ERR_INVALID_ARG;
+  if (B == 0) return DES_OK;
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope ps(KID_FM_FINALIZE, s);
+  hipLaunchKernelGGL(k_fm_finalize, dim3(grid_for(B * 8, kBlock, 1ll << 30)), dim3(kBlock), 0, s, A_sum, A_sq, B, D, fm2);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+static des_status_t check_batch(des_table_t *t, const des_batch_t *b, const int32_t *rows) {
+  if (!t || !b) return DES_ERR_INVALID_ARG;
+  if (b->B < 0 || b->F < 1 || b->nnz < 0 || b->nnz >= 2147483647ll || b->B * (int64_t)b->F >= 2147483647ll)
+    return DES_ERR_INVALID_ARG;
+  if (!b->offsets) return DES_ERR_INVALID_ARG;
+  if (b->nnz > 0 && (!b->keys || !rows)) return DES_ERR_INVALID_ARG;
+  if (((uintptr_t)b->keys & 7u) || ((uintptr_t)b->offsets & 3u) || ((uintptr_t)rows & 3u) || ((uintptr_t)b->vals & 3u))
+    return DES_ERR_INVALID_ARG;
+  return DES_OK;
+}
+
+des_status_t des_partial_forward(des_table_t *t, const des_batch_t *batch, const int32_t *rows, float *P_lr,
+                                 float *P_sum, float *P_sq, float *pool, void *stream) {
+  des_status_t st = check_batch(t, batch, rows);
+  if (st != DES_OK) return st;
+  if ((P_sum == nullptr) != (P_sq == nullptr)) return DES_ERR_INVALID_ARG;
+  if (!P_lr && !P_sum && !pool) return DES_ERR_INVALID_ARG;
+  if ((P_sum && !aligned16(P_sum)) || (pool && !aligned16(pool))) return DES_ERR_INVALID_ARG;
+  t->last_stream = (hipStream_t)stream;
+  return forward_launch(t, batch, rows, P_lr, P_sum, P_sq, pool, (hipStream_t)stream);
+}
+
+des_status_t des_partial_forward_lr(des_table_t *t, const des_batch_t *batch, const int32_t *rows, float *P_lr,
+                                    void *stream) {
+  if (!P_lr) return DES_ERR_INVALID_ARG;
+  return des_partial_forward(t, batch, rows, P_lr, nullptr, nullptr, nullptr, stream);
+}
+
+des_status_t des_partial_forward_fm(des_table_t *t, const des_batch_t *batch, const int32_t *rows, float *P_sum,
+                                    float *P_sq, void *stream) {
+  if (!P_sum || !P_sq) return DES_ERR_INVALID_ARG;
+  return des_partial_forward(t, batch, rows, nullptr, P_sum, P_sq, nullptr, stream);
+}
+
+des_status_t des_partial_forward_pool(des_table_t *t, const des_batch_t *batch, const int32_t *rows, float *P_pool,
+                                      int32_t dense_k, void *stream) {
+  if (!P_pool) return DES_ERR_INVALID_ARG;
+  if (!dense_k) return des_partial_forward(t, batch, rows, nullptr, nullptr, nullptr, P_pool, stream);
+  des_status_t st = check_batch(t, batch, rows);
+  if (st != DES_OK) return st;
+  if (!aligned16(P_pool)) return DES_ERR_INVALID_ARG;
+  t->last_stream = (hipStream_t)stream;
+  return pool_dense_launch(t, batch, rows, P_pool, (hipStream_t)stream);
+}
+
+static des_status_t backward_api(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                 const des_backward_io_t *io, int opt, float lr, float eps, void *stream) {
+  des_status_t st = check_batch(t, batch, rows);
+  if (st != DES_OK) return st;
+  if (!io) return DES_ERR_INVALID_ARG;
+  if ((io->g_fm == nullptr) != (io->A_sum == nullptr)) return DES_ERR_INVALID_ARG;
+  if ((io->A_sum && !aligned16(io->A_sum)) || (io->g_pool && !aligned16(io->g_pool))) return DES_ERR_INVALID_ARG;
+  if (opt == DES_OPT_ADAGRAD && (!t->cfg.acc_emb || !t->cfg.acc_w || !(eps > 0.f))) return DES_ERR_INVALID_ARG;
+  if (opt != DES_OPT_NONE && !(lr == lr)) return DES_ERR_INVALID_ARG;
+  if (256 + backward_ws_bytes(t->cfg.dim, batch->nnz) > t->cfg.workspace_bytes) return DES_ERR_WORKSPACE;
+  t->last_stream = (hipStream_t)stream;
+  return backward_launch(t, batch, rows, io, opt, lr, eps, (hipStream_t)stream);
+}
+
+des_status_t des_backward_update_sgd(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                     const des_backward_io_t *io, float lr, void *stream) {
+  return backward_api(t, batch, rows, io, DES_OPT_SGD, lr, 0.f, stream);
+}
+
+des_status_t des_backward_update_adagrad(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                         const des_backward_io_t *io, float lr, float eps, void *stream) {
+  return backward_api(t, batch, rows, io, DES_OPT_ADAGRAD, lr, eps, stream);
+}
+
+des_status_t des_backward_merge(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                const des_backward_io_t *io, void *stream) {
+  return backward_api(t, batch, rows, io, DES_OPT_NONE, 0.f, 0.f, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,264 @@
+"""ctypes binding of libdes.so: same names as the C interface (include/des.h), argument
+marshalling only.  PyTorch supplies device memory (tensors) and the current HIP stream; every
+step of the path runs in the library's kernels.  Importing this module fails loudly when the
+library has not been built (python -m paper_1909_04823_amd.build)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdes.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1909_04823_amd.build`; "
+                      "there is no fallback path")
+_lib = C.CDLL(LIB_PATH)
+
+OK, ERR_INVALID_ARG, ERR_INVALID_KEY, ERR_FULL, ERR_WORKSPACE, ERR_DEVICE = range(6)
+SHARD_KEY_HASH, SHARD_FIELD_MOD = 0, 1
+OPT_NONE, OPT_SGD, OPT_ADAGRAD = 0, 1, 2
+MISS_ZERO, MISS_INSERT = 0, 1
+
+EXPORTS = [
+    "des_table_query_bytes", "des_table_create", "des_table_destroy", "des_table_insert", "des_table_find",
+    "des_table_size", "des_table_status", "des_partial_forward_lr", "des_partial_forward_fm",
+    "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_fm_finalize",
+    "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_merge", "des_profile_enable",
+    "des_profile_read", "des_status_string",
+]
+
+
+class TableConfig(C.Structure):
+    _fields_ = [("dim", C.c_int32), ("capacity_rows", C.c_int64), ("num_shards", C.c_int32),
+                ("shard_policy", C.c_int32), ("opt", C.c_int32), ("init_seed", C.c_uint64),
+                ("init_scale", C.c_float), ("emb", C.c_void_p), ("w", C.c_void_p), ("acc_emb", C.c_void_p),
+                ("acc_w", C.c_void_p), ("row_keys", C.c_void_p), ("slots", C.c_void_p), ("slots_bytes", C.c_size_t),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class BatchDesc(C.Structure):
+    _fields_ = [("B", C.c_int64), ("F", C.c_int32), ("nnz", C.c_int64), ("keys", C.c_void_p),
+                ("offsets", C.c_void_p), ("vals", C.c_void_p)]
+
+
+class BackwardIO(C.Structure):
+    _fields_ = [("g_lr", C.c_void_p), ("g_fm", C.c_void_p), ("A_sum", C.c_void_p), ("g_pool", C.c_void_p),
+                ("uniq_rows_out", C.c_void_p), ("uniq_keys_out", C.c_void_p), ("counts_out", C.c_void_p),
+                ("merged_out", C.c_void_p), ("n_uniq_out", C.c_void_p)]
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("launches", C.c_int64), ("total_ms", C.c_double)]
+
+
+vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+_sig = {
+    "des_table_query_bytes": [C.POINTER(TableConfig), i64, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)],
+    "des_table_create": [C.POINTER(TableConfig), C.POINTER(vp)],
+    "des_table_destroy": [vp],
+    "des_table_insert": [vp, vp, i64, vp, vp, vp],
+    "des_table_find": [vp, vp, i64, i32, vp, vp],
+    "des_table_size": [vp, C.POINTER(i64)],
+    "des_table_status": [vp],
+    "des_partial_forward_lr": [vp, C.POINTER(BatchDesc), vp, vp, vp],
+    "des_partial_forward_fm": [vp, C.POINTER(BatchDesc), vp, vp, vp, vp],
+    "des_partial_forward_pool": [vp, C.POINTER(BatchDesc), vp, vp, i32, vp],
+    "des_partial_forward": [vp, C.POINTER(BatchDesc), vp, vp, vp, vp, vp, vp],
+    "des_aggregate_partials": [vp, i32, i64, vp, vp],
+    "des_fm_finalize": [vp, vp, i64, i32, vp, vp],
+    "des_backward_update_sgd": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), f32, vp],
+    "des_backward_update_adagrad": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), f32, f32, vp],
+    "des_backward_merge": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), vp],
+    "des_profile_enable": [i32],
+    "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
+}
+for _name, _args in _sig.items():
+    _fn = getattr(_lib, _name)
+    _fn.argtypes = _args
+    _fn.restype = C.c_int
+_lib.des_status_string.argtypes = [C.c_int]
+_lib.des_status_string.restype = C.c_char_p
+
+
+class DesError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = int(code)
+        super().__init__(f"{where}: {_lib.des_status_string(self.code).decode()} (status {self.code})")
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise DesError(code, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Batch:
+    """Device-resident CSR batch (keys int64 tensor holding the uint64 bit patterns)."""
+
+    def __init__(self, B: int, F: int, keys: torch.Tensor, offsets: torch.Tensor, vals: Optional[torch.Tensor] = None):
+        assert keys.dtype == torch.int64 and offsets.dtype == torch.int32
+        assert offsets.numel() == B * F + 1
+        assert vals is None or (vals.dtype == torch.float32 and vals.numel() == keys.numel())
+        self.B, self.F, self.nnz = int(B), int(F), int(keys.numel())
+        self.keys, self.offsets, self.vals = keys, offsets, vals
+        self.desc = BatchDesc(self.B, self.F, self.nnz, _ptr(keys), _ptr(offsets), _ptr(vals))
+
+    @staticmethod
+    def from_numpy(b, device="cuda"):
+        keys = torch.from_numpy(b.keys.view("int64")).to(device)
+        offsets = torch.from_numpy(b.offsets).to(device)
+        vals = None if b.vals is None else torch.from_numpy(b.vals).to(device)
+        return Batch(b.B, b.F, keys, offsets, vals)
+
+
+class Table:
+    """Owns the tensors that back one table and the library handle."""
+
+    def __init__(self, dim: int, capacity: int, num_shards: int = 1, shard_policy: int = SHARD_KEY_HASH,
+                 opt: int = OPT_ADAGRAD, init_seed: int = 0, init_scale: float = 0.01, max_n: int = 1 << 20,
+                 device="cuda"):
+        self.dim, self.capacity, self.K = int(dim), int(capacity), int(num_shards)
+        self.max_n = int(max_n)
+        cfg = TableConfig()
+        cfg.dim, cfg.capacity_rows, cfg.num_shards = self.dim, self.capacity, self.K
+        cfg.shard_policy, cfg.opt, cfg.init_seed, cfg.init_scale = shard_policy, opt, init_seed, init_scale
+        sb, wb = C.c_size_t(0), C.c_size_t(0)
+        _check(_lib.des_table_query_bytes(C.byref(cfg), self.max_n, C.byref(sb), C.byref(wb)), "des_table_query_bytes")
+        dev = torch.device(device)
+        self.emb = torch.empty((self.capacity, self.dim), dtype=torch.float32, device=dev)
+        self.w = torch.empty((self.capacity,), dtype=torch.float32, device=dev)
+        adagrad = opt == OPT_ADAGRAD
+        self.acc_emb = torch.empty((self.capacity, self.dim), dtype=torch.float32, device=dev) if adagrad else None
+        self.acc_w = torch.empty((self.capacity,), dtype=torch.float32, device=dev) if adagrad else None
+        self.row_keys = torch.empty((self.capacity,), dtype=torch.int64, device=dev)
+        self.slots = torch.empty((sb.value,), dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty((wb.value,), dtype=torch.uint8, device=dev)
+        cfg.emb, cfg.w, cfg.acc_emb, cfg.acc_w = _ptr(self.emb), _ptr(self.w), _ptr(self.acc_emb), _ptr(self.acc_w)
+        cfg.row_keys, cfg.slots, cfg.slots_bytes = _ptr(self.row_keys), _ptr(self.slots), sb.value
+        cfg.workspace, cfg.workspace_bytes = _ptr(self.workspace), wb.value
+        self.cfg = cfg
+        torch.cuda.synchronize()
+        h = vp()
+        _check(_lib.des_table_create(C.byref(cfg), C.byref(h)), "des_table_create")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.des_table_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- table ------------------------------------------------------------------------------
+    def insert(self, keys: torch.Tensor, values: Optional[torch.Tensor] = None, rows_out: Optional[torch.Tensor] = None):
+        _check(_lib.des_table_insert(self._h, _ptr(keys), keys.numel(), _ptr(values), _ptr(rows_out), _stream()),
+               "des_table_insert")
+        return rows_out
+
+    def find(self, keys: torch.Tensor, miss: int = MISS_ZERO, rows_out: Optional[torch.Tensor] = None):
+        if rows_out is None:
+            rows_out = torch.empty(keys.numel(), dtype=torch.int32, device=keys.device)
+        _check(_lib.des_table_find(self._h, _ptr(keys), keys.numel(), miss, _ptr(rows_out), _stream()), "des_table_find")
+        return rows_out
+
+    def size(self) -> int:
+        n = i64(0)
+        _check(_lib.des_table_size(self._h, C.byref(n)), "des_table_size")
+        return int(n.value)
+
+    def status(self) -> int:
+        return int(_lib.des_table_status(self._h))
+
+    # ---- forward ----------------------------------------------------------------------------
+    def partial_forward_lr(self, batch: Batch, rows, P_lr):
+        _check(_lib.des_partial_forward_lr(self._h, C.byref(batch.desc), _ptr(rows), _ptr(P_lr), _stream()),
+               "des_partial_forward_lr")
+
+    def partial_forward_fm(self, batch: Batch, rows, P_sum, P_sq):
+        _check(_lib.des_partial_forward_fm(self._h, C.byref(batch.desc), _ptr(rows), _ptr(P_sum), _ptr(P_sq), _stream()),
+               "des_partial_forward_fm")
+
+    def partial_forward_pool(self, batch: Batch, rows, P_pool, dense_k: bool):
+        _check(_lib.des_partial_forward_pool(self._h, C.byref(batch.desc), _ptr(rows), _ptr(P_pool), int(dense_k),
+                                             _stream()), "des_partial_forward_pool")
+
+    def partial_forward(self, batch: Batch, rows, P_lr=None, P_sum=None, P_sq=None, pool=None):
+        _check(_lib.des_partial_forward(self._h, C.byref(batch.desc), _ptr(rows), _ptr(P_lr), _ptr(P_sum), _ptr(P_sq),
+                                        _ptr(pool), _stream()), "des_partial_forward")
+
+    # ---- backward ---------------------------------------------------------------------------
+    def _io(self, g_lr, g_fm, A_sum, g_pool, dbg):
+        io = BackwardIO(_ptr(g_lr), _ptr(g_fm), _ptr(A_sum), _ptr(g_pool), None, None, None, None, None)
+        if dbg:
+            io.uniq_rows_out, io.uniq_keys_out = _ptr(dbg.get("uniq_rows")), _ptr(dbg.get("uniq_keys"))
+            io.counts_out, io.merged_out, io.n_uniq_out = _ptr(dbg.get("counts")), _ptr(dbg.get("merged")), _ptr(dbg.get("n_uniq"))
+        return io
+
+    def backward_update_sgd(self, batch, rows, lr, g_lr=None, g_fm=None, A_sum=None, g_pool=None, dbg=None):
+        io = self._io(g_lr, g_fm, A_sum, g_pool, dbg)
+        _check(_lib.des_backward_update_sgd(self._h, C.byref(batch.desc), _ptr(rows), C.byref(io), lr, _stream()),
+               "des_backward_update_sgd")
+
+    def backward_update_adagrad(self, batch, rows, lr, eps, g_lr=None, g_fm=None, A_sum=None, g_pool=None, dbg=None):
+        io = self._io(g_lr, g_fm, A_sum, g_pool, dbg)
+        _check(_lib.des_backward_update_adagrad(self._h, C.byref(batch.desc), _ptr(rows), C.byref(io), lr, eps,
+                                                _stream()), "des_backward_update_adagrad")
+
+    def backward_merge(self, batch, rows, g_lr=None, g_fm=None, A_sum=None, g_pool=None, dbg=None):
+        io = self._io(g_lr, g_fm, A_sum, g_pool, dbg)
+        _check(_lib.des_backward_merge(self._h, C.byref(batch.desc), _ptr(rows), C.byref(io), _stream()),
+               "des_backward_merge")
+
+    def debug_buffers(self, nnz: int):
+        dev = self.emb.device
+        return {"uniq_rows": torch.empty(nnz, dtype=torch.int32, device=dev),
+                "uniq_keys": torch.empty(nnz, dtype=torch.int64, device=dev),
+                "counts": torch.empty(nnz, dtype=torch.int32, device=dev),
+                "merged": torch.empty((nnz, self.dim + 1), dtype=torch.float32, device=dev),
+                "n_uniq": torch.zeros(1, dtype=torch.int64, device=dev)}
+
+
+def aggregate_partials(P: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    K = P.shape[0]
+    n = P.numel() // K
+    if out is None:
+        out = torch.empty(P.shape[1:], dtype=torch.float32, device=P.device)
+    _check(_lib.des_aggregate_partials(_ptr(P), K, n, _ptr(out), _stream()), "des_aggregate_partials")
+    return out
+
+
+def fm_finalize(A_sum: torch.Tensor, A_sq: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    B, D = A_sum.shape
+    if out is None:
+        out = torch.empty(B, dtype=torch.float32, device=A_sum.device)
+    _check(_lib.des_fm_finalize(_ptr(A_sum), _ptr(A_sq), B, D, _ptr(out), _stream()), "des_fm_finalize")
+    return out
+
+
+def profile_enable(on: bool):
+    _check(_lib.des_profile_enable(int(on)), "des_profile_enable")
+
+
+def profile_read():
+    buf = (KernelTime * 64)()
+    n = i32(0)
+    _check(_lib.des_profile_read(buf, 64, C.byref(n)), "des_profile_read")
+    return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(n.value)}

@@ -1,0 +1,269 @@
+"""GPU parity: the HIP library (through its C interface) against the CPU oracle on the same
+seeded inputs.  Shrunken copies of the five benchmark workloads keep their F, D, K, bag-length
+and popularity laws at a size the oracle finishes in seconds while spanning many tiles, ragged
+tails, long (hot-key) and short merge segments; workloads 0 and 1 also run at full size."""
+import numpy as np
+import pytest
+
+from paper_1909_04823_amd import synth
+from _harness import Pair, assert_close, assert_equal, dev, host_u64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def des():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_1909_04823_amd import des as d
+    return d
+
+
+def opt_code(des, w):
+    return des.OPT_SGD if w.opt == "sgd" else des.OPT_ADAGRAD
+
+
+def build_pair(oracle, des, w, policy=0, K=None, max_n=None):
+    import torch
+    K = w.K if K is None else K
+    nnz_hint = int(w.B * w.F * (w.mean_bag() * 1.3 + 2)) + 1024
+    max_n = max(nnz_hint, w.preinsert + 16) if max_n is None else max_n
+    p = Pair(oracle, des, w.D, w.capacity, K, policy, opt_code(des, w), seed=w.seed, init_scale=w.init_std, max_n=max_n)
+    keys0 = synth.preinsert_keys(w)
+    vals0 = synth.host_values(w, keys0.shape[0]) if w.host_values else None
+    rows_o = p.ot.insert(keys0, vals0)
+    rows_g = torch.empty(keys0.shape[0], dtype=torch.int32, device="cuda")
+    p.gt.insert(dev(keys0, torch), dev(vals0, torch), rows_g)
+    torch.cuda.synchronize()
+    assert_equal(rows_g.cpu().numpy(), rows_o, "pre-insert rows")
+    p.check_table("after pre-insert")
+    p.check_weights("after pre-insert", exact=True)
+    return p
+
+
+def one_step(oracle, des, w, policy=0, K=None, with_vals=False, dense_pool=False, separate_calls=False, steps=1):
+    p = build_pair(oracle, des, w, policy, K)
+    try:
+        for step in range(steps):
+            batch = synth.gen_batch(w, step, with_vals=with_vals)
+            p.find(batch, insert=True)
+            p.check_table(f"step {step} after find")
+            A_sum = p.forward(batch, dense_pool=dense_pool, separate_calls=separate_calls)
+            g_lr, g_fm, g_pool = synth.upstream_gradients(w, step)
+            p.backward(batch, g_lr, g_fm, A_sum, g_pool, lr=w.lr, eps=w.eps if w.eps else 1e-8)
+            p.check_weights(f"step {step} after update")
+    finally:
+        p.close()
+
+
+# ------------------------------------------------------------------------------- table --------
+def test_table_insert_find_adversarial(oracle, des):
+    import torch
+    p = Pair(oracle, des, 8, 6000, 2, 0, des.OPT_ADAGRAD, seed=5, init_scale=0.5, max_n=8192)
+    rng = np.random.default_rng(3)
+    calls = [
+        np.concatenate([np.arange(0, 700, dtype=np.uint64),                        # consecutive integers
+                        np.arange(1, 300, dtype=np.uint64) << np.uint64(40),       # equal low bits
+                        np.array([2**64 - 2, 2**63, 2**63 - 1, 0], dtype=np.uint64)]),
+        rng.integers(0, 2500, size=4000, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15),   # many duplicates
+        rng.integers(0, 2**64 - 1, size=1500, dtype=np.uint64),
+    ]
+    for i, keys in enumerate(calls):
+        keys = keys[rng.permutation(keys.shape[0])]
+        vals = rng.standard_normal((keys.shape[0], 9)).astype(np.float32) if i == 1 else None
+        rows_o = p.ot.insert(keys, vals)
+        rows_g = torch.empty(keys.shape[0], dtype=torch.int32, device="cuda")
+        p.gt.insert(dev(keys, torch), dev(vals, torch), rows_g)
+        torch.cuda.synchronize()
+        assert_equal(rows_g.cpu().numpy(), rows_o, f"call {i} rows")
+        p.check_table(f"call {i}")
+        p.check_weights(f"call {i}", exact=True)          # initialiser and copied values are bit-exact
+    probe = np.concatenate([calls[2][:100], np.array([123456789012345, 42424242424242], dtype=np.uint64)])
+    got = p.gt.find(dev(probe, torch), des.MISS_ZERO).cpu().numpy()
+    assert_equal(got, p.ot.find(probe), "find without insert")
+    assert got[-1] == -1 and got[-2] == -1
+    n0 = p.gt.size()
+    p.gt.insert(dev(calls[0], torch))                      # idempotent, rows_out omitted
+    assert p.gt.size() == n0
+    # empty call
+    p.gt.find(torch.empty(0, dtype=torch.int64, device="cuda"), des.MISS_INSERT)
+    assert p.gt.size() == n0 and p.gt.status() == 0
+    p.close()
+
+
+def test_table_full_and_reserved_key_are_sticky_errors(oracle, des):
+    import torch
+    p = Pair(oracle, des, 4, 100, 1, 0, des.OPT_SGD, max_n=4096)
+    ok = np.arange(1, 91, dtype=np.uint64)
+    p.gt.insert(dev(ok, torch))
+    assert p.gt.size() == 90 and p.gt.status() == 0
+    too_many = np.arange(1000, 1020, dtype=np.uint64)
+    rows = p.gt.find(dev(too_many, torch), des.MISS_INSERT)
+    assert p.gt.status() == des.ERR_FULL
+    assert p.gt.size() == 90                                   # nothing was added
+    assert (rows.cpu().numpy() == -1).all()
+    # the table still answers lookups and refuses to grow
+    assert_equal(p.gt.find(dev(ok, torch), des.MISS_ZERO).cpu().numpy(), np.arange(90, dtype=np.int32), "lookup after error")
+    rows = p.gt.find(dev(np.array([5, 777777], dtype=np.uint64), torch), des.MISS_INSERT).cpu().numpy()
+    assert rows.tolist() == [4, -1] and p.gt.size() == 90
+    p.close()
+    q = Pair(oracle, des, 4, 100, 1, 0, des.OPT_SGD, max_n=4096)
+    rows = q.gt.find(dev(np.array([7, 2**64 - 1, 9], dtype=np.uint64), torch), des.MISS_INSERT).cpu().numpy()
+    assert q.gt.status() == des.ERR_INVALID_KEY and rows[1] == -1
+    q.close()
+
+
+# ------------------------------------------------------------------------------- workloads ----
+def test_workload0_full_size_with_loss_head(oracle, des):
+    """Tiny LR+FM at its full size: forward, the harness loss head (sigmoid + mean log-loss on
+    Bernoulli(0.2) labels), SGD step; then a second step to check the updated weights are used."""
+    import torch
+    w = synth.workload(0)
+    p = build_pair(oracle, des, w)
+    head = synth.head_weights(w).astype(np.float64)
+    for step in range(2):
+        batch = synth.gen_batch(w, step)
+        p.find(batch)
+        A_sum = p.forward(batch, dense_pool=True, separate_calls=(step == 1))
+        logit = p.fwd["A_lr"] + p.fwd["fm2"] + (p.fwd["pool"] * head).sum(axis=(1, 2))
+        g_logit = ((1 / (1 + np.exp(-logit)) - batch.labels) / w.B)
+        g_lr = g_fm = g_logit.astype(np.float32)
+        g_pool = (g_logit[:, None, None] * head).astype(np.float32)
+        p.backward(batch, g_lr, g_fm, A_sum, g_pool, lr=w.lr, opt=des.OPT_SGD)
+        p.check_weights(f"step {step}")
+    p.close()
+
+
+def test_workload1_full_size(oracle, des):
+    one_step(oracle, des, synth.workload(1), dense_pool=True, steps=2)
+
+
+@pytest.mark.parametrize("index,scale", [(1, 1 / 16), (2, 1 / 64), (3, 1 / 128), (4, 1 / 512)])
+def test_shrunken_workloads(oracle, des, index, scale):
+    w = synth.workload(index, scale=scale)
+    if w.p_new:
+        return streaming(oracle, des, w, steps=4)
+    one_step(oracle, des, w, steps=2)
+
+
+def streaming(oracle, des, w, steps):
+    """Streaming workload: every step looks up, inserts the unseen IDs, runs forward, backward and
+    the Adagrad update on a growing table."""
+    import torch
+    gen = synth.StreamingGenerator(w)
+    nnz_hint = int(w.B * w.F * (w.mean_bag() * 1.3 + 2)) + 1024
+    p = Pair(oracle, des, w.D, w.capacity, w.K, 0, des.OPT_ADAGRAD, seed=w.seed, init_scale=w.init_std,
+             max_n=max(nnz_hint, w.preinsert))
+    keys0 = gen.initial_keys()
+    p.ot.insert(keys0)
+    p.gt.insert(dev(keys0, torch))
+    p.check_table("initial")
+    p.check_weights("initial", exact=True)
+    for step in range(steps):
+        n0 = p.ot.n_rows
+        batch = gen.next_batch()
+        p.find(batch, insert=True)
+        assert p.check_table(f"step {step}") > n0
+        A_sum = p.forward(batch)
+        g_lr, g_fm, g_pool = synth.upstream_gradients(w, step)
+        p.backward(batch, g_lr, g_fm, A_sum, g_pool, lr=w.lr, eps=w.eps)
+        p.check_weights(f"step {step}")
+    p.close()
+
+
+@pytest.mark.parametrize("D,K,policy,with_vals", [(4, 1, 0, False), (8, 3, 0, True), (16, 7, 1, True),
+                                                    (32, 16, 1, False), (128, 5, 0, True), (256, 2, 0, False)])
+def test_shapes_policies_and_feature_values(oracle, des, D, K, policy, with_vals):
+    """Every supported row width, odd shard counts, both partitions, non-unit feature values,
+    dense pooled partials and the three separate forward calls."""
+    w = synth.workload(1, scale=1 / 64, D=D, K=K)
+    one_step(oracle, des, w, policy=policy, with_vals=with_vals, dense_pool=True, separate_calls=True)
+
+
+def test_absent_keys_and_empty_bags(oracle, des):
+    """Lookup without insert leaves rows at -1: they add nothing forward and get no gradient;
+    bags may be empty; an all-absent batch merges to nothing."""
+    import torch
+    w = synth.workload(1, scale=1 / 64, bag=("uniform", 0, 3))
+    p = build_pair(oracle, des, w)
+    batch = synth.gen_batch(w, 0)
+    rows = p.find(batch, insert=False)
+    assert (rows < 0).any() and (np.diff(batch.offsets) == 0).any()
+    A_sum = p.forward(batch)
+    g_lr, g_fm, g_pool = synth.upstream_gradients(w, 0)
+    p.backward(batch, g_lr, g_fm, A_sum, g_pool, lr=w.lr, eps=w.eps)
+    p.check_weights("absent rows")
+    n_before = p.gt.size()
+    # all keys absent
+    batch.keys = (np.arange(batch.nnz, dtype=np.uint64) + np.uint64(1)) * np.uint64(0x1234567)
+    rows = p.find(batch, insert=False)
+    assert (rows < 0).all()
+    p.forward(batch)
+    ref = p.backward(batch, g_lr, g_fm, A_sum, g_pool, lr=w.lr, eps=w.eps)
+    assert ref["uniq_rows"].size == 0 and p.gt.size() == n_before
+    p.check_weights("all absent")
+    p.close()
+
+
+def test_terms_can_be_dropped_and_merge_only(oracle, des):
+    w = synth.workload(2, scale=1 / 256)
+    p = build_pair(oracle, des, w)
+    batch = synth.gen_batch(w, 0)
+    p.find(batch)
+    A_sum = p.forward(batch)
+    g_lr, g_fm, g_pool = synth.upstream_gradients(w, 0)
+    before = p.gt.emb.clone()
+    p.backward(batch, g_lr, g_fm, A_sum, g_pool, opt=des.OPT_NONE)        # merge only: nothing changes
+    assert (p.gt.emb == before).all()
+    p.backward(batch, g_lr, None, None, None, lr=w.lr, eps=w.eps)         # LR term only
+    p.check_weights("lr only")
+    p.backward(batch, None, g_fm, A_sum, None, lr=w.lr, eps=w.eps)        # FM term only
+    p.check_weights("fm only")
+    p.backward(batch, None, None, None, g_pool, lr=w.lr, eps=w.eps)       # pooling term only
+    p.check_weights("pool only")
+    p.close()
+
+
+def test_integers_are_deterministic_run_to_run(oracle, des):
+    import torch
+    w = synth.workload(3, scale=1 / 128)
+    snaps = []
+    for _ in range(2):
+        gen = synth.StreamingGenerator(w)
+        t = des.Table(w.D, w.capacity, w.K, 0, des.OPT_ADAGRAD, w.seed, w.init_std, max_n=1 << 18)
+        t.insert(dev(gen.initial_keys(), torch))
+        out = []
+        for step in range(2):
+            b = des.Batch.from_numpy(gen.next_batch())
+            rows = t.find(b.keys, des.MISS_INSERT)
+            dbg = t.debug_buffers(b.nnz)
+            g_lr, g_fm, g_pool = synth.upstream_gradients(w, step)
+            t.backward_merge(b, rows, g_lr=dev(g_lr, torch), g_pool=dev(g_pool, torch), dbg=dbg)
+            U = int(dbg["n_uniq"].item())
+            out += [rows.cpu().numpy(), dbg["uniq_rows"][:U].cpu().numpy(), dbg["counts"][:U].cpu().numpy(),
+                    dbg["merged"][:U].cpu().numpy()]
+        n = t.size()
+        out.append(host_u64(t.row_keys[:n]))
+        snaps.append(out)
+        t.close()
+    for a, b in zip(*snaps):
+        assert_equal(a, b, "run-to-run")
+
+
+def test_host_side_argument_checks(des):
+    import ctypes as C
+    import torch
+    cfg = des.TableConfig()
+    cfg.dim, cfg.capacity_rows, cfg.num_shards = 12, 100, 2           # dim not a power of two
+    sb, wb = C.c_size_t(), C.c_size_t()
+    assert des._lib.des_table_query_bytes(C.byref(cfg), 10, C.byref(sb), C.byref(wb)) == des.ERR_INVALID_ARG
+    t = des.Table(8, 1000, 2, max_n=1000)
+    keys = torch.arange(1, 5001, dtype=torch.int64, device="cuda")
+    with pytest.raises(des.DesError) as e:                            # more keys than the workspace was sized for
+        t.find(keys, des.MISS_INSERT)
+    assert e.value.code == des.ERR_WORKSPACE
+    with pytest.raises(des.DesError) as e:
+        des._check(des._lib.des_table_find(t._h, None, 5, 0, None, None), "find")
+    assert e.value.code == des.ERR_INVALID_ARG
+    assert t.status() == 0 and t.size() == 0
+    t.close()
