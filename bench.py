@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Throughput of the DES sparse forward+backward step on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch that is already resident in
+HBM: des_table_find (inserting unseen IDs where the workload grows) -> des_partial_forward
+(LR, FM, pooled partials of all K shards) -> des_aggregate_partials x3 + des_fm_finalize ->
+des_backward_update_{adagrad,sgd} (sort by row, duplicate merge, fused row update).  Upstream
+gradients are seeded random tensors of the real shapes (the loss head is outside the path).
+
+Prints ONE JSON line.  `value` = lookups (CSR entries) per second; samples/s is alongside.
+The roofline object is for the kernel with the largest share of the step, timed with HIP
+events on the launch stream in a second pass over the same steps; the CPU baseline is the
+oracle, single-threaded, on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def batch_stats(keys: np.ndarray, chunk: int = 32):
+    """Input statistics the byte model needs: distinct keys and how the entries split into
+    short (<= chunk occurrences) and long merge segments."""
+    _, counts = np.unique(keys, return_counts=True)
+    long_ = counts > chunk
+    return {
+        "U": int(counts.size), "U_long": int(long_.sum()), "U_short": int((~long_).sum()),
+        "n_long": int(counts[long_].sum()), "n_short": int(counts[~long_].sum()),
+        "n_chunks": int(((counts[long_] + chunk - 1) // chunk).sum()),
+    }
+
+
+def algorithmic_bytes(w, nnz, st, sort_passes, state_mult):
+    """Compulsory bytes per step of each kernel (what the method itself has to move)."""
+    B, F, D, K = w.B, w.F, w.D, w.K
+    R = D + 1
+    n, U = nnz, st["U"]
+    gp = 4.0 * B * F * D                      # g_pool, each bag row once
+    return {
+        "table_probe": 8 * n + 4 * n + 16 * U,
+        "forward_gather_pool": 8 * n + 4 * n + 4 * (B * F + 1) + 4 * R * U + 4 * K * B * (D + 2) + 4 * B * F * D,
+        "aggregate_partials": 4 * (K + 1) * B * (D + 2),
+        "fm_finalize": 4 * B * (D + 2),
+        "backward_expand": 4 * n + 4 * (B * F + 1) + 8 * n,
+        "sort_histogram": sort_passes * 4 * n,
+        "sort_scatter": sort_passes * 16 * n,
+        "backward_segment_heads": 8 * n + 8 * U,
+        "backward_short_update": 4 * st["n_short"] + 8 * U + gp * st["n_short"] / max(n, 1) + 4 * B * (D + 2) * st["n_short"] / max(n, 1)
+                                 + 2 * state_mult * 4 * R * st["U_short"],
+        "backward_long_partial": 4 * st["n_long"] + gp * st["n_long"] / max(n, 1) + 4 * B * (D + 2) * st["n_long"] / max(n, 1)
+                                 + 8 * (D + 4) * st["n_chunks"],
+        "backward_long_final": 8 * (D + 4) * st["n_chunks"] + 2 * state_mult * 4 * R * st["U_long"],
+    }
+
+
+def cpu_baseline(w, batch, sample_B, opt_code):
+    """The oracle, as it stands, on the first `sample_B` samples of batch 0 with a table that
+    holds exactly the IDs those samples touch (pre-inserted head with initialiser weights; the
+    rest is inserted by the timed lookup, as on the GPU)."""
+    import oracle
+    F, D = w.F, w.D
+    nb = min(sample_B, w.B)
+    end = int(batch.offsets[nb * F])
+    keys, offsets = batch.keys[:end].copy(), batch.offsets[:nb * F + 1].copy()
+    if batch.ranks is not None:
+        head = np.unique(keys[batch.ranks[:end] <= w.preinsert])
+    else:
+        head = np.unique(keys)
+    t = oracle.Table(D, head.size + np.unique(keys).size + 16, seed=w.seed, init_scale=w.init_std)
+    t.insert(head)
+    rng = np.random.default_rng(1)
+    g_lr = (rng.standard_normal(nb) / w.B).astype(np.float32)
+    g_fm = (rng.standard_normal(nb) / w.B).astype(np.float32)
+    g_pool = (rng.standard_normal((nb, F, D)) / w.B).astype(np.float32)
+    t0 = time.perf_counter()
+    rows = t.find(keys, insert_missing=True)
+    P = t.partial_forward(nb, F, keys, offsets, rows, w.K, 0, None, pool=False)
+    pool = t.partial_forward(nb, F, keys, offsets, rows, 1, 0, None, lr=False, fm=False, pool=True)["P_pool"]
+    A_sum = oracle.aggregate(P["P_sum"]); A_sq = oracle.aggregate(P["P_sq"]); oracle.aggregate(P["P_lr"])
+    oracle.aggregate(pool)
+    oracle.fm_finalize(A_sum, A_sq)
+    t.backward_update(nb, F, offsets, rows, g_lr, g_fm, A_sum.astype(np.float32), g_pool, opt_code, w.lr,
+                      w.eps if w.eps else 1e-8)
+    dt = time.perf_counter() - t0
+    t.close()
+    return {"value": end / dt, "unit": "lookups/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {nb} of {w.B} samples of batch 0 ({end} lookups, {dt:.2f} s); table holds only the "
+                      f"{head.size} pre-inserted IDs these samples touch, initialiser weights",
+            "samples_per_s": nb / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations (0-4)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
+    ap.add_argument("--batches", type=int, default=0, help="distinct pre-generated batches (default 8, fewer for huge ones)")
+    ap.add_argument("--cpu-samples", type=int, default=2048)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (K logical shards on one device); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1909_04823_amd import des, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    w = synth.workload(args.config, scale=args.scale)
+    streaming = bool(w.p_new)
+    opt = des.OPT_SGD if w.opt == "sgd" else des.OPT_ADAGRAD
+    state_mult = 1 if w.opt == "sgd" else 2
+    total_steps = args.warmup + args.steps
+    n_batches = args.batches or (total_steps if streaming else (2 if w.index == 4 and args.scale == 1.0 else 8))
+    n_batches = min(n_batches, total_steps) if not streaming else total_steps
+
+    # ---- inputs (host generation, then resident in HBM) --------------------------------------
+    t_setup = time.perf_counter()
+    if streaming:
+        gen = synth.StreamingGenerator(w)
+        first_keys = gen.initial_keys()
+        host_batches = [gen.next_batch() for _ in range(n_batches)]
+    else:
+        host_batches = [synth.gen_batch(w, i) for i in range(n_batches)]
+    max_nnz = max(b.nnz for b in host_batches)
+    chunk = 1 << 22
+    table = des.Table(w.D, w.capacity, w.K, des.SHARD_KEY_HASH, opt, init_seed=w.seed, init_scale=w.init_std,
+                      max_n=max(max_nnz, min(chunk, w.preinsert)))
+    if streaming:
+        for lo in range(0, first_keys.size, chunk):
+            table.insert(torch.from_numpy(first_keys[lo:lo + chunk].view(np.int64)).cuda())
+    else:
+        for lo in range(0, w.preinsert, chunk):
+            k = synth.preinsert_keys(w, lo, min(w.preinsert, lo + chunk))
+            vals = None
+            if w.host_values:
+                vals = torch.from_numpy(synth.host_values(w, w.preinsert)[lo:lo + chunk]).cuda()
+            table.insert(torch.from_numpy(k.view(np.int64)).cuda(), vals)
+    assert table.status() == 0
+    rows_before = table.size()
+    batches = [des.Batch.from_numpy(b) for b in host_batches]
+    g_lr, g_fm, g_pool = synth.upstream_gradients(w, 0)
+    g_lr, g_fm, g_pool = (torch.from_numpy(a).cuda() for a in (g_lr, g_fm, g_pool))
+    B, F, D, K = w.B, w.F, w.D, w.K
+    dev = torch.device("cuda")
+    rows = torch.empty(max_nnz, dtype=torch.int32, device=dev)
+    P_lr = torch.empty((K, B), dtype=torch.float32, device=dev)
+    P_sum = torch.empty((K, B, D), dtype=torch.float32, device=dev)
+    P_sq = torch.empty((K, B), dtype=torch.float32, device=dev)
+    pool = torch.empty((B, F, D), dtype=torch.float32, device=dev)
+    A_lr = torch.empty(B, dtype=torch.float32, device=dev)
+    A_sum = torch.empty((B, D), dtype=torch.float32, device=dev)
+    A_sq = torch.empty(B, dtype=torch.float32, device=dev)
+    fm2 = torch.empty(B, dtype=torch.float32, device=dev)
+    n_uniq = torch.zeros(1, dtype=torch.int64, device=dev)
+    miss = des.MISS_INSERT if (w.preinsert < w.key_space or streaming) else des.MISS_ZERO
+    eps = w.eps if w.eps else 1e-8
+    setup_s = time.perf_counter() - t_setup
+
+    def step(i):
+        b = batches[i % len(batches)]
+        r = rows[:b.nnz]
+        table.find(b.keys, miss, r)
+        table.partial_forward(b, r, P_lr, P_sum, P_sq, pool)
+        des.aggregate_partials(P_lr, A_lr)
+        des.aggregate_partials(P_sum, A_sum)
+        des.aggregate_partials(P_sq, A_sq)
+        des.fm_finalize(A_sum, A_sq, fm2)
+        dbg = {"n_uniq": n_uniq}
+        if opt == des.OPT_SGD:
+            table.backward_update_sgd(b, r, w.lr, g_lr, g_fm, A_sum, g_pool, dbg=dbg)
+        else:
+            table.backward_update_adagrad(b, r, w.lr, eps, g_lr, g_fm, A_sum, g_pool, dbg=dbg)
+        return b.nnz
+
+    # ---- timed region ---------------------------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    lookups = 0
+    for i in range(args.warmup, total_steps):
+        lookups += step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert table.status() == 0, "device-side error during the timed steps"
+    assert bool(torch.isfinite(fm2).all()) and bool(torch.isfinite(pool).all())
+    ms_per_step = 1e3 * dt / args.steps
+
+    # ---- per-kernel pass: same steps again, HIP events on the launch stream around every launch --
+    kernels, roof = {}, None
+    if not args.no_kernel_pass and not streaming:
+        des.profile_enable(True)
+        for i in range(args.warmup, total_steps):
+            step(i)
+        prof = des.profile_read()
+        des.profile_enable(False)
+        used = sorted({i % len(batches) for i in range(args.warmup, total_steps)})
+        stats = [batch_stats(host_batches[i].keys) for i in used[:2]]
+        st = {k: float(np.mean([s[k] for s in stats])) for k in stats[0]}
+        cap_bits = max(1, int(w.capacity).bit_length())
+        sort_passes = (cap_bits + 7) // 8
+        nnz_mean = lookups / args.steps
+        model = algorithmic_bytes(w, nnz_mean, st, sort_passes, state_mult)
+        for name, (launches, total_ms) in prof.items():
+            per_step_ms = total_ms / args.steps
+            entry = {"launches_per_step": launches / args.steps, "ms_per_step": round(per_step_ms, 4)}
+            if name in model and per_step_ms > 0:
+                entry["algorithmic_GBps"] = round(model[name] / (per_step_ms * 1e-3) / 1e9, 1)
+            kernels[name] = entry
+        dom = max((k for k in kernels if k in model), key=lambda k: kernels[k]["ms_per_step"])
+        lps = kernels[dom]["launches_per_step"]
+        per_launch_bytes = model[dom] / lps
+        per_launch_s = kernels[dom]["ms_per_step"] * 1e-3 / lps
+        achieved = per_launch_bytes / per_launch_s / 1e9
+        roof = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": int(per_launch_bytes), "avg_launch_ms": round(per_launch_s * 1e3, 4),
+                "distinct_rows_per_step": st["U"], "kernel_ms_sum_per_step": round(sum(v["ms_per_step"] for v in kernels.values()), 4)}
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(w, host_batches[0], args.cpu_samples, 1 if w.opt == "sgd" else 2)
+
+    out = {
+        "metric": "sparse lookups/sec, DES fwd+bwd step (samples/sec alongside)",
+        "value": lookups / dt, "unit": "lookups/s", "samples_per_s": args.steps * B / dt,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (f64 accumulation)", "data": "synthetic",
+        "config": {"workload": f"configs[{w.index}] {w.name}" + ("" if args.scale == 1.0 else f" scaled x{args.scale}"),
+                   "B": B, "F": F, "D": D, "K": K, "optimizer": w.opt, "nnz_per_step": lookups / args.steps,
+                   "table_rows": rows_before, "table_rows_after": table.size(), "distinct_batches": len(batches),
+                   "find_policy": "insert" if miss == des.MISS_INSERT else "lookup", "setup_s": round(setup_s, 1)},
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

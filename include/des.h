@@ -31,7 +31,8 @@
  *   shard         DES_SHARD_KEY_HASH: (uint32)(mix64(key)>>32) mod K;
  *                 DES_SHARD_FIELD_MOD: field mod K (Section 5, "i = f mod N").
  *   row numbers   dense 0..n_rows-1; the distinct unseen keys of one insert/find call get
- *                 consecutive rows in ascending unsigned key order.
+ *                 consecutive rows in the order of their first occurrence in the call, i.e.
+ *                 the result of a sequential insert loop over the keys.
  *   initialiser   column c of a row inserted without values is
  *                 ((mix64(key ^ mix64(seed+c)) >> 40) * 2^-24 - 0.5) * (float)(2*sqrt(3)*init_scale)
  *                 (c < dim latent, c == dim the LR weight); optimizer state starts at 0.

@@ -21,8 +21,8 @@
  *                                        of the aggregate reaches every sub-operator unchanged
  *
  * Conventions the paper leaves open and this build fixes (the HIP library implements the same
- * text independently): the 64-bit mixer, the row initialiser, the row-assignment order, the
- * merged-key order and the placement of eps in Adagrad.  These are "parity unpinned": nothing
+ * text independently): the 64-bit mixer, the row initialiser, the row-assignment order (that of
+ * a sequential insert loop), the merged-key order and the placement of eps in Adagrad.  These are "parity unpinned": nothing
  * in the paper can confirm them, the two implementations merely have to agree.
  */
 #include <math.h>
@@ -127,10 +127,17 @@ static int cmp_newkey(const void *a, const void *b) {
   return x->first < y->first ? -1 : (x->first > y->first);
 }
 
-/* Insert-if-absent.  The distinct keys of this call that the table does not hold yet receive
- * the next consecutive rows in ascending unsigned key order.  Their weights are the host
- * values of the key's first occurrence in the call, or the initialiser; optimizer state is
- * zero.  Keys already present are left untouched.  rows_out[i] = row of keys[i]. */
+static int cmp_first(const void *a, const void *b) {
+  const newkey_t *x = (const newkey_t *)a, *y = (const newkey_t *)b;
+  return x->first < y->first ? -1 : (x->first > y->first);
+}
+
+/* Insert-if-absent, with the result of the plain sequential loop
+ *     for i in 0..n-1: if keys[i] not in table: table[keys[i]] = n_rows++
+ * i.e. the distinct keys of this call that the table does not hold yet receive the next
+ * consecutive rows in the order of their first occurrence in the call.  Their weights are the
+ * host values of that first occurrence, or the initialiser; optimizer state is zero.  Keys
+ * already present are left untouched.  rows_out[i] = row of keys[i]. */
 int oracle_table_insert(oracle_table *t, const uint64_t *keys, int64_t n, const float *values,
                         int32_t *rows_out) {
   if (!t || n < 0 || (n > 0 && !keys)) return ORACLE_ERR_INVALID_ARG;
@@ -144,6 +151,7 @@ int oracle_table_insert(oracle_table *t, const uint64_t *keys, int64_t n, const 
   for (int64_t i = 0; i < m; ++i)
     if (i == 0 || cand[i].key != cand[i - 1].key) cand[u++] = cand[i];
   if (t->n_rows + u > t->capacity) { free(cand); return ORACLE_ERR_FULL; }
+  qsort(cand, (size_t)u, sizeof(newkey_t), cmp_first);   /* row order = order of first occurrence */
   const int D = t->D;
   for (int64_t j = 0; j < u; ++j) {
     int64_t row = t->n_rows + j;
@@ -156,12 +164,14 @@ int oracle_table_insert(oracle_table *t, const uint64_t *keys, int64_t n, const 
                        : oracle_init_value(k, D, t->seed, t->init_scale);
     for (int c = 0; c < D; ++c) t->acc_emb[row * D + c] = 0.0f;
     t->acc_w[row] = 0.0f;
+    cand[j].first = row;                           /* reuse the field: the key's row */
   }
-  /* merge the new (ascending) keys into the ascending key list, back to front */
+  /* merge the new keys, ascending by key, into the ascending key list, back to front */
+  qsort(cand, (size_t)u, sizeof(newkey_t), cmp_newkey);
   int64_t a = t->n_rows - 1, b = u - 1, o = t->n_rows + u - 1;
   while (b >= 0) {
     if (a >= 0 && t->skeys[a] > cand[b].key) { t->skeys[o] = t->skeys[a]; t->srows[o] = t->srows[a]; --a; }
-    else { t->skeys[o] = cand[b].key; t->srows[o] = (int32_t)(t->n_rows + b); --b; }
+    else { t->skeys[o] = cand[b].key; t->srows[o] = (int32_t)cand[b].first; --b; }
     --o;
   }
   t->n_rows += u;

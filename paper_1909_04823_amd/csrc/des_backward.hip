@@ -18,7 +18,8 @@
 namespace des {
 namespace {
 
-constexpr int kChunk = 32;                 // entries per chunk; segments up to this long are "short"
+constexpr int kShortMax = 32;              // segments up to this many entries are reduced by one lane group
+constexpr int kChunk = 512;                // entries per chunk of a longer segment (one wave per chunk)
 constexpr int kHeadItems = 8;
 constexpr int kHeadTile = kBlock * kHeadItems;
 constexpr int kWavesPerBlock = kBlock / kWave;
@@ -43,10 +44,10 @@ struct BwdArgs {
   int32_t *seg_off;     // [n+1]
   int32_t *uniq_rows;   // [n]
   uint32_t *head_sums;
-  int32_t *long_seg;    // [n/kChunk+1]  segment index of long segment j
-  uint32_t *long_c0;    // [n/kChunk+1]  first chunk of long segment j
-  int32_t *chunk_owner; // [2n/kChunk+2] long segment index of chunk c
-  double *partials;     // [2n/kChunk+2][D+4]
+  int32_t *long_seg;    // segment index of long segment j
+  uint32_t *long_c0;    // first chunk of long segment j
+  int32_t *chunk_owner; // long segment index of chunk c
+  double *partials;     // [chunks][D+4]
   // optimizer
   int opt;
   float lr, eps;
@@ -183,18 +184,39 @@ __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
   }
 }
 
-// long segments get a chunk range; the order of the list is irrelevant to the results
+// Long segments get a chunk range.  The order of the list is irrelevant to the results, so
+// ranges are handed out with one atomic pair per workgroup.
 __global__ __launch_bounds__(kBlock) void k_classify(const BwdArgs a) {
+  __shared__ uint32_t lds[kWavesPerBlock];
+  __shared__ unsigned long long base_long, base_chunk;
   const long long U = a.ctrl->n_uniq;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < U; u += stride) {
-    const int len = a.seg_off[u + 1] - a.seg_off[u];
-    if (len > kChunk) {
-      const unsigned long long j = atomicAdd(reinterpret_cast<unsigned long long *>(&a.ctrl->n_long), 1ull);
-      const unsigned long long c0 = atomicAdd(reinterpret_cast<unsigned long long *>(&a.ctrl->n_chunks),
-                                              (unsigned long long)((len + kChunk - 1) / kChunk));
-      a.long_seg[j] = (int32_t)u;
-      a.long_c0[j] = (uint32_t)c0;
+  const int64_t tile0 = (int64_t)blockIdx.x * kHeadTile + (int64_t)threadIdx.x * kHeadItems;
+  if ((int64_t)blockIdx.x * kHeadTile >= U) return;          // uniform per workgroup
+  uint32_t nl = 0, nc = 0;
+  int len[kHeadItems];
+#pragma unroll
+  for (int i = 0; i < kHeadItems; ++i) {
+    const int64_t u = tile0 + i;
+    len[i] = u < U ? a.seg_off[u + 1] - a.seg_off[u] : 0;
+    if (len[i] > kShortMax) { ++nl; nc += (uint32_t)((len[i] + kChunk - 1) / kChunk); }
+  }
+  uint32_t tot_l, tot_c;
+  uint32_t ex_l = block_excl_scan_u32(nl, lds, tot_l);
+  uint32_t ex_c = block_excl_scan_u32(nc, lds, tot_c);
+  if (tot_l == 0) return;                                    // uniform: the scans synchronised the workgroup
+  if (threadIdx.x == 0) {
+    base_long = atomicAdd(reinterpret_cast<unsigned long long *>(&a.ctrl->n_long), (unsigned long long)tot_l);
+    base_chunk = atomicAdd(reinterpret_cast<unsigned long long *>(&a.ctrl->n_chunks), (unsigned long long)tot_c);
+  }
+  __syncthreads();
+  uint32_t j = (uint32_t)base_long + ex_l, c0 = (uint32_t)base_chunk + ex_c;
+#pragma unroll
+  for (int i = 0; i < kHeadItems; ++i) {
+    if (len[i] > kShortMax) {
+      a.long_seg[j] = (int32_t)(tile0 + i);
+      a.long_c0[j] = c0;
+      ++j;
+      c0 += (uint32_t)((len[i] + kChunk - 1) / kChunk);
     }
   }
 }
@@ -304,30 +326,44 @@ __global__ __launch_bounds__(kBlock) void k_short_update(const BwdArgs a) {
   const int sub = (int)(gid % G);
   if (u >= a.ctrl->n_uniq) return;
   const int i0 = a.seg_off[u], i1 = a.seg_off[u + 1];
-  if (i1 - i0 > kChunk) return;
+  if (i1 - i0 > kShortMax) return;
   Acc acc = acc_zero();
   reduce_entries<D, kHasVals>(a, i0, i1, sub, acc);
   apply_row<D>(a, u, a.uniq_rows[u], sub, acc);
 }
 
-// (4b) one lane group per chunk of a long segment -> partials[c] = (s1[D], s2, gw, 0, 0) in double
+// (4b) one wave per chunk of a long segment: the chunk is split evenly over the wave's lane
+// groups, the groups' sums are combined with cross-lane shuffles, and the wave writes
+// partials[c] = (s1[D], s2, gw, 0, 0) in double
 template <int D, bool kHasVals>
 __global__ __launch_bounds__(kBlock) void k_long_partial(const BwdArgs a) {
   constexpr int G = D / 4;
-  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t c = gid / G;
-  const int sub = (int)(gid % G);
-  if (c >= a.ctrl->n_chunks) return;
+  constexpr int NG = kWave / G;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t c = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  if (c >= a.ctrl->n_chunks) return;                          // uniform per wave
+  const int g = lane / G, sub = lane % G;
   const int j = a.chunk_owner[c];
   const int u = a.long_seg[j];
-  const int i0 = a.seg_off[u] + (int)(c - a.long_c0[j]) * kChunk;
-  const int i1 = min(i0 + kChunk, a.seg_off[u + 1]);
+  const int c_lo = a.seg_off[u] + (int)(c - a.long_c0[j]) * kChunk;
+  const int c_hi = min(c_lo + kChunk, a.seg_off[u + 1]);
+  const int per = (c_hi - c_lo + NG - 1) / NG;
+  const int i0 = min(c_lo + g * per, c_hi), i1 = min(i0 + per, c_hi);
   Acc acc = acc_zero();
   reduce_entries<D, kHasVals>(a, i0, i1, sub, acc);
-  double *p = a.partials + c * (D + 4);
 #pragma unroll
-  for (int k = 0; k < 4; ++k) p[sub * 4 + k] = acc.v[k];
-  if (sub == 0) { p[D] = acc.s2; p[D + 1] = acc.gw; }
+  for (int m = G; m < kWave; m <<= 1) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc.v[k] += __shfl_xor(acc.v[k], m, kWave);
+    acc.s2 += __shfl_xor(acc.s2, m, kWave);
+    acc.gw += __shfl_xor(acc.gw, m, kWave);
+  }
+  if (g == 0) {
+    double *p = a.partials + c * (D + 4);
+    *reinterpret_cast<double2 *>(p + sub * 4) = make_double2(acc.v[0], acc.v[1]);
+    *reinterpret_cast<double2 *>(p + sub * 4 + 2) = make_double2(acc.v[2], acc.v[3]);
+    if (sub == 0) *reinterpret_cast<double2 *>(p + D) = make_double2(acc.s2, acc.gw);
+  }
 }
 
 // (4c) one workgroup per long segment: lane groups stride over the chunk partials, an LDS tree
@@ -346,9 +382,13 @@ __global__ __launch_bounds__(kBlock) void k_long_final(const BwdArgs a) {
     Acc acc = acc_zero();
     for (int c = grp; c < nch; c += NGB) {
       const double *p = p0 + (int64_t)c * (D + 4);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) acc.v[k] += p[sub * 4 + k];
-      if (sub == 0) { acc.s2 += p[D]; acc.gw += p[D + 1]; }
+      const double2 lo = *reinterpret_cast<const double2 *>(p + sub * 4);
+      const double2 hi = *reinterpret_cast<const double2 *>(p + sub * 4 + 2);
+      acc.v[0] += lo.x; acc.v[1] += lo.y; acc.v[2] += hi.x; acc.v[3] += hi.y;
+      if (sub == 0) {
+        const double2 t = *reinterpret_cast<const double2 *>(p + D);
+        acc.s2 += t.x; acc.gw += t.y;
+      }
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) red[grp][sub * 4 + k] = acc.v[k];
@@ -397,15 +437,15 @@ inline unsigned blocks_for(int64_t threads, int64_t cap = 1ll << 30) {
 template <int D, bool kHasVals>
 void launch_update(const BwdArgs &a, hipStream_t s) {
   constexpr int G = D / 4;
-  const int64_t max_chunks = 2 * (a.n / kChunk) + 2;
-  const int64_t max_long = a.n / kChunk + 1;
+  const int64_t max_long = a.n / (kShortMax + 1) + 1;
+  const int64_t max_chunks = a.n / kChunk + max_long + 1;
   {
     ProfScope ps(KID_SHORT_UPDATE, s);
     hipLaunchKernelGGL((k_short_update<D, kHasVals>), dim3(blocks_for(a.n * G)), dim3(kBlock), 0, s, a);
   }
   {
     ProfScope ps(KID_LONG_PARTIAL, s);
-    hipLaunchKernelGGL((k_long_partial<D, kHasVals>), dim3(blocks_for(max_chunks * G)), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((k_long_partial<D, kHasVals>), dim3(blocks_for(max_chunks * kWave)), dim3(kBlock), 0, s, a);
   }
   {
     ProfScope ps(KID_LONG_FINAL, s);
@@ -425,7 +465,7 @@ struct Layout {
 
 Layout layout_for(int D, int64_t n) {
   const size_t m = (size_t)(n > 0 ? n : 1);
-  const size_t max_long = m / kChunk + 1, max_chunks = 2 * (m / kChunk) + 2;
+  const size_t max_long = m / (kShortMax + 1) + 1, max_chunks = m / kChunk + max_long + 1;
   Layout L;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
@@ -498,8 +538,8 @@ des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *
   }
   {
     ProfScope ps(KID_CLASSIFY, s);
-    hipLaunchKernelGGL(k_classify, dim3(blocks_for(n, 1 << 16)), dim3(kBlock), 0, s, a);
-    const int64_t max_long = n / kChunk + 1;
+    hipLaunchKernelGGL(k_classify, dim3((unsigned)((n + kHeadTile - 1) / kHeadTile)), dim3(kBlock), 0, s, a);
+    const int64_t max_long = n / (kShortMax + 1) + 1;
     hipLaunchKernelGGL(k_chunk_owner, dim3((unsigned)(max_long < 65536 ? max_long : 65536)), dim3(kBlock), 0, s, a);
   }
   switch (D) {

@@ -15,8 +15,8 @@ constexpr int kBlock = 256;
 // One hash slot: key and row side by side so a probe is one 16-byte access.
 struct __attribute__((aligned(16))) Slot {
   uint64_t key;
-  int32_t row;
-  int32_t pad;
+  int32_t row;        // -1 until the key's row is known
+  uint32_t first;     // smallest entry index of the call that claimed the key (meaningful while row < 0)
 };
 
 // Device-resident control block at the head of the workspace.
@@ -41,7 +41,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- per-kernel timing (process-wide collector) ----------------------------------------
 enum KernelId {
-  KID_PROBE = 0, KID_ASSIGN, KID_PATCH, KID_COPY_VALUES, KID_COMMIT,
+  KID_PROBE = 0, KID_ASSIGN, KID_PATCH, KID_INIT_ROWS,
   KID_FORWARD, KID_POOL_DENSE, KID_AGGREGATE, KID_FM_FINALIZE,
   KID_EXPAND, KID_SORT_HIST, KID_SORT_SCAN, KID_SORT_SCATTER,
   KID_HEADS, KID_CLASSIFY, KID_SHORT_UPDATE, KID_LONG_PARTIAL, KID_LONG_FINAL, KID_EXPORT,
@@ -64,12 +64,10 @@ size_t sort_scratch_bytes(int64_t n);
 void exclusive_scan_u64(unsigned long long *data, int64_t n, unsigned long long *total_out,
                         void *scratch, hipStream_t s);
 
-// Stable LSD radix sort of the low `bits` bits.  n_dev (device, may be null) overrides n with a
-// device-side count <= n.  Result lands in the buffer the function returns (a or b side).
+// Stable LSD radix sort of (32-bit key, 32-bit payload) pairs on the low `bits` bits of the key.
+// Returns 0 if the sorted data is in the *_a buffers, 1 if in *_b.
 struct SortBuffers { void *keys_a, *keys_b; uint32_t *pay_a, *pay_b; };
-// returns 0 if the sorted data is in the *_a buffers, 1 if in *_b
 int radix_sort_u32_pairs(SortBuffers buf, int64_t n, int bits, void *scratch, hipStream_t s);
-int radix_sort_u64_keys(SortBuffers buf, int64_t n, const long long *n_dev, void *scratch, hipStream_t s);
 
 }  // namespace des
 

@@ -198,7 +198,8 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict
 inline int64_t sort_blocks(int64_t n) { return (n + kSortTile - 1) / kSortTile; }
 
 template <typename KeyT, bool kHasPayload>
-int radix_sort(SortBuffers buf, int64_t n, const long long *n_dev, int bits, void *scratch, hipStream_t s) {
+int radix_sort(SortBuffers buf, int64_t n, const long long *n_dev, int bits, void *scratch, hipStream_t s,
+               int kid_hist, int kid_scan, int kid_scatter) {
   if (n <= 0 || bits <= 0) return 0;
   const int nblocks = (int)sort_blocks(n);
   uint32_t *hist = (uint32_t *)scratch;
@@ -212,15 +213,15 @@ int radix_sort(SortBuffers buf, int64_t n, const long long *n_dev, int bits, voi
     const int shift = p * per;
     const int b = (bits - shift) < per ? (bits - shift) : per;
     {
-      ProfScope ps(KID_SORT_HIST, s);
+      ProfScope ps(kid_hist, s);
       hipLaunchKernelGGL(k_radix_hist<KeyT>, dim3(nblocks), dim3(kBlock), 0, s, kin, n, n_dev, shift, b, hist, nblocks);
     }
     {
-      ProfScope ps(KID_SORT_SCAN, s);
+      ProfScope ps(kid_scan, s);
       exclusive_scan<uint32_t>(hist, (int64_t)(1 << b) * nblocks, nullptr, scan_scratch, s);
     }
     {
-      ProfScope ps(KID_SORT_SCATTER, s);
+      ProfScope ps(kid_scatter, s);
       hipLaunchKernelGGL((k_radix_scatter<KeyT, kHasPayload>), dim3(nblocks), dim3(kBlock), 0, s, kin, pin, kout, pout,
                          n, n_dev, shift, b, hist, nblocks);
     }
@@ -249,11 +250,7 @@ void exclusive_scan_u64(unsigned long long *data, int64_t n, unsigned long long 
 }
 
 int radix_sort_u32_pairs(SortBuffers buf, int64_t n, int bits, void *scratch, hipStream_t s) {
-  return radix_sort<uint32_t, true>(buf, n, nullptr, bits, scratch, s);
-}
-
-int radix_sort_u64_keys(SortBuffers buf, int64_t n, const long long *n_dev, void *scratch, hipStream_t s) {
-  return radix_sort<unsigned long long, false>(buf, n, n_dev, 64, scratch, s);
+  return radix_sort<uint32_t, true>(buf, n, nullptr, bits, scratch, s, KID_SORT_HIST, KID_SORT_SCAN, KID_SORT_SCATTER);
 }
 
 }  // namespace des

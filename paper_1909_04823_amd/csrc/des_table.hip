@@ -2,9 +2,12 @@
 // over 16-byte slots, 64-bit keys claimed with a compare-and-swap, plus the C entry points
 // that do not belong to the forward or backward files.
 //
-// Row numbers must not depend on which thread wins a slot, so an insert is split in two:
-// claiming a slot (racy, unobservable) and numbering the claimed keys (sort the distinct new
-// keys of the call ascending, row = n_rows + rank).
+// Row numbers must not depend on which thread wins a slot: they are those of a sequential
+// insert loop (unseen distinct keys numbered in order of first occurrence).  An insert is
+// therefore split in two: claiming a slot (racy, unobservable), during which every entry of a
+// new key lowers the slot's "first occurrence" index with an atomic minimum, and numbering:
+// the entries that ARE the first occurrence of a new key are counted with a prefix sum in
+// entry order, row = n_rows + prefix.
 #include <math.h>
 #include <string.h>
 #include <new>
@@ -15,6 +18,10 @@ using namespace des;
 
 namespace {
 
+constexpr int kFlagItems = 8;                       // entries per thread in the numbering kernels
+constexpr int kFlagTile = kBlock * kFlagItems;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
 __device__ inline void set_status(Ctrl *c, int st) { atomicCAS(&c->status, 0, st); }
 
 __device__ inline Slot load_slot(const Slot *p) {
@@ -22,16 +29,17 @@ __device__ inline Slot load_slot(const Slot *p) {
   Slot s;
   s.key = ((uint64_t)raw.y << 32) | raw.x;
   s.row = (int32_t)raw.z;
-  s.pad = 0;
+  s.first = raw.w;
   return s;
 }
 
-// Pass A.  rows[e] = row (>= 0), kRowAbsent, or kRowPending for keys claimed in this call.
+// Pass A.  rows[e] = row (>= 0), kRowAbsent, or kRowPending for keys claimed in this call; for
+// pending entries slot_of[e] remembers the slot so later passes need not probe again.
 template <bool kInsert>
 __global__ __launch_bounds__(kBlock) void k_probe(Slot *__restrict__ slots, uint64_t slot_mask,
                                                    const uint64_t *__restrict__ keys, int64_t n,
                                                    int32_t *__restrict__ rows, Ctrl *__restrict__ ctrl,
-                                                   unsigned long long *__restrict__ new_keys) {
+                                                   uint32_t *__restrict__ slot_of) {
   // after a sticky error the table no longer grows: the call degrades to a pure lookup, so
   // rows[] is still fully written with valid rows or kRowAbsent
   const bool can_insert = kInsert && ctrl->status == 0;
@@ -45,13 +53,13 @@ __global__ __launch_bounds__(kBlock) void k_probe(Slot *__restrict__ slots, uint
       continue;
     }
     uint64_t idx = mix64(key) & slot_mask;
-    bool done = false;
+    bool done = false, pending = false;
     for (uint64_t probe = 0; probe <= slot_mask && !done; ++probe) {
       const Slot s = load_slot(&slots[idx]);
       if (s.key == key) {
         // a negative row under a key is a claim of the running call, or the leftover of a
-        // call that failed: only a call that can insert will resolve it later
-        out = s.row >= 0 ? s.row : (can_insert ? kRowPending : kRowAbsent);
+        // call that failed: only a call that can insert resolves it
+        if (s.row >= 0) out = s.row; else pending = can_insert;
         done = true;
       } else if (s.key == kEmptyKey) {
         if (!can_insert) {
@@ -59,13 +67,8 @@ __global__ __launch_bounds__(kBlock) void k_probe(Slot *__restrict__ slots, uint
         } else {
           const unsigned long long old =
               atomicCAS(reinterpret_cast<unsigned long long *>(&slots[idx].key), kEmptyKey, key);
-          if (old == kEmptyKey) {                 // this thread claimed the slot: a new distinct key
-            const unsigned long long pos = atomicAdd(reinterpret_cast<unsigned long long *>(&ctrl->n_new), 1ull);
-            new_keys[pos] = key;
-            out = kRowPending;
-            done = true;
-          } else if (old == key) {                // another thread claimed it for the same key
-            out = kRowPending;
+          if (old == kEmptyKey || old == key) {   // claimed here, or by another entry of the same key
+            pending = true;
             done = true;
           } else {
             idx = (idx + 1) & slot_mask;          // lost the slot to a different key
@@ -76,31 +79,112 @@ __global__ __launch_bounds__(kBlock) void k_probe(Slot *__restrict__ slots, uint
       }
     }
     if (!done) set_status(ctrl, DES_ERR_FULL);     // every slot visited
+    if (pending) {
+      atomicMin(&slots[idx].first, (uint32_t)e);
+      slot_of[e] = (uint32_t)idx;
+      out = kRowPending;
+    }
     rows[e] = out;
   }
 }
 
-// Pass C.  Sorted new key i gets row n_rows + i; its slot learns the row.
-__global__ __launch_bounds__(kBlock) void k_assign(Slot *__restrict__ slots, uint64_t slot_mask,
-                                                    const unsigned long long *__restrict__ sorted_keys,
-                                                    Ctrl *__restrict__ ctrl, int64_t capacity,
-                                                    uint64_t *__restrict__ row_keys, int32_t *__restrict__ first_idx) {
-  if (ctrl->status != 0) return;
-  const long long n_new = ctrl->n_new, n_rows = ctrl->n_rows;
-  if (n_rows + n_new > capacity) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) set_status(ctrl, DES_ERR_FULL);
-    return;
+__device__ inline uint32_t wave_incl_scan_u32(uint32_t v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t o = __shfl_up(v, off, kWave);
+    if (lane >= off) v += o;
   }
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_new; i += stride) {
-    const uint64_t key = sorted_keys[i];
-    uint64_t idx = mix64(key) & slot_mask;
-    for (uint64_t probe = 0; probe <= slot_mask; ++probe) {
-      if (slots[idx].key == key) { slots[idx].row = (int32_t)(n_rows + i); break; }
-      idx = (idx + 1) & slot_mask;
+  return v;
+}
+
+__device__ inline uint32_t block_excl_scan_u32(uint32_t v, uint32_t *lds, uint32_t &total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const uint32_t inc = wave_incl_scan_u32(v);
+  if (lane == kWave - 1) lds[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    const uint32_t x = lds[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  __syncthreads();
+  total = tot;
+  return base + inc - v;
+}
+
+// entry e opens a new row iff it is pending and is the first occurrence recorded in its slot
+__device__ inline bool opens_row(const Slot *slots, const int32_t *rows, const uint32_t *slot_of, int64_t e) {
+  return rows[e] == kRowPending && slots[slot_of[e]].first == (uint32_t)e;
+}
+
+// Pass B1: per tile, how many entries open a new row.
+__global__ __launch_bounds__(kBlock) void k_new_count(const Slot *__restrict__ slots, const int32_t *__restrict__ rows,
+                                                       const uint32_t *__restrict__ slot_of, int64_t n,
+                                                       uint32_t *__restrict__ tile_sums) {
+  __shared__ uint32_t lds[kWavesPerBlock];
+  const int64_t base = (int64_t)blockIdx.x * kFlagTile + (int64_t)threadIdx.x * kFlagItems;
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kFlagItems; ++i)
+    if (base + i < n && opens_row(slots, rows, slot_of, base + i)) ++cnt;
+  uint32_t total;
+  block_excl_scan_u32(cnt, lds, total);
+  if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
+}
+
+// Pass B2: one workgroup turns the tile counts into tile offsets, publishes the number of new
+// rows and checks the capacity.
+__global__ __launch_bounds__(kBlock) void k_new_sums(uint32_t *__restrict__ tile_sums, int64_t nb,
+                                                      Ctrl *__restrict__ ctrl, int64_t capacity) {
+  __shared__ uint32_t lds[kWavesPerBlock];
+  uint32_t carry = 0;
+  for (int64_t base = 0; base < nb; base += kBlock) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = i < nb ? tile_sums[i] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_excl_scan_u32(v, lds, total);
+    if (i < nb) tile_sums[i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    ctrl->n_new = carry;
+    if (ctrl->n_rows + (long long)carry > capacity) set_status(ctrl, DES_ERR_FULL);
+  }
+}
+
+// Pass B3: number the new rows in entry order; the slot learns its row.
+__global__ __launch_bounds__(kBlock) void k_new_assign(Slot *__restrict__ slots, const int32_t *__restrict__ rows,
+                                                        const uint32_t *__restrict__ slot_of,
+                                                        const uint64_t *__restrict__ keys, int64_t n,
+                                                        const uint32_t *__restrict__ tile_sums,
+                                                        const Ctrl *__restrict__ ctrl, uint64_t *__restrict__ row_keys,
+                                                        int32_t *__restrict__ first_idx) {
+  __shared__ uint32_t lds[kWavesPerBlock];
+  if (ctrl->status != 0) return;                    // uniform: includes "would exceed the capacity"
+  const long long n_rows = ctrl->n_rows;
+  const int64_t base = (int64_t)blockIdx.x * kFlagTile + (int64_t)threadIdx.x * kFlagItems;
+  bool flag[kFlagItems];
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kFlagItems; ++i) {
+    flag[i] = base + i < n && opens_row(slots, rows, slot_of, base + i);
+    cnt += flag[i] ? 1u : 0u;
+  }
+  uint32_t total;
+  uint32_t rank = tile_sums[blockIdx.x] + block_excl_scan_u32(cnt, lds, total);
+#pragma unroll
+  for (int i = 0; i < kFlagItems; ++i) {
+    if (flag[i]) {
+      const int64_t e = base + i;
+      const long long row = n_rows + rank;
+      slots[slot_of[e]].row = (int32_t)row;
+      row_keys[row] = keys[e];
+      first_idx[rank] = (int32_t)e;
+      ++rank;
     }
-    row_keys[n_rows + i] = key;
-    if (first_idx) first_idx[i] = 0x7FFFFFFF;
   }
 }
 
@@ -140,27 +224,14 @@ __global__ __launch_bounds__(kBlock) void k_init_rows(const Ctrl *__restrict__ c
   }
 }
 
-// Pass D.  Entries that saw a pending key read the row now; with host values every entry of a
-// new key competes for "first occurrence" with an atomic minimum on its index.
-__global__ __launch_bounds__(kBlock) void k_patch(const Slot *__restrict__ slots, uint64_t slot_mask,
-                                                   const uint64_t *__restrict__ keys, int64_t n,
-                                                   int32_t *__restrict__ rows, const Ctrl *__restrict__ ctrl,
-                                                   int32_t *__restrict__ first_idx) {
-  const long long n_rows = ctrl->n_rows;
+// Pass D.  Entries that saw a pending key read the row from the slot they remembered.
+__global__ __launch_bounds__(kBlock) void k_patch(const Slot *__restrict__ slots, int64_t n,
+                                                   int32_t *__restrict__ rows, const uint32_t *__restrict__ slot_of) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) {
     if (rows[e] != kRowPending) continue;
-    const uint64_t key = keys[e];
-    uint64_t idx = mix64(key) & slot_mask;
-    int32_t out = kRowAbsent;
-    for (uint64_t probe = 0; probe <= slot_mask; ++probe) {
-      const Slot s = load_slot(&slots[idx]);
-      if (s.key == key) { out = s.row >= 0 ? s.row : kRowAbsent; break; }
-      if (s.key == kEmptyKey) break;
-      idx = (idx + 1) & slot_mask;
-    }
-    rows[e] = out;
-    if (first_idx && out >= n_rows) atomicMin(&first_idx[out - n_rows], (int32_t)e);
+    const int32_t row = slots[slot_of[e]].row;
+    rows[e] = row >= 0 ? row : kRowAbsent;         // negative only after a failed call
   }
 }
 
@@ -182,7 +253,7 @@ __global__ __launch_bounds__(kBlock) void k_copy_values(const Ctrl *__restrict__
     const int c = (int)(i % cols);
     const int64_t row = n_rows + j;
     const int32_t src = first_idx[j];
-    const float val = src == 0x7FFFFFFF ? 0.f : values[(int64_t)src * cols + c];
+    const float val = values[(int64_t)src * cols + c];
     if (c < D) {
       emb[row * D + c] = val;
       if (acc_emb) acc_emb[row * D + c] = 0.f;
@@ -286,10 +357,10 @@ namespace des {
 
 size_t insert_ws_bytes(int64_t n) {
   const size_t m = (size_t)(n > 0 ? n : 1);
-  return align_up(m * 4, 256)            // rows when the caller passes none
-         + 2 * align_up(m * 8, 256)      // new keys, two sides of the sort
-         + align_up(m * 4, 256)          // first-occurrence indices
-         + sort_scratch_bytes(n);
+  return align_up(m * 4, 256)                                   // rows when the caller passes none
+         + align_up(m * 4, 256)                                 // slot of each pending entry
+         + align_up(m * 4, 256)                                 // first-occurrence entry of each new row
+         + align_up(((m + kFlagTile - 1) / kFlagTile + 1) * 4, 256);   // per-tile counts
 }
 
 // ---- profiler ------------------------------------------------------------------------------
@@ -299,7 +370,7 @@ bool g_prof_on = false;
 std::vector<ProfRec> g_prof;
 hipEvent_t g_open[KID_COUNT];
 const char *kKernelNames[KID_COUNT] = {
-    "table_probe", "table_assign_rows", "table_patch_rows", "table_copy_values", "table_commit",
+    "table_probe", "table_number_new_rows", "table_patch_rows", "table_init_rows",
     "forward_gather_pool", "forward_pool_dense", "aggregate_partials", "fm_finalize",
     "backward_expand", "sort_histogram", "sort_scan", "sort_scatter",
     "backward_segment_heads", "backward_classify", "backward_short_update", "backward_long_partial",
@@ -432,46 +503,43 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
     if (!rows_out) return DES_ERR_INVALID_ARG;
     ProfScope ps(KID_PROBE, s);
     hipLaunchKernelGGL(k_probe<false>, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows_out,
-                       t->ctrl, (unsigned long long *)nullptr);
+                       t->ctrl, (uint32_t *)nullptr);
     return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
   }
   const size_t m = (size_t)n;
   char *p = t->ws;
   int32_t *tmp_rows = (int32_t *)p; p += align_up(m * 4, 256);
-  unsigned long long *nk_a = (unsigned long long *)p; p += align_up(m * 8, 256);
-  unsigned long long *nk_b = (unsigned long long *)p; p += align_up(m * 8, 256);
+  uint32_t *slot_of = (uint32_t *)p; p += align_up(m * 4, 256);
   int32_t *first_idx = (int32_t *)p; p += align_up(m * 4, 256);
-  void *sort_scratch = p;
+  uint32_t *tile_sums = (uint32_t *)p;
   int32_t *rows = rows_out ? rows_out : tmp_rows;
   const des_table_config_t &c = t->cfg;
+  const int64_t nb = (n + kFlagTile - 1) / kFlagTile;
   {
     ProfScope ps(KID_PROBE, s);
     hipLaunchKernelGGL(k_probe<true>, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows, t->ctrl,
-                       nk_a);
+                       slot_of);
   }
-  SortBuffers sb{nk_a, nk_b, nullptr, nullptr};
-  const int side = radix_sort_u64_keys(sb, n, &t->ctrl->n_new, sort_scratch, s);
-  const unsigned long long *sorted = side ? nk_b : nk_a;
   {
     ProfScope ps(KID_ASSIGN, s);
-    hipLaunchKernelGGL(k_assign, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, sorted, t->ctrl,
-                       c.capacity_rows, c.row_keys, values ? first_idx : (int32_t *)nullptr);
-    if (!values)
-      hipLaunchKernelGGL(k_init_rows, dim3(grid_for(n * (c.dim / 4 + 1))), dim3(kBlock), 0, s, t->ctrl, c.dim,
-                         c.init_seed, t->init_width, c.row_keys, c.emb, c.w, c.acc_emb, c.acc_w, c.capacity_rows);
+    hipLaunchKernelGGL(k_new_count, dim3((unsigned)nb), dim3(kBlock), 0, s, t->slots, rows, slot_of, n, tile_sums);
+    hipLaunchKernelGGL(k_new_sums, dim3(1), dim3(kBlock), 0, s, tile_sums, nb, t->ctrl, c.capacity_rows);
+    hipLaunchKernelGGL(k_new_assign, dim3((unsigned)nb), dim3(kBlock), 0, s, t->slots, rows, slot_of, keys, n,
+                       tile_sums, t->ctrl, c.row_keys, first_idx);
+  }
+  {
+    ProfScope ps(KID_INIT_ROWS, s);
+    if (values)
+      hipLaunchKernelGGL(k_copy_values, dim3(grid_for(n * (c.dim + 1), kBlock, 1 << 16)), dim3(kBlock), 0, s, t->ctrl,
+                         c.dim, values, first_idx, c.emb, c.w, c.acc_emb, c.acc_w, c.capacity_rows);
+    else
+      hipLaunchKernelGGL(k_init_rows, dim3(grid_for(n * (c.dim / 4 + 1), kBlock, 1 << 16)), dim3(kBlock), 0, s, t->ctrl,
+                         c.dim, c.init_seed, t->init_width, c.row_keys, c.emb, c.w, c.acc_emb, c.acc_w,
+                         c.capacity_rows);
   }
   {
     ProfScope ps(KID_PATCH, s);
-    hipLaunchKernelGGL(k_patch, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows, t->ctrl,
-                       values ? first_idx : (int32_t *)nullptr);
-  }
-  if (values) {
-    ProfScope ps(KID_COPY_VALUES, s);
-    hipLaunchKernelGGL(k_copy_values, dim3(grid_for(n * (c.dim + 1))), dim3(kBlock), 0, s, t->ctrl, c.dim, values,
-                       first_idx, c.emb, c.w, c.acc_emb, c.acc_w, c.capacity_rows);
-  }
-  {
-    ProfScope ps(KID_COMMIT, s);
+    hipLaunchKernelGGL(k_patch, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, n, rows, slot_of);
     hipLaunchKernelGGL(k_commit, dim3(1), dim3(1), 0, s, t->ctrl, c.capacity_rows);
   }
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;

@@ -171,6 +171,7 @@ class Batch:
     offsets: np.ndarray     # [B*F+1] int32; bag (b,f) = entries offsets[b*F+f] .. offsets[b*F+f+1]
     vals: Optional[np.ndarray] = None   # [nnz] float32 feature values; None => all ones
     labels: Optional[np.ndarray] = None  # [B] float32 in {0,1}
+    ranks: Optional[np.ndarray] = None   # [nnz] int64 popularity rank of each entry (non-streaming workloads)
 
     @property
     def nnz(self) -> int:
@@ -217,7 +218,7 @@ def gen_batch(w: Workload, step: int = 0, with_vals: bool = False) -> Batch:
     if with_vals:
         vals = rng.uniform(0.25, 2.0, size=nnz).astype(np.float32)
     labels = (rng.random(w.B) < 0.2).astype(np.float32)
-    return Batch(w.B, w.F, keys, offsets.astype(np.int32), vals, labels)
+    return Batch(w.B, w.F, keys, offsets.astype(np.int32), vals, labels, ranks)
 
 
 class StreamingGenerator:
@@ -225,8 +226,8 @@ class StreamingGenerator:
     ``p_new``, else the ID of an existing row drawn by popularity over the rows known so far.
 
     The generator mirrors the table's row -> key map on the host.  It relies only on the
-    documented row-assignment rule of the table interface (new distinct IDs of one call get
-    consecutive rows in ascending unsigned ID order); it does not look at the table.
+    documented row-assignment rule of the table interface (the unseen distinct IDs of one call
+    get consecutive rows in the order of their first occurrence); it does not look at the table.
     """
 
     _PERM_MULT = 2_654_435_761  # odd; rank -> row through (rank * mult) mod n_rows
@@ -236,8 +237,8 @@ class StreamingGenerator:
             raise ValueError("not a streaming workload")
         self.w = w
         self.step = 0
-        first = scramble64(np.arange(1, w.preinsert + 1, dtype=np.uint64))
-        self.row_keys = np.sort(first)          # rows 0..preinsert-1 in ascending ID order
+        self.row_keys = scramble64(np.arange(1, w.preinsert + 1, dtype=np.uint64))   # distinct: rows 0..preinsert-1
+        self._known_sorted = np.sort(self.row_keys)
 
     def initial_keys(self) -> np.ndarray:
         return self.row_keys.copy()
@@ -255,26 +256,18 @@ class StreamingGenerator:
         keys = self.row_keys[rows]
         fresh = rng.random(nnz) < w.p_new
         n_fresh = int(fresh.sum())
-        new_keys = rng.integers(0, 2**64 - 1, size=n_fresh, dtype=np.uint64)  # excludes the reserved ID
-        keys[fresh] = new_keys
-        # mirror of the table: unseen distinct IDs, ascending, appended as new rows
-        cand = np.unique(new_keys)
-        known = self._sorted_known()
-        pos = np.searchsorted(known, cand)
-        hit = (pos < known.shape[0]) & (known[np.minimum(pos, known.shape[0] - 1)] == cand)
-        add = cand[~hit]
+        keys[fresh] = rng.integers(0, 2**64 - 1, size=n_fresh, dtype=np.uint64)  # excludes the reserved ID
+        # mirror of the table: unseen distinct IDs become new rows in order of first occurrence
+        cand, first = np.unique(keys[fresh], return_index=True)
+        known = self._known_sorted
+        pos = np.minimum(np.searchsorted(known, cand), known.shape[0] - 1)
+        unseen = known[pos] != cand
+        add = cand[unseen][np.argsort(first[unseen], kind="stable")]
         self.row_keys = np.concatenate([self.row_keys, add])
-        self._known_sorted = None
+        self._known_sorted = np.sort(self.row_keys)
         labels = (rng.random(w.B) < 0.2).astype(np.float32)
         self.step += 1
         return Batch(w.B, w.F, keys, offsets.astype(np.int32), None, labels)
-
-    _known_sorted = None
-
-    def _sorted_known(self) -> np.ndarray:
-        if self._known_sorted is None:
-            self._known_sorted = np.sort(self.row_keys)
-        return self._known_sorted
 
 
 def upstream_gradients(w: Workload, step: int = 0, pool: bool = True):

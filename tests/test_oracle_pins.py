@@ -84,9 +84,9 @@ def test_table_against_python_dict(oracle):
             keys = rng.integers(0, 3000, size=700, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15)
         keys = keys[rng.permutation(keys.shape[0])]
         rows = t.insert(keys)
-        new = sorted(set(int(k) for k in keys) - set(ref))          # ascending unsigned order
-        for k in new:
-            ref[k] = len(ref)
+        for k in keys:                                              # the plain sequential insert loop
+            if int(k) not in ref:
+                ref[int(k)] = len(ref)
         assert t.n_rows == len(ref)
         assert [ref[int(k)] for k in keys] == rows.tolist()
     assert sorted(ref.values()) == list(range(len(ref)))              # bijection onto 0..n-1
@@ -100,6 +100,8 @@ def test_table_against_python_dict(oracle):
     assert t.n_rows == n0
     got = t.find(probe, insert_missing=True)                          # one call looks up and grows
     assert got[50:].tolist() == [n0, n0 + 1] and t.n_rows == n0 + 2
+    got = t.find(np.array([9_000_002, 9_000_001, 9_000_002], dtype=np.uint64), insert_missing=True)
+    assert got.tolist() == [n0 + 2, n0 + 3, n0 + 2]                  # first occurrence decides, not key order
 
 
 def test_table_values_first_occurrence_and_init(oracle):
@@ -107,11 +109,11 @@ def test_table_values_first_occurrence_and_init(oracle):
     keys = np.array([50, 40, 50, 60], dtype=np.uint64)
     vals = np.arange(12, dtype=np.float32).reshape(4, 3)
     rows = t.insert(keys, vals)
-    assert rows.tolist() == [1, 0, 1, 2]
-    np.testing.assert_array_equal(t.emb, [[3, 4], [0, 1], [9, 10]])   # key 50 keeps its first values
-    np.testing.assert_array_equal(t.w, [5, 2, 11])
+    assert rows.tolist() == [0, 1, 0, 2]                              # rows in order of first occurrence
+    np.testing.assert_array_equal(t.emb, [[0, 1], [3, 4], [9, 10]])   # key 50 keeps its first values
+    np.testing.assert_array_equal(t.w, [2, 5, 11])
     t.insert(np.array([50], dtype=np.uint64), np.full((1, 3), 99, np.float32))
-    np.testing.assert_array_equal(t.w, [5, 2, 11])                    # existing keys untouched
+    np.testing.assert_array_equal(t.w, [2, 5, 11])                    # existing keys untouched
     r = t.insert(np.array([7], dtype=np.uint64))
     assert r.tolist() == [3]
     assert t.emb[3, 1] == np.float32(oracle.init_value(7, 1, 9, 0.5)) and t.w[3] == np.float32(oracle.init_value(7, 2, 9, 0.5))
