@@ -2,13 +2,16 @@
 //   LR  M1 (Section 4.1, Eq. lr_m1), FM M1 and M2 (Section 4.2, Eq. fm_m1m2) and the per-field
 //   pooled embeddings (Section 4.3).
 //
-// Mapping: 1, 2 or 4 wave64s per sample.  A row of D floats is read by D/4 adjacent lanes as
-// one 16-byte load each, so a wave holds 64/(D/4) "lane groups" that each fetch a different
-// row at the same time.  Every group owns a contiguous range of the sample's bags, walks its
-// entries in CSR order and keeps the running bag sum in registers (the pooled output is
-// written once per bag, already summed over shards).  The per-shard FM / LR partials of the
-// sample live in LDS ([K][D] + 2 [K] doubles per sample) and are updated with LDS atomics,
-// because the entries of one shard are scattered over all groups.
+// Mapping: 1, 2 or 4 wave64s per sample.  A row of D floats is read by G = D/4 adjacent lanes
+// as one 16-byte load each, so a wave holds 64/G "lane groups" that each fetch a different row
+// at the same time.  Every group owns a contiguous range of the sample's bags and walks its
+// entries in CSR order in chunks of G: lane i of the group loads the metadata of entry i of
+// the chunk (row, key -> shard, value, LR weight, bag by binary search in the sample's offsets
+// staged in LDS), the metadata is then broadcast lane by lane with cross-lane shuffles, and the
+// row gathers of a chunk are issued back to back.  The running bag sum stays in registers (the
+// pooled output is written once per bag, already summed over shards).  The per-shard FM / LR
+// partials of the sample live in LDS ([K][D] + 2 [K] doubles per sample) and are updated with
+// LDS atomics, because the entries of one shard are scattered over all groups.
 //
 // Accumulation is in double, inputs and outputs are fp32: a sample's sum of several hundred
 // signed terms cancels, and fp32 accumulation alone would exceed the 1e-5 relative bound
@@ -27,25 +30,51 @@ struct FwdArgs {
   float *P_lr, *P_sum, *P_sq, *pool;
   int64_t B;
   int F, K, policy;
-  int lds_per_sample;   // doubles
+  int acc_doubles;      // LDS doubles per sample for the accumulators
+  int lds_per_sample;   // LDS doubles per sample in total (accumulators + staged offsets)
   int wps;              // waves per sample: 1, 2 or 4
 };
 
 __device__ inline float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ inline void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
 
-template <int D, int U>
+// Cross-lane move of a double with a DPP control word (VALU, does not use the LDS pipe).
+template <int kCtrl>
+__device__ inline double dpp_f64(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, kCtrl, 0xF, 0xF, true);
+  hi = __builtin_amdgcn_update_dpp(0, hi, kCtrl, 0xF, 0xF, true);
+  return __hiloint2double(hi, lo);
+}
+
+// Sum of q over the G adjacent lanes of a lane group (every lane gets the total).
+template <int G>
+__device__ inline double group_sum(double q) {
+  if (G >= 2) q += dpp_f64<0xB1>(q);     // quad_perm [1,0,3,2]
+  if (G >= 4) q += dpp_f64<0x4E>(q);     // quad_perm [2,3,0,1]
+  if (G >= 8) q += dpp_f64<0x141>(q);    // row_half_mirror: pairs the two quads of 8 lanes
+  if (G >= 16) q += dpp_f64<0x140>(q);   // row_mirror: pairs the two halves of 16 lanes
+#pragma unroll
+  for (int m = 16; m < G; m <<= 1) q += __shfl_xor(q, m, kWave);
+  return q;
+}
+
+template <int D>
 __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   extern __shared__ __align__(16) double lds[];
-  constexpr int G = D / 4;            // lanes per row
-  constexpr int NG = kWave / G;       // lane groups per wave
+  constexpr int G = D / 4;                 // lanes per row = entries per chunk
+  constexpr int NG = kWave / G;            // lane groups per wave
+  constexpr int U = G < 8 ? G : 8;         // row gathers in flight per lane
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / G, sub = lane % G;
   const int K = a.K, F = a.F, wps = a.wps;
   const int local = wave / wps, wis = wave % wps;         // sample slot in the workgroup, wave in sample
-  double *sum = lds + (size_t)local * a.lds_per_sample;   // [K][D]
+  // LDS: one 16-byte metadata slot per thread, then per sample the accumulators and offsets
+  int4 *meta = reinterpret_cast<int4 *>(lds) + wave * kWave;
+  double *sum = lds + 2 * kBlock + (size_t)local * a.lds_per_sample;   // [K][D]
   double *sq = sum + (size_t)K * D;                       // [K]
   double *lrp = sq + K;                                   // [K]
+  int *offs = reinterpret_cast<int *>(sum + a.acc_doubles);   // [F+1]
   const int64_t b = (int64_t)blockIdx.x * (kBlock / kWave / wps) + local;
   const bool active = b < a.B;
   const bool need_fm = a.P_sum != nullptr, need_lr = a.P_lr != nullptr, need_pool = a.pool != nullptr;
@@ -53,76 +82,111 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   const bool by_key = a.policy == DES_SHARD_KEY_HASH;
   const int tis = wis * kWave + lane, nts = wps * kWave;  // thread in sample, threads per sample
 
-  for (int i = tis; i < a.lds_per_sample; i += nts) sum[i] = 0.0;
+  for (int i = tis; i < a.acc_doubles; i += nts) sum[i] = 0.0;
+  if (active)
+    for (int i = tis; i <= F; i += nts) offs[i] = a.offsets[b * F + i];
   __syncthreads();
 
   if (active) {
-    const int32_t *off = a.offsets + b * F;
     const int gg = wis * NG + g, ngt = wps * NG;
     const int f0 = (int)(((int64_t)F * gg) / ngt), f1 = (int)(((int64_t)F * (gg + 1)) / ngt);
-    int e = off[f0];
-    const int e1 = off[f1];
-    int f = f0;
-    int bag_end = f < f1 ? off[f + 1] : e1;
+    const int e0 = offs[f0], e1 = offs[f1];
+    int cur = f0;                                         // bag whose sum is being accumulated
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     float *pool_row = need_pool ? a.pool + (b * F) * (int64_t)D + sub * 4 : nullptr;
-    while (e < e1) {
-      int r[U];
-      float x[U], wv[U];
-      float4 v[U];
-      int sh[U];
-#pragma unroll
-      for (int i = 0; i < U; ++i) r[i] = (e + i < e1) ? a.rows[e + i] : -1;
-#pragma unroll
-      for (int i = 0; i < U; ++i) {
-        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        wv[i] = 0.f;
-        x[i] = 1.f;
-        sh[i] = 0;
-        if (r[i] >= 0) {
-          if (need_v) v[i] = ld4(a.emb + (int64_t)r[i] * D + sub * 4);
-          if (need_lr && sub == 0) wv[i] = a.w[r[i]];
-          if (a.vals) x[i] = a.vals[e + i];
-          if (by_key) sh[i] = (int)((uint32_t)(mix64(a.keys[e + i]) >> 32) % (uint32_t)K);
-        }
+
+    // metadata of entry e0 + sub of the first chunk; later chunks are fetched one chunk ahead
+    int r_n = -1;
+    uint64_t key_n = 0;
+    float x_n = 1.f;
+    {
+      const int my = e0 + sub;
+      if (my < e1) {
+        r_n = a.rows[my];
+        if (by_key) key_n = a.keys[my];
+        if (a.vals) x_n = a.vals[my];
       }
-#pragma unroll
-      for (int i = 0; i < U; ++i) {
-        const int ee = e + i;
-        if (ee < e1) {
-          while (ee >= bag_end) {                       // close finished (possibly empty) bags
-            if (need_pool)
-              st4(pool_row + (int64_t)f * D, make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
-            acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
-            ++f;
-            bag_end = off[f + 1];
-          }
-          if (r[i] >= 0) {
-            const int s = by_key ? sh[i] : f % K;
-            const double xd = (double)x[i];
-            const double xv[4] = {xd * (double)v[i].x, xd * (double)v[i].y, xd * (double)v[i].z, xd * (double)v[i].w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) acc[k] += xv[k];
-            if (need_fm) {
-              double *dst = sum + s * D + sub * 4;
-#pragma unroll
-              for (int k = 0; k < 4; ++k) atomicAdd(dst + k, xv[k]);
-              double q = xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
-#pragma unroll
-              for (int m = G / 2; m >= 1; m >>= 1) q += __shfl_xor(q, m, kWave);
-              if (sub == 0) atomicAdd(sq + s, q);
-            }
-            if (need_lr && sub == 0) atomicAdd(lrp + s, xd * (double)wv[i]);
-          }
-        }
-      }
-      e += U;
     }
-    while (f < f1) {                                    // last bag of the range and empty ones after it
+    for (int e = e0; e < e1; e += G) {
+      const int my = e + sub;
+      const int r_l = r_n;
+      const uint64_t key_l = key_n;
+      const float x_l = x_n;
+      {                                                   // prefetch the next chunk's metadata
+        const int nx = my + G;
+        r_n = -1;
+        if (nx < e1) {
+          r_n = a.rows[nx];
+          if (by_key) key_n = a.keys[nx];
+          if (a.vals) x_n = a.vals[nx];
+        }
+      }
+      int bag_l = f0;
+      if (my < e1) {                                      // largest f with offs[f] <= my
+        int lo = f0, hi = f1;
+        while (hi - lo > 1) {
+          const int mid = (lo + hi) >> 1;
+          if (offs[mid] <= my) lo = mid; else hi = mid;
+        }
+        bag_l = lo;
+      }
+      const int sh_l = by_key ? (int)((uint32_t)(mix64(key_l) >> 32) % (uint32_t)K) : bag_l % K;
+      // publish (row, bag, shard, value) of this lane's entry; the group then reads entry j of the
+      // chunk from slot j with one broadcast LDS read.  Same wave, program order: no barrier needed.
+      meta[lane] = make_int4(r_l, bag_l, sh_l, __float_as_int(x_l));
+      const int cnt = min(G, e1 - e);
+#pragma unroll
+      for (int j0 = 0; j0 < G; j0 += U) {
+        if (j0 < cnt) {
+          int4 md[U];
+          float4 v[U];
+          float wv[U];
+#pragma unroll
+          for (int i = 0; i < U; ++i) {
+            md[i] = meta[g * G + j0 + i];
+            v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            wv[i] = 0.f;
+            if (j0 + i < cnt && md[i].x >= 0) {
+              if (need_v) v[i] = ld4(a.emb + (int64_t)md[i].x * D + sub * 4);
+              if (need_lr && sub == 0) wv[i] = a.w[md[i].x];
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < U; ++i) {
+            if (j0 + i < cnt) {
+              const int bag = md[i].y, s = md[i].z;
+              while (cur < bag) {                          // close finished (possibly empty) bags
+                if (need_pool)
+                  st4(pool_row + (int64_t)cur * D,
+                      make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
+                acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
+                ++cur;
+              }
+              if (md[i].x >= 0) {
+                const double xd = (double)__int_as_float(md[i].w);
+                const double xv[4] = {xd * (double)v[i].x, xd * (double)v[i].y, xd * (double)v[i].z,
+                                      xd * (double)v[i].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[k] += xv[k];
+                if (need_fm) {
+                  double *dst = sum + s * D + sub * 4;
+#pragma unroll
+                  for (int k = 0; k < 4; ++k) atomicAdd(dst + k, xv[k]);
+                  const double q = group_sum<G>(xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3]);
+                  if (sub == 0) atomicAdd(sq + s, q);
+                }
+                if (need_lr && sub == 0) atomicAdd(lrp + s, xd * (double)wv[i]);
+              }
+            }
+          }
+        }
+      }
+    }
+    while (cur < f1) {                                    // last bag of the range and empty ones after it
       if (need_pool)
-        st4(pool_row + (int64_t)f * D, make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
+        st4(pool_row + (int64_t)cur * D, make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
       acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
-      ++f;
+      ++cur;
     }
   }
   __syncthreads();
@@ -176,7 +240,7 @@ FwdArgs make_args(des_table *t, const des_batch_t *b, const int32_t *rows) {
   a.keys = b->keys; a.offsets = b->offsets; a.vals = b->vals; a.rows = rows;
   a.P_lr = a.P_sum = a.P_sq = a.pool = nullptr;
   a.B = b->B; a.F = b->F; a.K = t->cfg.num_shards; a.policy = t->cfg.shard_policy;
-  a.lds_per_sample = 0; a.wps = 1;
+  a.acc_doubles = 0; a.lds_per_sample = 0; a.wps = 1;
   return a;
 }
 
@@ -188,10 +252,13 @@ des_status_t forward_launch(des_table *t, const des_batch_t *b, const int32_t *r
   FwdArgs a = make_args(t, b, rows);
   a.P_lr = P_lr; a.P_sum = P_sum; a.P_sq = P_sq; a.pool = pool;
   const int D = t->cfg.dim;
-  // LDS per sample: K*(D+2) doubles.  Fewer samples per workgroup (more waves per sample) when
-  // that is large, so that a CU still holds several workgroups.
-  const int64_t per_sample = (int64_t)align_up((size_t)a.K * (D + 2), 2);
-  if (per_sample * 8 > 65536) return DES_ERR_INVALID_ARG;   // num_shards*(dim+2) doubles must fit 64 KB of LDS
+  // LDS per sample: K*(D+2) doubles of accumulators plus the sample's F+1 offsets.  Fewer
+  // samples per workgroup (more waves per sample) when that is large, so that a CU still holds
+  // several workgroups.
+  const int64_t acc_doubles = (int64_t)align_up((size_t)a.K * (D + 2), 2);
+  const int64_t per_sample = acc_doubles + ((int64_t)b->F + 2) / 2;
+  if (per_sample * 8 + 16 * kBlock > 65536) return DES_ERR_INVALID_ARG;   // K*(dim+2) doubles + F+1 ints + 4 KB must fit 64 KB of LDS
+  a.acc_doubles = (int)acc_doubles;
   a.lds_per_sample = (int)per_sample;
   int wps = 1;
   while (wps < 4 && (kBlock / kWave / wps) * per_sample * 8 > 40 * 1024) wps *= 2;
@@ -200,16 +267,16 @@ des_status_t forward_launch(des_table *t, const des_batch_t *b, const int32_t *r
   a.wps = wps;
   const int spb = kBlock / kWave / wps;
   const dim3 grid((unsigned)((b->B + spb - 1) / spb)), block(kBlock);
-  const size_t shmem = (size_t)per_sample * 8 * spb;
+  const size_t shmem = 16 * (size_t)kBlock + (size_t)per_sample * 8 * spb;
   ProfScope ps(KID_FORWARD, s);
   switch (D) {
-    case 4: hipLaunchKernelGGL((k_forward<4, 4>), grid, block, shmem, s, a); break;
-    case 8: hipLaunchKernelGGL((k_forward<8, 4>), grid, block, shmem, s, a); break;
-    case 16: hipLaunchKernelGGL((k_forward<16, 4>), grid, block, shmem, s, a); break;
-    case 32: hipLaunchKernelGGL((k_forward<32, 4>), grid, block, shmem, s, a); break;
-    case 64: hipLaunchKernelGGL((k_forward<64, 4>), grid, block, shmem, s, a); break;
-    case 128: hipLaunchKernelGGL((k_forward<128, 4>), grid, block, shmem, s, a); break;
-    case 256: hipLaunchKernelGGL((k_forward<256, 4>), grid, block, shmem, s, a); break;
+    case 4: hipLaunchKernelGGL(k_forward<4>, grid, block, shmem, s, a); break;
+    case 8: hipLaunchKernelGGL(k_forward<8>, grid, block, shmem, s, a); break;
+    case 16: hipLaunchKernelGGL(k_forward<16>, grid, block, shmem, s, a); break;
+    case 32: hipLaunchKernelGGL(k_forward<32>, grid, block, shmem, s, a); break;
+    case 64: hipLaunchKernelGGL(k_forward<64>, grid, block, shmem, s, a); break;
+    case 128: hipLaunchKernelGGL(k_forward<128>, grid, block, shmem, s, a); break;
+    case 256: hipLaunchKernelGGL(k_forward<256>, grid, block, shmem, s, a); break;
     default: return DES_ERR_INVALID_ARG;
   }
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
