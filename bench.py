@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--cpu-samples", type=int, default=2048)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference reading for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (K logical shards on one device); --gpus must be 1",
@@ -126,8 +128,12 @@ def main():
     opt = des.OPT_SGD if w.opt == "sgd" else des.OPT_ADAGRAD
     state_mult = 1 if w.opt == "sgd" else 2
     total_steps = args.warmup + args.steps
-    n_batches = args.batches or (total_steps if streaming else (2 if w.index == 4 and args.scale == 1.0 else 8))
-    n_batches = min(n_batches, total_steps) if not streaming else total_steps
+    # streaming: every step needs its own batch (the table grows), and the per-kernel pass runs on
+    # the batches after the timed ones
+    n_batches = args.batches or (2 if w.index == 4 and args.scale == 1.0 else 8)
+    n_batches = min(n_batches, total_steps)
+    if streaming:
+        n_batches = total_steps + (0 if args.no_kernel_pass else args.steps)
 
     # ---- inputs (host generation, then resident in HBM) --------------------------------------
     t_setup = time.perf_counter()
@@ -188,6 +194,14 @@ def main():
             table.backward_update_adagrad(b, r, w.lr, eps, g_lr, g_fm, A_sum, g_pool, dbg=dbg)
         return b.nnz
 
+    if args.calib_copy_mib:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                    # the plain copy kernel of known size: reads and writes calib_copy_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- timed region ---------------------------------------------------------------------------
     for i in range(args.warmup):
         step(i)
@@ -204,13 +218,14 @@ def main():
 
     # ---- per-kernel pass: same steps again, HIP events on the launch stream around every launch --
     kernels, roof = {}, None
-    if not args.no_kernel_pass and not streaming:
+    if not args.no_kernel_pass:
+        first = total_steps if streaming else args.warmup
         des.profile_enable(True)
-        for i in range(args.warmup, total_steps):
+        for i in range(first, first + args.steps):
             step(i)
         prof = des.profile_read()
         des.profile_enable(False)
-        used = sorted({i % len(batches) for i in range(args.warmup, total_steps)})
+        used = sorted({i % len(batches) for i in range(first, first + args.steps)})
         stats = [batch_stats(host_batches[i].keys) for i in used[:2]]
         st = {k: float(np.mean([s[k] for s in stats])) for k in stats[0]}
         cap_bits = max(1, int(w.capacity).bit_length())

@@ -43,6 +43,7 @@ struct BwdArgs {
   int32_t *bag_of;      // entry -> bag, only with vals
   int32_t *seg_off;     // [n+1]
   int32_t *uniq_rows;   // [n]
+  uint32_t *first_pay;  // [n]  payload of the first entry of each segment
   uint32_t *head_sums;
   int32_t *long_seg;    // segment index of long segment j
   uint32_t *long_c0;    // first chunk of long segment j
@@ -174,6 +175,7 @@ __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
       if (flag[i]) {
         a.uniq_rows[u] = (int32_t)key[i];
         a.seg_off[u] = (int32_t)idx;
+        a.first_pay[u] = a.pay_sorted[idx];
         ++u;
       }
       // end of the last segment: first entry without a row, or the end of the array
@@ -284,16 +286,38 @@ __device__ inline void reduce_entries(const BwdArgs &a, int i0, int i1, int sub,
   }
 }
 
-// Apply the merged gradient of one row.  Lane `sub` owns columns 4*sub..4*sub+3; sub 0 also owns
-// the LR weight.  Reads the pre-update weights.  The merged gradient is formed in double and
-// rounded once; the optimizer arithmetic itself is well conditioned and runs in fp32.
+// Pre-update state of one row as seen by the lane that owns columns 4*sub..4*sub+3 (sub 0 also
+// owns the LR weight).  Loaded before the gradient reduction so that the row's memory latency
+// overlaps the gathers of the upstream gradients.
+struct RowState {
+  float4 v, s;      // latent columns and their Adagrad accumulators
+  float w, aw;      // LR weight and its accumulator
+};
+
 template <int D>
-__device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, const Acc &acc) {
-  float *vp = a.emb + (int64_t)row * D + sub * 4;
-  const float4 v = ld4(vp);
+__device__ inline RowState load_row(const BwdArgs &a, int row, int sub) {
+  RowState st;
+  st.v = ld4(a.emb + (int64_t)row * D + sub * 4);
+  st.s = f4zero();
+  st.w = 0.f;
+  st.aw = 0.f;
+  if (a.opt == DES_OPT_ADAGRAD) st.s = ld4(a.acc_emb + (int64_t)row * D + sub * 4);
+  if (sub == 0 && a.opt != DES_OPT_NONE) {
+    st.w = a.w[row];
+    if (a.opt == DES_OPT_ADAGRAD) st.aw = a.acc_w[row];
+  }
+  return st;
+}
+
+// Apply the merged gradient of one row.  The merged gradient is formed in double and rounded
+// once; the optimizer arithmetic itself is well conditioned and runs in fp32.
+template <int D>
+__device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, const RowState &st, const Acc &acc) {
+  const float4 v = st.v;
   const float4 G = make_float4((float)(acc.v[0] - (double)v.x * acc.s2), (float)(acc.v[1] - (double)v.y * acc.s2),
                                (float)(acc.v[2] - (double)v.z * acc.s2), (float)(acc.v[3] - (double)v.w * acc.s2));
   const float gw = (float)acc.gw;
+  float *vp = a.emb + (int64_t)row * D + sub * 4;
   if (a.merged_out) {
     float *m = a.merged_out + u * (D + 1) + sub * 4;
     m[0] = G.x; m[1] = G.y; m[2] = G.z; m[3] = G.w;
@@ -301,23 +325,47 @@ __device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, 
   }
   if (a.opt == DES_OPT_SGD) {
     st4(vp, make_float4(v.x - a.lr * G.x, v.y - a.lr * G.y, v.z - a.lr * G.z, v.w - a.lr * G.w));
-    if (sub == 0) a.w[row] = a.w[row] - a.lr * gw;
+    if (sub == 0) a.w[row] = st.w - a.lr * gw;
   } else if (a.opt == DES_OPT_ADAGRAD) {
-    float *ap = a.acc_emb + (int64_t)row * D + sub * 4;
-    float4 s = ld4(ap);
+    float4 s = st.s;
     s.x += G.x * G.x; s.y += G.y * G.y; s.z += G.z * G.z; s.w += G.w * G.w;
-    st4(ap, s);
+    st4(a.acc_emb + (int64_t)row * D + sub * 4, s);
     st4(vp, make_float4(v.x - a.lr * G.x / (sqrtf(s.x) + a.eps), v.y - a.lr * G.y / (sqrtf(s.y) + a.eps),
                         v.z - a.lr * G.z / (sqrtf(s.z) + a.eps), v.w - a.lr * G.w / (sqrtf(s.w) + a.eps)));
     if (sub == 0) {
-      const float aw = a.acc_w[row] + gw * gw;
+      const float aw = st.aw + gw * gw;
       a.acc_w[row] = aw;
-      a.w[row] = a.w[row] - a.lr * gw / (sqrtf(aw) + a.eps);
+      a.w[row] = st.w - a.lr * gw / (sqrtf(aw) + a.eps);
     }
   }
 }
 
-// (4a) one lane group per segment; long segments are left to the chunked path
+// Terms of one entry with payload p (bag, or entry index when feature values are present).
+template <int D, bool kHasVals>
+__device__ inline void add_entry(const BwdArgs &a, uint32_t p, int sub, Acc &acc) {
+  float x = 1.f;
+  if (kHasVals) {
+    x = a.vals[p];
+    p = (uint32_t)a.bag_of[p];
+  }
+  const uint32_t b = p / (uint32_t)a.F;
+  const float4 gp = a.g_pool ? ld4(a.g_pool + (int64_t)p * D + sub * 4) : f4zero();
+  const float4 as = a.g_fm ? ld4(a.A_sum + (int64_t)b * D + sub * 4) : f4zero();
+  const float gf = a.g_fm ? a.g_fm[b] : 0.f;
+  const float gl = a.g_lr ? a.g_lr[b] : 0.f;
+  const double xd = (double)x;
+  const double xg = xd * (double)gf;
+  acc.v[0] += xd * (double)gp.x + xg * (double)as.x;
+  acc.v[1] += xd * (double)gp.y + xg * (double)as.y;
+  acc.v[2] += xd * (double)gp.z + xg * (double)as.z;
+  acc.v[3] += xd * (double)gp.w + xg * (double)as.w;
+  acc.s2 += xd * xg;
+  acc.gw += xd * (double)gl;
+}
+
+// (4a) one lane group per segment; long segments are left to the chunked path.  The segment's
+// bounds, row and first payload arrive together; the row state and the first entry's upstream
+// gradients are then fetched together, so a one-entry segment costs two memory round trips.
 template <int D, bool kHasVals>
 __global__ __launch_bounds__(kBlock) void k_short_update(const BwdArgs a) {
   constexpr int G = D / 4;
@@ -326,10 +374,14 @@ __global__ __launch_bounds__(kBlock) void k_short_update(const BwdArgs a) {
   const int sub = (int)(gid % G);
   if (u >= a.ctrl->n_uniq) return;
   const int i0 = a.seg_off[u], i1 = a.seg_off[u + 1];
+  const int row = a.uniq_rows[u];
+  const uint32_t p0 = a.first_pay[u];
   if (i1 - i0 > kShortMax) return;
+  const RowState st = load_row<D>(a, row, sub);
   Acc acc = acc_zero();
-  reduce_entries<D, kHasVals>(a, i0, i1, sub, acc);
-  apply_row<D>(a, u, a.uniq_rows[u], sub, acc);
+  add_entry<D, kHasVals>(a, p0, sub, acc);
+  reduce_entries<D, kHasVals>(a, i0 + 1, i1, sub, acc);
+  apply_row<D>(a, u, row, sub, st, acc);
 }
 
 // (4b) one wave per chunk of a long segment: the chunk is split evenly over the wave's lane
@@ -408,7 +460,8 @@ __global__ __launch_bounds__(kBlock) void k_long_final(const BwdArgs a) {
       for (int k = 0; k < 4; ++k) tot.v[k] = red[0][sub * 4 + k];
       tot.s2 = red[0][D];
       tot.gw = red[0][D + 1];
-      apply_row<D>(a, u, a.uniq_rows[u], sub, tot);
+      const int row = a.uniq_rows[u];
+      apply_row<D>(a, u, row, sub, load_row<D>(a, row, sub), tot);
     }
     __syncthreads();
   }
@@ -459,7 +512,7 @@ void launch_update_v(const BwdArgs &a, hipStream_t s) {
 }
 
 struct Layout {
-  size_t key_a, key_b, pay_a, pay_b, bag_of, seg_off, uniq_rows, head_sums, long_seg, long_c0, chunk_owner, partials,
+  size_t key_a, key_b, pay_a, pay_b, bag_of, seg_off, uniq_rows, first_pay, head_sums, long_seg, long_c0, chunk_owner, partials,
       sort_scratch, total;
 };
 
@@ -471,7 +524,7 @@ Layout layout_for(int D, int64_t n) {
   auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
   L.key_a = take(m * 4); L.key_b = take(m * 4); L.pay_a = take(m * 4); L.pay_b = take(m * 4);
   L.bag_of = take(m * 4);
-  L.seg_off = take((m + 1) * 4); L.uniq_rows = take(m * 4);
+  L.seg_off = take((m + 1) * 4); L.uniq_rows = take(m * 4); L.first_pay = take(m * 4);
   L.head_sums = take(((m + kHeadTile - 1) / kHeadTile + 1) * 4);
   L.long_seg = take(max_long * 4); L.long_c0 = take(max_long * 4);
   L.chunk_owner = take(max_chunks * 4);
@@ -510,6 +563,7 @@ des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *
   a.row_keys = t->cfg.row_keys; a.ctrl = t->ctrl;
   a.bag_of = (int32_t *)(ws + L.bag_of);
   a.seg_off = (int32_t *)(ws + L.seg_off); a.uniq_rows = (int32_t *)(ws + L.uniq_rows);
+  a.first_pay = (uint32_t *)(ws + L.first_pay);
   a.head_sums = (uint32_t *)(ws + L.head_sums);
   a.long_seg = (int32_t *)(ws + L.long_seg); a.long_c0 = (uint32_t *)(ws + L.long_c0);
   a.chunk_owner = (int32_t *)(ws + L.chunk_owner); a.partials = (double *)(ws + L.partials);

@@ -10,8 +10,11 @@
 // staged in LDS), the metadata is then broadcast lane by lane with cross-lane shuffles, and the
 // row gathers of a chunk are issued back to back.  The running bag sum stays in registers (the
 // pooled output is written once per bag, already summed over shards).  The per-shard FM / LR
-// partials of the sample live in LDS ([K][D] + 2 [K] doubles per sample) and are updated with
-// LDS atomics, because the entries of one shard are scattered over all groups.
+// partials of the sample live in LDS ([K][D+2] doubles per sample: D columns, then the sum of
+// squares and the LR sum) and are updated with LDS atomics, because the entries of one shard are
+// scattered over all groups.  A lane owns columns 4*sub..4*sub+3 of a row but the LDS copy is
+// stored column-permuted (column 4*sub+k at k*G+sub) with a row pitch of D+2 doubles, so that the
+// 64 lanes of one atomic instruction spread over the LDS banks instead of piling onto a few.
 //
 // Accumulation is in double, inputs and outputs are fp32: a sample's sum of several hundred
 // signed terms cancels, and fp32 accumulation alone would exceed the 1e-5 relative bound
@@ -71,9 +74,8 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   const int local = wave / wps, wis = wave % wps;         // sample slot in the workgroup, wave in sample
   // LDS: one 16-byte metadata slot per thread, then per sample the accumulators and offsets
   int4 *meta = reinterpret_cast<int4 *>(lds) + wave * kWave;
-  double *sum = lds + 2 * kBlock + (size_t)local * a.lds_per_sample;   // [K][D]
-  double *sq = sum + (size_t)K * D;                       // [K]
-  double *lrp = sq + K;                                   // [K]
+  constexpr int P = D + 2;                                // row pitch: D columns, sum of squares, LR sum
+  double *sum = lds + 2 * kBlock + (size_t)local * a.lds_per_sample;   // [K][P]
   int *offs = reinterpret_cast<int *>(sum + a.acc_doubles);   // [F+1]
   const int64_t b = (int64_t)blockIdx.x * (kBlock / kWave / wps) + local;
   const bool active = b < a.B;
@@ -169,13 +171,13 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) acc[k] += xv[k];
                 if (need_fm) {
-                  double *dst = sum + s * D + sub * 4;
+                  double *dst = sum + s * P + sub;
 #pragma unroll
-                  for (int k = 0; k < 4; ++k) atomicAdd(dst + k, xv[k]);
+                  for (int k = 0; k < 4; ++k) atomicAdd(dst + k * G, xv[k]);
                   const double q = group_sum<G>(xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3]);
-                  if (sub == 0) atomicAdd(sq + s, q);
+                  if (sub == 0) atomicAdd(sum + s * P + D, q);
                 }
-                if (need_lr && sub == 0) atomicAdd(lrp + s, xd * (double)wv[i]);
+                if (need_lr && sub == 0) atomicAdd(sum + s * P + D + 1, xd * (double)wv[i]);
               }
             }
           }
@@ -194,14 +196,15 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   if (active) {
     if (need_fm) {
       for (int idx = tis * 4; idx < K * D; idx += nts * 4) {
-        const int s = idx / D, d = idx % D;
+        const int s = idx / D, d = idx % D;                 // d = 4*sub: columns d..d+3 sit at k*G + sub
+        const double *row = sum + s * P + d / 4;
         st4(a.P_sum + ((int64_t)s * a.B + b) * D + d,
-            make_float4((float)sum[idx], (float)sum[idx + 1], (float)sum[idx + 2], (float)sum[idx + 3]));
+            make_float4((float)row[0], (float)row[G], (float)row[2 * G], (float)row[3 * G]));
       }
-      for (int s = tis; s < K; s += nts) a.P_sq[(int64_t)s * a.B + b] = (float)sq[s];
+      for (int s = tis; s < K; s += nts) a.P_sq[(int64_t)s * a.B + b] = (float)sum[s * P + D];
     }
     if (need_lr)
-      for (int s = tis; s < K; s += nts) a.P_lr[(int64_t)s * a.B + b] = (float)lrp[s];
+      for (int s = tis; s < K; s += nts) a.P_lr[(int64_t)s * a.B + b] = (float)sum[s * P + D + 1];
   }
 }
 

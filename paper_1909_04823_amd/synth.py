@@ -209,10 +209,14 @@ def gen_batch(w: Workload, step: int = 0, with_vals: bool = False) -> Batch:
     if w.zipf_a is None:
         ranks = rng.integers(1, w.key_space + 1, size=nnz, dtype=np.int64)
     else:
-        ranks = zipf_truncated(rng, w.zipf_a, w.key_space, nnz)
         if w.uniform_mix > 0.0:
             uni = rng.random(nnz) < w.uniform_mix
-            ranks[uni] = rng.integers(1, w.preinsert + 1, size=int(uni.sum()), dtype=np.int64)
+            n_uni = int(uni.sum())
+            ranks = np.empty(nnz, dtype=np.int64)
+            ranks[uni] = rng.integers(1, w.preinsert + 1, size=n_uni, dtype=np.int64)
+            ranks[~uni] = zipf_truncated(rng, w.zipf_a, w.key_space, nnz - n_uni)
+        else:
+            ranks = zipf_truncated(rng, w.zipf_a, w.key_space, nnz)
     keys = w.rank_to_key(ranks.astype(np.uint64))
     vals = None
     if with_vals:
