@@ -62,6 +62,17 @@ struct BwdArgs {
 
 __device__ inline float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ inline void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+// Streaming variants for data that is touched once per call (table rows of one-entry segments,
+// upstream gradient rows): they do not displace the reusable lines in the caches.
+typedef float v4f __attribute__((ext_vector_type(4)));
+__device__ inline float4 ld4_stream(const float *p) {
+  const v4f r = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+  return make_float4(r.x, r.y, r.z, r.w);
+}
+__device__ inline void st4_stream(float *p, float4 v) {
+  v4f r; r.x = v.x; r.y = v.y; r.z = v.z; r.w = v.w;
+  __builtin_nontemporal_store(r, reinterpret_cast<v4f *>(p));
+}
 __device__ inline float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
 __device__ inline float4 f4add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
@@ -244,9 +255,8 @@ struct Acc {
 };
 __device__ inline Acc acc_zero() { Acc r; r.v[0] = r.v[1] = r.v[2] = r.v[3] = 0.0; r.s2 = 0.0; r.gw = 0.0; return r; }
 
-template <int D, bool kHasVals>
+template <int D, bool kHasVals, int U>
 __device__ inline void reduce_entries(const BwdArgs &a, int i0, int i1, int sub, Acc &acc) {
-  constexpr int U = 4;
   for (int i = i0; i < i1; i += U) {
     uint32_t bag[U];
     bool live[U];
@@ -297,11 +307,11 @@ struct RowState {
 template <int D>
 __device__ inline RowState load_row(const BwdArgs &a, int row, int sub) {
   RowState st;
-  st.v = ld4(a.emb + (int64_t)row * D + sub * 4);
+  st.v = ld4_stream(a.emb + (int64_t)row * D + sub * 4);
   st.s = f4zero();
   st.w = 0.f;
   st.aw = 0.f;
-  if (a.opt == DES_OPT_ADAGRAD) st.s = ld4(a.acc_emb + (int64_t)row * D + sub * 4);
+  if (a.opt == DES_OPT_ADAGRAD) st.s = ld4_stream(a.acc_emb + (int64_t)row * D + sub * 4);
   if (sub == 0 && a.opt != DES_OPT_NONE) {
     st.w = a.w[row];
     if (a.opt == DES_OPT_ADAGRAD) st.aw = a.acc_w[row];
@@ -324,13 +334,13 @@ __device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, 
     if (sub == 0) a.merged_out[u * (D + 1) + D] = gw;
   }
   if (a.opt == DES_OPT_SGD) {
-    st4(vp, make_float4(v.x - a.lr * G.x, v.y - a.lr * G.y, v.z - a.lr * G.z, v.w - a.lr * G.w));
+    st4_stream(vp, make_float4(v.x - a.lr * G.x, v.y - a.lr * G.y, v.z - a.lr * G.z, v.w - a.lr * G.w));
     if (sub == 0) a.w[row] = st.w - a.lr * gw;
   } else if (a.opt == DES_OPT_ADAGRAD) {
     float4 s = st.s;
     s.x += G.x * G.x; s.y += G.y * G.y; s.z += G.z * G.z; s.w += G.w * G.w;
-    st4(a.acc_emb + (int64_t)row * D + sub * 4, s);
-    st4(vp, make_float4(v.x - a.lr * G.x / (sqrtf(s.x) + a.eps), v.y - a.lr * G.y / (sqrtf(s.y) + a.eps),
+    st4_stream(a.acc_emb + (int64_t)row * D + sub * 4, s);
+    st4_stream(vp, make_float4(v.x - a.lr * G.x / (sqrtf(s.x) + a.eps), v.y - a.lr * G.y / (sqrtf(s.y) + a.eps),
                         v.z - a.lr * G.z / (sqrtf(s.z) + a.eps), v.w - a.lr * G.w / (sqrtf(s.w) + a.eps)));
     if (sub == 0) {
       const float aw = st.aw + gw * gw;
@@ -349,7 +359,7 @@ __device__ inline void add_entry(const BwdArgs &a, uint32_t p, int sub, Acc &acc
     p = (uint32_t)a.bag_of[p];
   }
   const uint32_t b = p / (uint32_t)a.F;
-  const float4 gp = a.g_pool ? ld4(a.g_pool + (int64_t)p * D + sub * 4) : f4zero();
+  const float4 gp = a.g_pool ? ld4_stream(a.g_pool + (int64_t)p * D + sub * 4) : f4zero();
   const float4 as = a.g_fm ? ld4(a.A_sum + (int64_t)b * D + sub * 4) : f4zero();
   const float gf = a.g_fm ? a.g_fm[b] : 0.f;
   const float gl = a.g_lr ? a.g_lr[b] : 0.f;
@@ -380,7 +390,7 @@ __global__ __launch_bounds__(kBlock) void k_short_update(const BwdArgs a) {
   const RowState st = load_row<D>(a, row, sub);
   Acc acc = acc_zero();
   add_entry<D, kHasVals>(a, p0, sub, acc);
-  reduce_entries<D, kHasVals>(a, i0 + 1, i1, sub, acc);
+  reduce_entries<D, kHasVals, 2>(a, i0 + 1, i1, sub, acc);
   apply_row<D>(a, u, row, sub, st, acc);
 }
 
@@ -402,7 +412,7 @@ __global__ __launch_bounds__(kBlock) void k_long_partial(const BwdArgs a) {
   const int per = (c_hi - c_lo + NG - 1) / NG;
   const int i0 = min(c_lo + g * per, c_hi), i1 = min(i0 + per, c_hi);
   Acc acc = acc_zero();
-  reduce_entries<D, kHasVals>(a, i0, i1, sub, acc);
+  reduce_entries<D, kHasVals, 4>(a, i0, i1, sub, acc);
 #pragma unroll
   for (int m = G; m < kWave; m <<= 1) {
 #pragma unroll
