@@ -63,6 +63,27 @@ def algorithmic_bytes(w, nnz, st, sort_passes, state_mult):
     }
 
 
+PROFILE_TAG = {0: "tiny_lr_fm", 1: "dlrm_pooled", 2: "deepfm", 3: "streaming", 4: "large_table"}
+
+
+def measured_traffic(index: int, label: str):
+    """HBM bytes per launch of kernel `label` from the committed rocprofv3 counter summary of this
+    workload (profiles/<tag>_hbm_traffic.md, columns fetch MB / write MB), or None."""
+    path = os.path.join(ROOT, "profiles", f"{PROFILE_TAG[index]}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    total, seen = 0.0, False
+    for line in open(path):
+        cells = [c.strip() for c in line.split("|")]
+        if len(cells) >= 6 and cells[2] == label:
+            try:
+                total += (float(cells[3]) + float(cells[4])) * 1e6
+                seen = True
+            except ValueError:
+                pass
+    return int(total) if seen else None
+
+
 def cpu_baseline(w, batch, sample_B, opt_code):
     """The oracle, as it stands, on the first `sample_B` samples of batch 0 with a table that
     holds exactly the IDs those samples touch (pre-inserted head with initialiser weights; the
@@ -244,7 +265,8 @@ def main():
         per_launch_s = kernels[dom]["ms_per_step"] * 1e-3 / lps
         achieved = per_launch_bytes / per_launch_s / 1e9
         roof = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": measured_traffic(w.index, dom) if args.scale == 1.0 else None,
                 "algorithmic_bytes_per_launch": int(per_launch_bytes), "avg_launch_ms": round(per_launch_s * 1e3, 4),
                 "distinct_rows_per_step": st["U"], "kernel_ms_sum_per_step": round(sum(v["ms_per_step"] for v in kernels.values()), 4)}
 
