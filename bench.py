@@ -28,11 +28,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def batch_stats(keys: np.ndarray, chunk: int = 32):
-    """Input statistics the byte model needs: distinct keys and how the entries split into
-    short (<= chunk occurrences) and long merge segments."""
+def batch_stats(keys: np.ndarray, short_max: int = 32, chunk: int = 512):
+    """Input statistics the byte model needs: distinct keys and how the entries split into short
+    (<= short_max occurrences) and long merge segments (cut into chunks of `chunk` entries)."""
     _, counts = np.unique(keys, return_counts=True)
-    long_ = counts > chunk
+    long_ = counts > short_max
     return {
         "U": int(counts.size), "U_long": int(long_.sum()), "U_short": int((~long_).sum()),
         "n_long": int(counts[long_].sum()), "n_short": int(counts[~long_].sum()),
@@ -125,10 +125,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations (0-4)")
+    ap.add_argument("--config", type=int, default=4, help="index into the benchmark configurations (0-4)")
+    ap.add_argument("--also", type=str, default=None,
+                    help="comma-separated further configurations measured after the main one and reported under "
+                         "\"also\" (default: 2 when the main one is 4; \"none\" to skip)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--batches", type=int, default=0, help="distinct pre-generated batches (default 8, fewer for huge ones)")
-    ap.add_argument("--cpu-samples", type=int, default=2048)
+    ap.add_argument("--cpu-lookups", type=float, default=1e7,
+                    help="size of the oracle's timed sample, in lookups (about 10 s of single-thread CPU work)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -140,11 +144,25 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_1909_04823_amd import des, synth
-
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
-    w = synth.workload(args.config, scale=args.scale)
+    out = run_workload(args, args.config, cpu=not args.no_cpu)
+    also = args.also if args.also is not None else ("2" if args.config == 4 and args.scale == 1.0 else "none")
+    if also != "none":
+        out["also"] = []
+        for idx in [int(x) for x in also.split(",") if x.strip()]:
+            torch.cuda.empty_cache()
+            r = run_workload(args, idx, cpu=False)
+            out["also"].append({k: r[k] for k in ("value", "unit", "samples_per_s", "ms_per_step", "steps", "warmup",
+                                                  "config", "roofline", "kernels")})
+    print(json.dumps(out))
+
+
+def run_workload(args, index, cpu):
+    import torch
+    from paper_1909_04823_amd import des, synth
+
+    w = synth.workload(index, scale=args.scale)
     streaming = bool(w.p_new)
     opt = des.OPT_SGD if w.opt == "sgd" else des.OPT_ADAGRAD
     state_mult = 1 if w.opt == "sgd" else 2
@@ -250,7 +268,7 @@ def main():
         stats = [batch_stats(host_batches[i].keys) for i in used[:2]]
         st = {k: float(np.mean([s[k] for s in stats])) for k in stats[0]}
         cap_bits = max(1, int(w.capacity).bit_length())
-        sort_passes = (cap_bits + 7) // 8
+        sort_passes = (cap_bits + 8) // 9
         nnz_mean = lookups / args.steps
         model = algorithmic_bytes(w, nnz_mean, st, sort_passes, state_mult)
         for name, (launches, total_ms) in prof.items():
@@ -270,9 +288,10 @@ def main():
                 "algorithmic_bytes_per_launch": int(per_launch_bytes), "avg_launch_ms": round(per_launch_s * 1e3, 4),
                 "distinct_rows_per_step": st["U"], "kernel_ms_sum_per_step": round(sum(v["ms_per_step"] for v in kernels.values()), 4)}
 
-    cpu = None
-    if not args.no_cpu:
-        cpu = cpu_baseline(w, host_batches[0], args.cpu_samples, 1 if w.opt == "sgd" else 2)
+    cpu_res = None
+    if cpu:
+        n_cpu = max(1, min(B, int(np.ceil(args.cpu_lookups / max(1.0, host_batches[0].nnz / B)))))
+        cpu_res = cpu_baseline(w, host_batches[0], n_cpu, 1 if w.opt == "sgd" else 2)
 
     out = {
         "metric": "sparse lookups/sec, DES fwd+bwd step (samples/sec alongside)",
@@ -284,9 +303,11 @@ def main():
                    "B": B, "F": F, "D": D, "K": K, "optimizer": w.opt, "nnz_per_step": lookups / args.steps,
                    "table_rows": rows_before, "table_rows_after": table.size(), "distinct_batches": len(batches),
                    "find_policy": "insert" if miss == des.MISS_INSERT else "lookup", "setup_s": round(setup_s, 1)},
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
-    print(json.dumps(out))
+    table.close()
+    del table, batches, pool, P_sum, g_pool
+    return out
 
 
 if __name__ == "__main__":

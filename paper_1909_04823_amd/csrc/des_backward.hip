@@ -76,18 +76,30 @@ __device__ inline void st4_stream(float *p, float4 v) {
 __device__ inline float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
 __device__ inline float4 f4add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
-// (1) one thread per bag: sort key = row (or `missing`), payload = bag (or entry index with vals)
+// (1) sort key = row (or `missing`), payload = bag (or entry index with vals).  A workgroup takes
+// kBlock consecutive bags, i.e. one contiguous range of entries, stages their offsets in LDS and
+// walks the entries with consecutive threads (coalesced reads and writes); the bag of an entry
+// is found by binary search in the staged offsets.
 template <bool kHasVals>
 __global__ __launch_bounds__(kBlock) void k_expand(const BwdArgs a, uint32_t *__restrict__ key_out,
                                                     uint32_t *__restrict__ pay_out) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t bag = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; bag < a.nbags; bag += stride) {
-    const int e0 = a.offsets[bag], e1 = a.offsets[bag + 1];
-    for (int e = e0; e < e1; ++e) {
+  __shared__ int offs[kBlock + 1];
+  for (int64_t bag0 = (int64_t)blockIdx.x * kBlock; bag0 < a.nbags; bag0 += (int64_t)gridDim.x * kBlock) {
+    const int nb = (int)min((int64_t)kBlock, a.nbags - bag0);
+    __syncthreads();
+    for (int i = threadIdx.x; i <= nb; i += kBlock) offs[i] = a.offsets[bag0 + i];
+    __syncthreads();
+    const int e0 = offs[0], e1 = offs[nb];
+    for (int e = e0 + threadIdx.x; e < e1; e += kBlock) {
+      int lo = 0, hi = nb;                              // largest i with offs[i] <= e
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (offs[mid] <= e) lo = mid; else hi = mid;
+      }
       const int r = a.rows[e];
       key_out[e] = r >= 0 ? (uint32_t)r : a.missing;
-      pay_out[e] = kHasVals ? (uint32_t)e : (uint32_t)bag;
-      if (kHasVals) a.bag_of[e] = (int32_t)bag;
+      pay_out[e] = kHasVals ? (uint32_t)e : (uint32_t)(bag0 + lo);
+      if (kHasVals) a.bag_of[e] = (int32_t)(bag0 + lo);
     }
   }
 }
@@ -159,6 +171,8 @@ __global__ __launch_bounds__(kBlock) void k_heads_sums(const BwdArgs a, int64_t 
 
 __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
   __shared__ uint32_t lds[kWavesPerBlock];
+  __shared__ uint32_t l_key[kHeadTile];
+  __shared__ int32_t l_idx[kHeadTile];
   const int64_t base = (int64_t)blockIdx.x * kHeadTile + (int64_t)threadIdx.x * kHeadItems;
   uint32_t key[kHeadItems];
   bool flag[kHeadItems];
@@ -177,23 +191,31 @@ __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
     }
   }
   uint32_t total;
-  uint32_t u = a.head_sums[blockIdx.x] + block_excl_scan_u32(cnt, lds, total);
+  const uint32_t u0 = a.head_sums[blockIdx.x];          // heads before this tile
+  uint32_t loc = block_excl_scan_u32(cnt, lds, total);  // heads before this thread inside the tile
   prev = first_prev;
 #pragma unroll
   for (int i = 0; i < kHeadItems; ++i) {
     const int64_t idx = base + i;
     if (idx < a.n) {
       if (flag[i]) {
-        a.uniq_rows[u] = (int32_t)key[i];
-        a.seg_off[u] = (int32_t)idx;
-        a.first_pay[u] = a.pay_sorted[idx];
-        ++u;
+        l_key[loc] = key[i];
+        l_idx[loc] = (int32_t)idx;
+        ++loc;
       }
       // end of the last segment: first entry without a row, or the end of the array
-      if (key[i] == a.missing && (idx == 0 || prev != a.missing)) a.seg_off[u] = (int32_t)idx;
-      if (idx == a.n - 1 && key[i] != a.missing) a.seg_off[u] = (int32_t)a.n;
+      if (key[i] == a.missing && (idx == 0 || prev != a.missing)) a.seg_off[u0 + loc] = (int32_t)idx;
+      if (idx == a.n - 1 && key[i] != a.missing) a.seg_off[u0 + loc] = (int32_t)a.n;
       prev = key[i];
     }
+  }
+  __syncthreads();
+  // the tile's heads occupy consecutive output positions: write them with consecutive threads
+  for (uint32_t j = threadIdx.x; j < total; j += kBlock) {
+    const int32_t idx = l_idx[j];
+    a.uniq_rows[u0 + j] = (int32_t)l_key[j];
+    a.seg_off[u0 + j] = idx;
+    a.first_pay[u0 + j] = a.pay_sorted[idx];
   }
 }
 
@@ -587,7 +609,7 @@ des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *
   {
     ProfScope ps(KID_EXPAND, s);
     if (a.vals) hipLaunchKernelGGL(k_expand<true>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);
-    else hipLaunchKernelGGL(k_expand<false>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);
+    else hipLaunchKernelGGL(k_expand<false>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);  // one workgroup per kBlock bags
   }
   SortBuffers sb{key_a, key_b, pay_a, pay_b};
   const int side = radix_sort_u32_pairs(sb, n, bits_for((uint64_t)t->cfg.capacity_rows), ws + L.sort_scratch, s);

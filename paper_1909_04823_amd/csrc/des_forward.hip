@@ -6,9 +6,9 @@
 // as one 16-byte load each, so a wave holds 64/G "lane groups" that each fetch a different row
 // at the same time.  Every group owns a contiguous range of the sample's bags and walks its
 // entries in CSR order in chunks of G: lane i of the group loads the metadata of entry i of
-// the chunk (row, key -> shard, value, LR weight, bag by binary search in the sample's offsets
-// staged in LDS), the metadata is then broadcast lane by lane with cross-lane shuffles, and the
-// row gathers of a chunk are issued back to back.  The running bag sum stays in registers (the
+// the chunk (row, key -> shard, value, bag found in the sample's offsets staged in LDS) and
+// publishes it in LDS, from where the group reads entry j with one broadcast read; the row
+// gathers of a chunk are issued back to back.  The running bag sum stays in registers (the
 // pooled output is written once per bag, already summed over shards).  The per-shard FM / LR
 // partials of the sample live in LDS ([K][D+2] doubles per sample: D columns, then the sum of
 // squares and the LR sum) and are updated with LDS atomics, because the entries of one shard are
@@ -67,7 +67,8 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   extern __shared__ __align__(16) double lds[];
   constexpr int G = D / 4;                 // lanes per row = entries per chunk
   constexpr int NG = kWave / G;            // lane groups per wave
-  constexpr int U = G < 8 ? G : 8;         // row gathers in flight per lane
+  constexpr int U = G < 4 ? G : 4;         // row gathers in flight per lane
+  constexpr int kLrLane = G > 1 ? 1 : 0;   // lane of a group that fetches and adds the LR weight
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / G, sub = lane % G;
   const int K = a.K, F = a.F, wps = a.wps;
@@ -123,12 +124,22 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
           if (a.vals) x_n = a.vals[nx];
         }
       }
-      int bag_l = f0;
-      if (my < e1) {                                      // largest f with offs[f] <= my
-        int lo = f0, hi = f1;
-        while (hi - lo > 1) {
-          const int mid = (lo + hi) >> 1;
-          if (offs[mid] <= my) lo = mid; else hi = mid;
+      // bag of this lane's entry: the largest f with offs[f] <= my.  Entries are walked in order,
+      // so it is at or shortly after the bag of the last processed entry: a few linear steps,
+      // then a binary search for the rare long run of empty bags.
+      int bag_l = cur;
+      if (my < e1) {
+        int lo = cur;
+#pragma unroll
+        for (int step = 0; step < 4; ++step)
+          if (offs[lo + 1] <= my) ++lo;
+        if (offs[lo + 1] <= my) {
+          int hi = f1;
+          ++lo;
+          while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (offs[mid] <= my) lo = mid; else hi = mid;
+          }
         }
         bag_l = lo;
       }
@@ -150,7 +161,7 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
             wv[i] = 0.f;
             if (j0 + i < cnt && md[i].x >= 0) {
               if (need_v) v[i] = ld4(a.emb + (int64_t)md[i].x * D + sub * 4);
-              if (need_lr && sub == 0) wv[i] = a.w[md[i].x];
+              if (need_lr && sub == kLrLane) wv[i] = a.w[md[i].x];
             }
           }
 #pragma unroll
@@ -170,14 +181,21 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
                                       xd * (double)v[i].w};
 #pragma unroll
                 for (int k = 0; k < 4; ++k) acc[k] += xv[k];
+                double q = 0.0;
                 if (need_fm) {
                   double *dst = sum + s * P + sub;
 #pragma unroll
                   for (int k = 0; k < 4; ++k) atomicAdd(dst + k * G, xv[k]);
-                  const double q = group_sum<G>(xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3]);
-                  if (sub == 0) atomicAdd(sum + s * P + D, q);
+                  q = group_sum<G>(xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3]);
                 }
-                if (need_lr && sub == 0) atomicAdd(sum + s * P + D + 1, xd * (double)wv[i]);
+                // one LDS instruction for both scalars: lane 0 adds the sum of squares, lane kLrLane
+                // the LR term (the same lane when a row is a single lane wide)
+                if (kLrLane == 0) {
+                  if (need_fm && sub == 0) atomicAdd(sum + s * P + D, q);
+                  if (need_lr && sub == 0) atomicAdd(sum + s * P + D + 1, xd * (double)wv[i]);
+                } else if ((sub == 0 && need_fm) || (sub == kLrLane && need_lr)) {
+                  atomicAdd(sum + s * P + D + sub, sub == 0 ? q : xd * (double)wv[i]);
+                }
               }
             }
           }

@@ -13,6 +13,8 @@ constexpr int kScanTile = kBlock * kScanItems;
 constexpr int kSortItems = 16;                      // items per thread in the sort kernels
 constexpr int kSortTile = kBlock * kSortItems;
 constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kMaxDigitBits = 9;                    // widest radix digit of one pass
+constexpr int kMaxRadix = 1 << kMaxDigitBits;
 
 template <typename T>
 __device__ inline T wave_inclusive_scan(T v) {
@@ -111,9 +113,10 @@ template <typename KeyT>
 __global__ __launch_bounds__(kBlock) void k_radix_hist(const KeyT *__restrict__ keys, int64_t n,
                                                         const long long *__restrict__ n_dev, int shift, int bits,
                                                         uint32_t *__restrict__ hist, int nblocks) {
-  __shared__ uint32_t cnt[256];
+  __shared__ uint32_t cnt[kMaxRadix];
   const int64_t n_eff = n_dev ? (int64_t)min((long long)n, *n_dev) : n;
-  cnt[threadIdx.x] = 0;
+  const int radix = 1 << bits;
+  for (int d = threadIdx.x; d < radix; d += kBlock) cnt[d] = 0;
   __syncthreads();
   const int64_t base = (int64_t)blockIdx.x * kSortTile;
   const uint32_t mask = (1u << bits) - 1u;
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(kBlock) void k_radix_hist(const KeyT *__restrict__ 
     if (idx < n_eff) atomicAdd(&cnt[(uint32_t)(keys[idx] >> shift) & mask], 1u);
   }
   __syncthreads();
-  if (threadIdx.x < (1u << bits)) hist[(size_t)threadIdx.x * nblocks + blockIdx.x] = cnt[threadIdx.x];
+  for (int d = threadIdx.x; d < radix; d += kBlock) hist[(size_t)d * nblocks + blockIdx.x] = cnt[d];
 }
 
 template <typename KeyT, bool kHasPayload>
@@ -132,13 +135,15 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict
                                                            KeyT *__restrict__ keys_out, uint32_t *__restrict__ pay_out,
                                                            int64_t n, const long long *__restrict__ n_dev, int shift,
                                                            int bits, const uint32_t *__restrict__ offsets, int nblocks) {
-  __shared__ uint32_t cnt[kWavesPerBlock][256];
+  __shared__ uint32_t cnt[kWavesPerBlock][kMaxRadix];
   const int64_t n_eff = n_dev ? (int64_t)min((long long)n, *n_dev) : n;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t tile = (int64_t)blockIdx.x * kSortTile;
   if (tile >= n_eff) return;                         // uniform per workgroup
+  const int radix = 1 << bits;
+  for (int d = threadIdx.x; d < radix; d += kBlock)
 #pragma unroll
-  for (int w = 0; w < kWavesPerBlock; ++w) cnt[w][threadIdx.x] = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) cnt[w][d] = 0;
   __syncthreads();
 
   const uint32_t mask = (1u << bits) - 1u;
@@ -173,12 +178,12 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict
   }
   __syncthreads();
   // per digit: exclusive prefix over the waves, on top of the tile's global offset
-  if (threadIdx.x < (1u << bits)) {
-    uint32_t run = offsets[(size_t)threadIdx.x * nblocks + blockIdx.x];
+  for (int d = threadIdx.x; d < radix; d += kBlock) {
+    uint32_t run = offsets[(size_t)d * nblocks + blockIdx.x];
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w) {
-      const uint32_t c = cnt[w][threadIdx.x];
-      cnt[w][threadIdx.x] = run;
+      const uint32_t c = cnt[w][d];
+      cnt[w][d] = run;
       run += c;
     }
   }
@@ -203,8 +208,8 @@ int radix_sort(SortBuffers buf, int64_t n, const long long *n_dev, int bits, voi
   if (n <= 0 || bits <= 0) return 0;
   const int nblocks = (int)sort_blocks(n);
   uint32_t *hist = (uint32_t *)scratch;
-  void *scan_scratch = (char *)scratch + align_up((size_t)256 * nblocks * sizeof(uint32_t), 256);
-  const int npass = (bits + 7) / 8;
+  void *scan_scratch = (char *)scratch + align_up((size_t)kMaxRadix * nblocks * sizeof(uint32_t), 256);
+  const int npass = (bits + kMaxDigitBits - 1) / kMaxDigitBits;
   const int per = (bits + npass - 1) / npass;
   KeyT *kin = (KeyT *)buf.keys_a, *kout = (KeyT *)buf.keys_b;
   uint32_t *pin = buf.pay_a, *pout = buf.pay_b;
@@ -241,7 +246,7 @@ size_t scan_scratch_bytes(int64_t n) {
 
 size_t sort_scratch_bytes(int64_t n) {
   const int64_t nblocks = sort_blocks(n > 0 ? n : 1);
-  return align_up((size_t)256 * nblocks * sizeof(uint32_t), 256) + scan_scratch_bytes(256 * nblocks);
+  return align_up((size_t)kMaxRadix * nblocks * sizeof(uint32_t), 256) + scan_scratch_bytes(kMaxRadix * nblocks);
 }
 
 void exclusive_scan_u64(unsigned long long *data, int64_t n, unsigned long long *total_out, void *scratch,

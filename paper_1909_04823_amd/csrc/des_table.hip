@@ -264,6 +264,7 @@ __global__ __launch_bounds__(kBlock) void k_copy_values(const Ctrl *__restrict__
   }
 }
 
+// Last kernel of an insert: the new rows become part of the table.
 __global__ void k_commit(Ctrl *ctrl, int64_t capacity) {
   if (ctrl->status == 0 && ctrl->n_rows + ctrl->n_new <= capacity) ctrl->n_rows += ctrl->n_new;
   ctrl->n_new = 0;
@@ -530,10 +531,10 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
   {
     ProfScope ps(KID_INIT_ROWS, s);
     if (values)
-      hipLaunchKernelGGL(k_copy_values, dim3(grid_for(n * (c.dim + 1), kBlock, 1 << 16)), dim3(kBlock), 0, s, t->ctrl,
+      hipLaunchKernelGGL(k_copy_values, dim3(grid_for(n * (c.dim + 1), kBlock, 2048)), dim3(kBlock), 0, s, t->ctrl,
                          c.dim, values, first_idx, c.emb, c.w, c.acc_emb, c.acc_w, c.capacity_rows);
     else
-      hipLaunchKernelGGL(k_init_rows, dim3(grid_for(n * (c.dim / 4 + 1), kBlock, 1 << 16)), dim3(kBlock), 0, s, t->ctrl,
+      hipLaunchKernelGGL(k_init_rows, dim3(grid_for(n * (c.dim / 4 + 1), kBlock, 2048)), dim3(kBlock), 0, s, t->ctrl,
                          c.dim, c.init_seed, t->init_width, c.row_keys, c.emb, c.w, c.acc_emb, c.acc_w,
                          c.capacity_rows);
   }
