@@ -224,6 +224,37 @@ def test_terms_can_be_dropped_and_merge_only(oracle, des):
     p.close()
 
 
+@pytest.mark.parametrize("D,with_vals", [(16, False), (64, True)])
+def test_merge_segment_length_boundaries(oracle, des, D, with_vals):
+    """Rows whose number of occurrences sits on every boundary of the merge: one entry, the
+    short-segment limit (32) and one more, whole and ragged 512-entry chunks, several chunks, and
+    one row that takes a third of the batch."""
+    import torch
+    counts = np.array([1, 2, 3, 31, 32, 33, 63, 64, 65, 511, 512, 513, 1023, 1024, 1025, 1537, 2048, 9000])
+    rng = np.random.default_rng(21)
+    vocab = rng.integers(1, 2**63, size=counts.size, dtype=np.uint64)
+    keys = np.repeat(vocab, counts)[rng.permutation(int(counts.sum()))]
+    B, F = 96, 7
+    cuts = np.sort(rng.integers(0, keys.size + 1, size=B * F - 1))
+    offsets = np.concatenate([[0], cuts, [keys.size]]).astype(np.int32)
+    vals = rng.uniform(0.25, 2.0, keys.size).astype(np.float32) if with_vals else None
+    batch = synth.Batch(B, F, keys, offsets, vals)
+    p = Pair(oracle, des, D, 64, 4, 0, des.OPT_ADAGRAD, seed=3, init_scale=0.1, max_n=keys.size + 64)
+    p.find(batch, insert=True)
+    p.check_table("boundaries")
+    A_sum = p.forward(batch)
+    g_lr = rng.standard_normal(B).astype(np.float32)
+    g_fm = rng.standard_normal(B).astype(np.float32)
+    g_pool = rng.standard_normal((B, F, D)).astype(np.float32)
+    ref = p.backward(batch, g_lr, g_fm, A_sum, g_pool, opt=des.OPT_NONE)
+    assert sorted(ref["counts"].tolist()) == sorted(counts.tolist())
+    p.backward(batch, g_lr * 1e-3, g_fm * 1e-3, A_sum, g_pool * 1e-3, lr=0.05, eps=1e-8)
+    p.check_weights("boundaries adagrad")
+    p.backward(batch, g_lr * 1e-3, g_fm * 1e-3, A_sum, g_pool * 1e-3, lr=0.05, opt=des.OPT_SGD)
+    p.check_weights("boundaries sgd")
+    p.close()
+
+
 def test_integers_are_deterministic_run_to_run(oracle, des):
     import torch
     w = synth.workload(3, scale=1 / 128)
