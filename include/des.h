@@ -23,7 +23,11 @@
  *   - Calls on one table must be ordered (same stream, or externally synchronised); two
  *     tables are independent.
  *   - Supported shapes: dim a power of two in [4, 256]; 1 <= num_shards <= 256;
- *     capacity_rows <= 2^31 - 2; nnz < 2^31; B*F < 2^31.
+ *     capacity_rows <= 2^31 - 2; nnz < 2^31; B*F < 2^31; for the forward calls
+ *     8*num_shards*(dim+2) + 4*(F+1) + 4096 <= 65536 (bytes of on-chip memory per sample).
+ *   - Not checked (the caller's contract): offsets are non-decreasing with offsets[0] = 0 and
+ *     offsets[B*F] = nnz; `rows` passed to the forward / backward calls were produced by
+ *     des_table_find / des_table_insert on the same table for the same keys.
  *
  * Conventions the paper leaves open, fixed here (the CPU oracle implements the same text):
  *   mix64(z)      finalizer of SplitMix64: z=(z^(z>>30))*0xBF58476D1CE4E5B9;
