@@ -64,7 +64,7 @@ typedef enum {
 } des_status_t;
 
 typedef enum { DES_SHARD_KEY_HASH = 0, DES_SHARD_FIELD_MOD = 1 } des_shard_policy_t;
-typedef enum { DES_OPT_NONE = 0, DES_OPT_SGD = 1, DES_OPT_ADAGRAD = 2 } des_opt_t;
+typedef enum { DES_OPT_NONE = 0, DES_OPT_SGD = 1, DES_OPT_ADAGRAD = 2, DES_OPT_ADAM = 3, DES_OPT_FTRL = 4 } des_opt_t;
 typedef enum { DES_MISS_ZERO = 0, DES_MISS_INSERT = 1 } des_miss_t;
 
 /* Table description.  The caller allocates every buffer (16-byte aligned). */
@@ -85,6 +85,8 @@ typedef struct {
   size_t slots_bytes;
   void *workspace;             /* device scratch for sort / scan / merge                     */
   size_t workspace_bytes;
+  float *acc2_emb;             /* device [capacity, D]   second state array (Adam) or NULL   */
+  float *acc2_w;               /* device [capacity]      second state (Adam, FTRL) or NULL   */
 } des_table_config_t;
 
 /* One batch in CSR form (Section 3.2.1: input X; variable-length multi-hot fields).
@@ -176,6 +178,27 @@ des_status_t des_backward_update_sgd(des_table_t *t, const des_batch_t *batch, c
                                      const des_backward_io_t *io, float lr, void *stream);
 des_status_t des_backward_update_adagrad(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
                                          const des_backward_io_t *io, float lr, float eps, void *stream);
+/* The optimizer setting of the paper's experiments (Section 6, "Parameter Settings": FTRL for
+ * order-1 components, AdaGrad or Adam for the embeddings), with the same merge as above.  The
+ * optimizers themselves are the published ones, restated:
+ *   Adam (Kingma & Ba), lazily per touched row, global step t = `step` >= 1:
+ *     m = b1*m + (1-b1)*G;  v = b2*v + (1-b2)*G*G;
+ *     theta -= lr * (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps)          state: acc = m, acc2 = v
+ *   FTRL-Proximal (McMahan et al.), order-1 weights only:
+ *     sigma = (sqrt(n+G*G) - sqrt(n))/alpha;  z += G - sigma*w;  n += G*G;
+ *     w = |z| <= l1 ? 0 : -(z - sign(z)*l1) / ((beta + sqrt(n))/alpha + l2)   state: acc_w = n, acc2_w = z
+ * opt_emb is SGD, ADAGRAD or ADAM; opt_w is SGD, ADAGRAD, ADAM or FTRL.  The state arrays an
+ * optimizer needs must have been given in des_table_config_t, else DES_ERR_INVALID_ARG. */
+typedef struct {
+  int32_t opt_emb, opt_w;       /* des_opt_t */
+  float lr, eps;                /* SGD / Adagrad / Adam */
+  float beta1, beta2;           /* Adam */
+  int64_t step;                 /* Adam: t >= 1 */
+  float ftrl_alpha, ftrl_beta, ftrl_l1, ftrl_l2;
+} des_optimizer_t;
+des_status_t des_backward_update(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                 const des_backward_io_t *io, const des_optimizer_t *optimizer, void *stream);
+
 /* Merge only (no weight changes); fills the optional outputs. */
 des_status_t des_backward_merge(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
                                 const des_backward_io_t *io, void *stream);

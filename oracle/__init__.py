@@ -18,7 +18,7 @@ _SRC = os.path.join(_HERE, "des_oracle.c")
 _LIB = os.path.join(_HERE, "libdes_oracle.so")
 
 SHARD_KEY_HASH, SHARD_FIELD_MOD = 0, 1
-OPT_NONE, OPT_SGD, OPT_ADAGRAD = 0, 1, 2
+OPT_NONE, OPT_SGD, OPT_ADAGRAD, OPT_ADAM, OPT_FTRL = 0, 1, 2, 3, 4
 OK, ERR_INVALID_ARG, ERR_INVALID_KEY, ERR_FULL = 0, 1, 2, 3
 
 
@@ -28,6 +28,13 @@ def build(force: bool = True) -> str:
         subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-std=c11", "-shared", "-fPIC",
                                "-o", _LIB, _SRC, "-lm"])
     return _LIB
+
+
+class Optimizer(C.Structure):
+    """Mirror of the C struct oracle_optimizer."""
+    _fields_ = [("opt_emb", C.c_int32), ("opt_w", C.c_int32), ("lr", C.c_float), ("eps", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("step", C.c_int64),
+                ("ftrl_alpha", C.c_float), ("ftrl_beta", C.c_float), ("ftrl_l1", C.c_float), ("ftrl_l2", C.c_float)]
 
 
 _lib = None
@@ -45,7 +52,7 @@ def lib():
         L.oracle_table_create.restype = vp; L.oracle_table_create.argtypes = [C.c_int, i64, u64, f32]
         L.oracle_table_destroy.restype = None; L.oracle_table_destroy.argtypes = [vp]
         L.oracle_table_size.restype = i64; L.oracle_table_size.argtypes = [vp]
-        for name in ("row_keys", "emb", "w", "acc_emb", "acc_w"):
+        for name in ("row_keys", "emb", "w", "acc_emb", "acc_w", "acc2_emb", "acc2_w"):
             fn = getattr(L, "oracle_table_" + name); fn.restype = vp; fn.argtypes = [vp]
         L.oracle_table_insert.restype = C.c_int; L.oracle_table_insert.argtypes = [vp, vp, i64, vp, vp]
         L.oracle_table_find.restype = C.c_int; L.oracle_table_find.argtypes = [vp, vp, i64, C.c_int, vp]
@@ -56,6 +63,9 @@ def lib():
         L.oracle_backward_update.restype = i64
         L.oracle_backward_update.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, C.c_int, f32, f32,
                                              vp, vp, vp, vp]
+        L.oracle_backward_update_opt.restype = i64
+        L.oracle_backward_update_opt.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, C.POINTER(Optimizer),
+                                                 vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -129,6 +139,10 @@ class Table:
     def acc_emb(self): return self._view("acc_emb", C.c_float, (self.n_rows, self.D))
     @property
     def acc_w(self): return self._view("acc_w", C.c_float, (self.n_rows,))
+    @property
+    def acc2_emb(self): return self._view("acc2_emb", C.c_float, (self.n_rows, self.D))
+    @property
+    def acc2_w(self): return self._view("acc2_w", C.c_float, (self.n_rows,))
 
     def insert(self, keys, values=None) -> np.ndarray:
         keys = _c(keys, np.uint64)
@@ -166,9 +180,11 @@ class Table:
         return out
 
     def backward_update(self, B, F, offsets, rows, g_lr=None, g_fm=None, A_sum=None, g_pool=None,
-                        opt=OPT_NONE, lr=0.0, eps=0.0, vals=None):
-        """Merge duplicate-row gradients (ascending row order) and apply the optimizer in place.
-        Returns dict(uniq_rows, uniq_keys, counts, merged[U,D+1] float64)."""
+                        opt=OPT_NONE, lr=0.0, eps=0.0, vals=None, optimizer: Optional[Optimizer] = None):
+        """Merge duplicate-row gradients (ascending row order) and apply the optimizer in place
+        (`optimizer` selects separate optimizers for latent vectors and LR weights; otherwise
+        `opt`, `lr`, `eps` apply to both).  Returns dict(uniq_rows, uniq_keys, counts,
+        merged[U,D+1] float64)."""
         offsets, rows = _c(offsets, np.int32), _c(rows, np.int32)
         vals = _c(vals, np.float32)
         g_lr, g_fm, A_sum, g_pool = (_c(a, np.float32) for a in (g_lr, g_fm, A_sum, g_pool))
@@ -177,9 +193,14 @@ class Table:
         nnz = int(offsets[B * F])
         uniq_rows = np.empty(nnz, np.int32); uniq_keys = np.empty(nnz, np.uint64)
         counts = np.empty(nnz, np.int32); merged = np.empty((nnz, self.D + 1), np.float64)
-        U = int(lib().oracle_backward_update(self._h, B, F, _p(offsets), _p(vals), _p(rows), _p(g_lr), _p(g_fm),
-                                             _p(A_sum), _p(g_pool), opt, C.c_float(lr), C.c_float(eps),
-                                             _p(uniq_rows), _p(uniq_keys), _p(counts), _p(merged)))
+        if optimizer is not None:
+            U = int(lib().oracle_backward_update_opt(self._h, B, F, _p(offsets), _p(vals), _p(rows), _p(g_lr),
+                                                     _p(g_fm), _p(A_sum), _p(g_pool), C.byref(optimizer),
+                                                     _p(uniq_rows), _p(uniq_keys), _p(counts), _p(merged)))
+        else:
+            U = int(lib().oracle_backward_update(self._h, B, F, _p(offsets), _p(vals), _p(rows), _p(g_lr), _p(g_fm),
+                                                 _p(A_sum), _p(g_pool), opt, C.c_float(lr), C.c_float(eps),
+                                                 _p(uniq_rows), _p(uniq_keys), _p(counts), _p(merged)))
         return {"uniq_rows": uniq_rows[:U].copy(), "uniq_keys": uniq_keys[:U].copy(),
                 "counts": counts[:U].copy(), "merged": merged[:U].copy()}
 

@@ -38,7 +38,7 @@
 #define ORACLE_EMPTY_KEY 0xFFFFFFFFFFFFFFFFull
 
 enum { SHARD_KEY_HASH = 0, SHARD_FIELD_MOD = 1 };
-enum { OPT_NONE = 0, OPT_SGD = 1, OPT_ADAGRAD = 2 };
+enum { OPT_NONE = 0, OPT_SGD = 1, OPT_ADAGRAD = 2, OPT_ADAM = 3, OPT_FTRL = 4 };
 
 /* ------------------------------------------------------------------ conventions ---------- */
 
@@ -76,6 +76,7 @@ typedef struct oracle_table {
   float init_scale;
   uint64_t *row_keys;           /* [capacity] row -> key                                   */
   float *emb, *w, *acc_emb, *acc_w;
+  float *acc2_emb, *acc2_w;      /* second optimizer state (Adam v; FTRL z)                  */
   uint64_t *skeys;              /* keys in ascending order                                  */
   int32_t *srows;               /* row of skeys[i]                                          */
 } oracle_table;
@@ -90,15 +91,18 @@ oracle_table *oracle_table_create(int D, int64_t capacity, uint64_t seed, float 
   t->w = (float *)calloc((size_t)capacity, sizeof(float));
   t->acc_emb = (float *)calloc((size_t)capacity * D, sizeof(float));
   t->acc_w = (float *)calloc((size_t)capacity, sizeof(float));
+  t->acc2_emb = (float *)calloc((size_t)capacity * D, sizeof(float));
+  t->acc2_w = (float *)calloc((size_t)capacity, sizeof(float));
   t->skeys = (uint64_t *)calloc((size_t)capacity, sizeof(uint64_t));
   t->srows = (int32_t *)calloc((size_t)capacity, sizeof(int32_t));
-  if (!t->row_keys || !t->emb || !t->w || !t->acc_emb || !t->acc_w || !t->skeys || !t->srows) return NULL;
+  if (!t->row_keys || !t->emb || !t->w || !t->acc_emb || !t->acc_w || !t->acc2_emb || !t->acc2_w || !t->skeys ||
+      !t->srows) return NULL;
   return t;
 }
 
 void oracle_table_destroy(oracle_table *t) {
   if (!t) return;
-  free(t->row_keys); free(t->emb); free(t->w); free(t->acc_emb); free(t->acc_w);
+  free(t->row_keys); free(t->emb); free(t->w); free(t->acc_emb); free(t->acc_w); free(t->acc2_emb); free(t->acc2_w);
   free(t->skeys); free(t->srows); free(t);
 }
 
@@ -108,6 +112,8 @@ float *oracle_table_emb(oracle_table *t) { return t->emb; }
 float *oracle_table_w(oracle_table *t) { return t->w; }
 float *oracle_table_acc_emb(oracle_table *t) { return t->acc_emb; }
 float *oracle_table_acc_w(oracle_table *t) { return t->acc_w; }
+float *oracle_table_acc2_emb(oracle_table *t) { return t->acc2_emb; }
+float *oracle_table_acc2_w(oracle_table *t) { return t->acc2_w; }
 
 /* Row of a key, or -1: binary search in the ascending key list. */
 static int32_t lookup(const oracle_table *t, uint64_t key) {
@@ -162,8 +168,8 @@ int oracle_table_insert(oracle_table *t, const uint64_t *keys, int64_t n, const 
                                    : oracle_init_value(k, c, t->seed, t->init_scale);
     t->w[row] = values ? values[cand[j].first * (D + 1) + D]
                        : oracle_init_value(k, D, t->seed, t->init_scale);
-    for (int c = 0; c < D; ++c) t->acc_emb[row * D + c] = 0.0f;
-    t->acc_w[row] = 0.0f;
+    for (int c = 0; c < D; ++c) t->acc_emb[row * D + c] = t->acc2_emb[row * D + c] = 0.0f;
+    t->acc_w[row] = t->acc2_w[row] = 0.0f;
     cand[j].first = row;                           /* reuse the field: the key's row */
   }
   /* merge the new keys, ascending by key, into the ascending key list, back to front */
@@ -254,6 +260,49 @@ static int cmp_rowent(const void *a, const void *b) {
   return x->e < y->e ? -1 : (x->e > y->e);
 }
 
+typedef struct {
+  int32_t opt_emb, opt_w;          /* latent vectors: SGD, ADAGRAD, ADAM; LR weight: those or FTRL */
+  float lr, eps;
+  float beta1, beta2;              /* Adam */
+  int64_t step;                    /* Adam: global step t >= 1 */
+  float ftrl_alpha, ftrl_beta, ftrl_l1, ftrl_l2;
+} oracle_optimizer;
+
+/* One optimizer step on one coordinate with merged gradient G (double); state and weight are
+ * stored in fp32.  SGD and Adagrad as in the comment of oracle_backward_update_opt; Adam and
+ * FTRL-Proximal are the published algorithms:
+ *   Adam (Kingma & Ba 2015, Algorithm 1), applied lazily to touched rows with the global step t:
+ *     m = b1 m + (1-b1) G;  v = b2 v + (1-b2) G^2;  theta -= lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps)
+ *   FTRL-Proximal (McMahan et al. 2013, Algorithm 1), per coordinate with state (z, n):
+ *     sigma = (sqrt(n+G^2) - sqrt(n))/alpha;  z += G - sigma w;  n += G^2;
+ *     w = 0 if |z| <= l1 else -(z - sign(z) l1) / ((beta + sqrt(n))/alpha + l2)               */
+static void optimizer_step(int opt, const oracle_optimizer *o, double G, float *theta, float *s1, float *s2) {
+  if (opt == OPT_SGD) {
+    *theta = (float)((double)*theta - (double)o->lr * G);
+  } else if (opt == OPT_ADAGRAD) {
+    double a = (double)*s1 + G * G;
+    *theta = (float)((double)*theta - (double)o->lr * G / (sqrt(a) + (double)o->eps));
+    *s1 = (float)a;
+  } else if (opt == OPT_ADAM) {
+    double b1 = (double)o->beta1, b2 = (double)o->beta2, t = (double)o->step;
+    double m = b1 * (double)*s1 + (1.0 - b1) * G;
+    double v = b2 * (double)*s2 + (1.0 - b2) * G * G;
+    double mhat = m / (1.0 - pow(b1, t)), vhat = v / (1.0 - pow(b2, t));
+    *theta = (float)((double)*theta - (double)o->lr * mhat / (sqrt(vhat) + (double)o->eps));
+    *s1 = (float)m;
+    *s2 = (float)v;
+  } else if (opt == OPT_FTRL) {
+    double n0 = (double)*s1, z0 = (double)*s2, alpha = (double)o->ftrl_alpha, l1 = (double)o->ftrl_l1;
+    double n1 = n0 + G * G;
+    double sigma = (sqrt(n1) - sqrt(n0)) / alpha;
+    double z = z0 + G - sigma * (double)*theta;
+    double w = fabs(z) <= l1 ? 0.0 : -(z - (z > 0 ? l1 : -l1)) / (((double)o->ftrl_beta + sqrt(n1)) / alpha + (double)o->ftrl_l2);
+    *theta = (float)w;
+    *s1 = (float)n1;
+    *s2 = (float)z;
+  }
+}
+
 /* Backward of the three sparse operators, duplicate-key merge and optimizer update.
  *
  * With upstream gradients g_lr[B] (of the aggregated LR sum), g_fm[B] (of the FM order-2
@@ -266,14 +315,15 @@ static int cmp_rowent(const void *a, const void *b) {
  * exactly those rows, reading the pre-update weights:
  *     SGD      theta <- theta - lr*G
  *     Adagrad  a <- a + G^2 ;  theta <- theta - lr*G / (sqrt(a) + eps)   (a already updated)
- * Any of g_lr, g_fm (with A_sum), g_pool may be NULL (term absent).  opt = OPT_NONE only
- * merges.  Returns the number U of distinct rows; outputs (all nullable) hold U entries:
+ *     Adam, FTRL-Proximal: see optimizer_step
+ * with one optimizer for the latent columns and one for the LR weight.  Any of g_lr, g_fm (with
+ * A_sum), g_pool may be NULL (term absent).  OPT_NONE for both only merges.  Returns the number U of distinct rows; outputs (all nullable) hold U entries:
  * uniq_rows, uniq_keys, counts, merged[U, D+1] (D latent columns then the LR weight). */
-int64_t oracle_backward_update(oracle_table *t, int64_t B, int32_t F, const int32_t *offsets,
-                               const float *vals, const int32_t *rows, const float *g_lr,
-                               const float *g_fm, const float *A_sum, const float *g_pool,
-                               int opt, float lr, float eps, int32_t *uniq_rows,
-                               uint64_t *uniq_keys, int32_t *counts, double *merged) {
+int64_t oracle_backward_update_opt(oracle_table *t, int64_t B, int32_t F, const int32_t *offsets,
+                                   const float *vals, const int32_t *rows, const float *g_lr,
+                                   const float *g_fm, const float *A_sum, const float *g_pool,
+                                   const oracle_optimizer *o, int32_t *uniq_rows,
+                                   uint64_t *uniq_keys, int32_t *counts, double *merged) {
   const int D = t->D;
   const int64_t nnz = offsets[B * F];
   rowent_t *ent = (rowent_t *)malloc(sizeof(rowent_t) * (size_t)(nnz > 0 ? nnz : 1));
@@ -308,19 +358,28 @@ int64_t oracle_backward_update(oracle_table *t, int64_t B, int32_t F, const int3
     if (counts) counts[U] = (int32_t)(j - i);
     if (merged) for (int c = 0; c <= D; ++c) merged[U * (D + 1) + c] = G[c];
     for (int c = 0; c <= D; ++c) {
-      float *theta = c < D ? &t->emb[(int64_t)r * D + c] : &t->w[r];
-      float *acc = c < D ? &t->acc_emb[(int64_t)r * D + c] : &t->acc_w[r];
-      if (opt == OPT_SGD) {
-        *theta = (float)((double)*theta - (double)lr * G[c]);
-      } else if (opt == OPT_ADAGRAD) {
-        double a = (double)*acc + G[c] * G[c];
-        *theta = (float)((double)*theta - (double)lr * G[c] / (sqrt(a) + (double)eps));
-        *acc = (float)a;
-      }
+      if (c < D)
+        optimizer_step(o->opt_emb, o, G[c], &t->emb[(int64_t)r * D + c], &t->acc_emb[(int64_t)r * D + c],
+                       &t->acc2_emb[(int64_t)r * D + c]);
+      else
+        optimizer_step(o->opt_w, o, G[c], &t->w[r], &t->acc_w[r], &t->acc2_w[r]);
     }
     ++U;
     i = j;
   }
   free(G); free(bag_of); free(ent);
   return U;
+}
+
+/* Same optimizer (SGD, Adagrad or none) for latent vectors and LR weights. */
+int64_t oracle_backward_update(oracle_table *t, int64_t B, int32_t F, const int32_t *offsets,
+                               const float *vals, const int32_t *rows, const float *g_lr,
+                               const float *g_fm, const float *A_sum, const float *g_pool,
+                               int opt, float lr, float eps, int32_t *uniq_rows,
+                               uint64_t *uniq_keys, int32_t *counts, double *merged) {
+  oracle_optimizer o;
+  memset(&o, 0, sizeof(o));
+  o.opt_emb = o.opt_w = opt; o.lr = lr; o.eps = eps; o.step = 1;
+  return oracle_backward_update_opt(t, B, F, offsets, vals, rows, g_lr, g_fm, A_sum, g_pool, &o, uniq_rows,
+                                    uniq_keys, counts, merged);
 }

@@ -13,6 +13,7 @@
 // Per entry e of bag (b,f) with value x:  d/dw += x*g_lr[b],
 //   d/dv += x*(g_fm[b]*A_sum[b,:] + g_pool[b,f,:]) - v * (x*x*g_fm[b])
 // i.e. the row's own vector v enters only through one scalar per segment, so v is read once.
+#include <math.h>
 #include "des_internal.h"
 
 namespace des {
@@ -35,7 +36,7 @@ struct BwdArgs {
   int F;
   uint32_t missing;     // sort key of entries without a row (= capacity, sorts last)
   // table
-  float *emb, *w, *acc_emb, *acc_w;
+  float *emb, *w, *acc_emb, *acc_w, *acc2_emb, *acc2_w;
   const uint64_t *row_keys;
   Ctrl *ctrl;
   // workspace
@@ -49,9 +50,11 @@ struct BwdArgs {
   uint32_t *long_c0;    // first chunk of long segment j
   int32_t *chunk_owner; // long segment index of chunk c
   double *partials;     // [chunks][D+4]
-  // optimizer
-  int opt;
+  // optimizer (opt_emb == DES_OPT_NONE: merge only)
+  int opt_emb, opt_w;
   float lr, eps;
+  float b1, b2, c1, c2;   // Adam: decay rates and bias corrections 1/(1-b1^t), 1/(1-b2^t)
+  float f_alpha, f_beta, f_l1, f_l2;
   // optional outputs
   int32_t *uniq_rows_out;
   uint64_t *uniq_keys_out;
@@ -322,8 +325,8 @@ __device__ inline void reduce_entries(const BwdArgs &a, int i0, int i1, int sub,
 // owns the LR weight).  Loaded before the gradient reduction so that the row's memory latency
 // overlaps the gathers of the upstream gradients.
 struct RowState {
-  float4 v, s;      // latent columns and their Adagrad accumulators
-  float w, aw;      // LR weight and its accumulator
+  float4 v, s, s2;      // latent columns and their first / second state arrays
+  float w, aw, aw2;     // LR weight and its state
 };
 
 template <int D>
@@ -331,18 +334,28 @@ __device__ inline RowState load_row(const BwdArgs &a, int row, int sub) {
   RowState st;
   st.v = ld4_stream(a.emb + (int64_t)row * D + sub * 4);
   st.s = f4zero();
-  st.w = 0.f;
-  st.aw = 0.f;
-  if (a.opt == DES_OPT_ADAGRAD) st.s = ld4_stream(a.acc_emb + (int64_t)row * D + sub * 4);
-  if (sub == 0 && a.opt != DES_OPT_NONE) {
+  st.s2 = f4zero();
+  st.w = st.aw = st.aw2 = 0.f;
+  if (a.opt_emb == DES_OPT_ADAGRAD || a.opt_emb == DES_OPT_ADAM)
+    st.s = ld4_stream(a.acc_emb + (int64_t)row * D + sub * 4);
+  if (a.opt_emb == DES_OPT_ADAM) st.s2 = ld4_stream(a.acc2_emb + (int64_t)row * D + sub * 4);
+  if (sub == 0 && a.opt_w != DES_OPT_NONE) {
     st.w = a.w[row];
-    if (a.opt == DES_OPT_ADAGRAD) st.aw = a.acc_w[row];
+    if (a.opt_w != DES_OPT_SGD) st.aw = a.acc_w[row];
+    if (a.opt_w == DES_OPT_ADAM || a.opt_w == DES_OPT_FTRL) st.aw2 = a.acc2_w[row];
   }
   return st;
 }
 
+__device__ inline float adam_step(const BwdArgs &a, float g, float &m, float &v) {
+  m = a.b1 * m + (1.f - a.b1) * g;
+  v = a.b2 * v + (1.f - a.b2) * g * g;
+  return a.lr * (m * a.c1) / (sqrtf(v * a.c2) + a.eps);
+}
+
 // Apply the merged gradient of one row.  The merged gradient is formed in double and rounded
-// once; the optimizer arithmetic itself is well conditioned and runs in fp32.
+// once; the optimizer arithmetic itself is well conditioned and runs in fp32 (FTRL, one scalar
+// per row with a difference of square roots, in double).
 template <int D>
 __device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, const RowState &st, const Acc &acc) {
   const float4 v = st.v;
@@ -355,19 +368,46 @@ __device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, 
     m[0] = G.x; m[1] = G.y; m[2] = G.z; m[3] = G.w;
     if (sub == 0) a.merged_out[u * (D + 1) + D] = gw;
   }
-  if (a.opt == DES_OPT_SGD) {
+  if (a.opt_emb == DES_OPT_SGD) {
     st4_stream(vp, make_float4(v.x - a.lr * G.x, v.y - a.lr * G.y, v.z - a.lr * G.z, v.w - a.lr * G.w));
-    if (sub == 0) a.w[row] = st.w - a.lr * gw;
-  } else if (a.opt == DES_OPT_ADAGRAD) {
+  } else if (a.opt_emb == DES_OPT_ADAGRAD) {
     float4 s = st.s;
     s.x += G.x * G.x; s.y += G.y * G.y; s.z += G.z * G.z; s.w += G.w * G.w;
     st4_stream(a.acc_emb + (int64_t)row * D + sub * 4, s);
     st4_stream(vp, make_float4(v.x - a.lr * G.x / (sqrtf(s.x) + a.eps), v.y - a.lr * G.y / (sqrtf(s.y) + a.eps),
-                        v.z - a.lr * G.z / (sqrtf(s.z) + a.eps), v.w - a.lr * G.w / (sqrtf(s.w) + a.eps)));
-    if (sub == 0) {
+                               v.z - a.lr * G.z / (sqrtf(s.z) + a.eps), v.w - a.lr * G.w / (sqrtf(s.w) + a.eps)));
+  } else if (a.opt_emb == DES_OPT_ADAM) {
+    float4 m = st.s, q = st.s2;
+    const float dx = adam_step(a, G.x, m.x, q.x), dy = adam_step(a, G.y, m.y, q.y);
+    const float dz = adam_step(a, G.z, m.z, q.z), dw = adam_step(a, G.w, m.w, q.w);
+    st4_stream(a.acc_emb + (int64_t)row * D + sub * 4, m);
+    st4_stream(a.acc2_emb + (int64_t)row * D + sub * 4, q);
+    st4_stream(vp, make_float4(v.x - dx, v.y - dy, v.z - dz, v.w - dw));
+  }
+  if (sub == 0) {
+    if (a.opt_w == DES_OPT_SGD) {
+      a.w[row] = st.w - a.lr * gw;
+    } else if (a.opt_w == DES_OPT_ADAGRAD) {
       const float aw = st.aw + gw * gw;
       a.acc_w[row] = aw;
       a.w[row] = st.w - a.lr * gw / (sqrtf(aw) + a.eps);
+    } else if (a.opt_w == DES_OPT_ADAM) {
+      float m = st.aw, q = st.aw2;
+      const float d = adam_step(a, gw, m, q);
+      a.acc_w[row] = m;
+      a.acc2_w[row] = q;
+      a.w[row] = st.w - d;
+    } else if (a.opt_w == DES_OPT_FTRL) {
+      const double g = acc.gw, n0 = (double)st.aw, alpha = (double)a.f_alpha;
+      const double n1 = n0 + g * g;
+      const double sigma = (sqrt(n1) - sqrt(n0)) / alpha;
+      const double z = (double)st.aw2 + g - sigma * (double)st.w;
+      const double l1 = (double)a.f_l1;
+      const double wn = fabs(z) <= l1 ? 0.0
+                                      : -(z - (z > 0.0 ? l1 : -l1)) / (((double)a.f_beta + sqrt(n1)) / alpha + (double)a.f_l2);
+      a.acc_w[row] = (float)n1;
+      a.acc2_w[row] = (float)z;
+      a.w[row] = (float)wn;
     }
   }
 }
@@ -577,7 +617,7 @@ int bits_for(uint64_t max_value) {
 size_t backward_ws_bytes(int D, int64_t max_n) { return layout_for(D, max_n).total; }
 
 des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *rows, const des_backward_io_t *io,
-                             int opt, float lr, float eps, hipStream_t s) {
+                             const des_optimizer_t *opt, hipStream_t s) {
   const int64_t n = b->nnz;
   const int D = t->cfg.dim;
   if (n == 0) {
@@ -592,6 +632,7 @@ des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *
   a.n = n; a.nbags = b->B * (int64_t)b->F; a.F = b->F;
   a.missing = (uint32_t)t->cfg.capacity_rows;
   a.emb = t->cfg.emb; a.w = t->cfg.w; a.acc_emb = t->cfg.acc_emb; a.acc_w = t->cfg.acc_w;
+  a.acc2_emb = t->cfg.acc2_emb; a.acc2_w = t->cfg.acc2_w;
   a.row_keys = t->cfg.row_keys; a.ctrl = t->ctrl;
   a.bag_of = (int32_t *)(ws + L.bag_of);
   a.seg_off = (int32_t *)(ws + L.seg_off); a.uniq_rows = (int32_t *)(ws + L.uniq_rows);
@@ -599,7 +640,12 @@ des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *
   a.head_sums = (uint32_t *)(ws + L.head_sums);
   a.long_seg = (int32_t *)(ws + L.long_seg); a.long_c0 = (uint32_t *)(ws + L.long_c0);
   a.chunk_owner = (int32_t *)(ws + L.chunk_owner); a.partials = (double *)(ws + L.partials);
-  a.opt = opt; a.lr = lr; a.eps = eps;
+  a.opt_emb = opt->opt_emb; a.opt_w = opt->opt_w; a.lr = opt->lr; a.eps = opt->eps;
+  a.b1 = opt->beta1; a.b2 = opt->beta2;
+  const double t_step = (double)(opt->step > 0 ? opt->step : 1);
+  a.c1 = (float)(1.0 / (1.0 - pow((double)opt->beta1, t_step)));
+  a.c2 = (float)(1.0 / (1.0 - pow((double)opt->beta2, t_step)));
+  a.f_alpha = opt->ftrl_alpha; a.f_beta = opt->ftrl_beta; a.f_l1 = opt->ftrl_l1; a.f_l2 = opt->ftrl_l2;
   a.uniq_rows_out = io->uniq_rows_out; a.uniq_keys_out = io->uniq_keys_out; a.counts_out = io->counts_out;
   a.merged_out = io->merged_out; a.n_uniq_out = io->n_uniq_out;
   a.key_sorted = nullptr; a.pay_sorted = nullptr;

@@ -89,7 +89,7 @@ des_status_t forward_launch(des_table *t, const des_batch_t *b, const int32_t *r
                             float *P_sq, float *pool, hipStream_t s);
 des_status_t pool_dense_launch(des_table *t, const des_batch_t *b, const int32_t *rows, float *P_pool, hipStream_t s);
 des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *rows, const des_backward_io_t *io,
-                             int opt, float lr, float eps, hipStream_t s);
+                             const des_optimizer_t *opt, hipStream_t s);
 size_t backward_ws_bytes(int D, int64_t max_n);
 size_t insert_ws_bytes(int64_t max_n);
 }  // namespace des

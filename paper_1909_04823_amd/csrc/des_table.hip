@@ -194,6 +194,7 @@ __global__ __launch_bounds__(kBlock) void k_init_rows(const Ctrl *__restrict__ c
                                                        float width, const uint64_t *__restrict__ row_keys,
                                                        float *__restrict__ emb, float *__restrict__ w,
                                                        float *__restrict__ acc_emb, float *__restrict__ acc_w,
+                                                       float *__restrict__ acc2_emb, float *__restrict__ acc2_w,
                                                        int64_t capacity) {
   if (ctrl->status != 0) return;
   const long long n_new = ctrl->n_new, n_rows = ctrl->n_rows;
@@ -215,11 +216,13 @@ __global__ __launch_bounds__(kBlock) void k_init_rows(const Ctrl *__restrict__ c
       }
       *reinterpret_cast<float4 *>(&emb[row * D + g * 4]) = make_float4(v[0], v[1], v[2], v[3]);
       if (acc_emb) *reinterpret_cast<float4 *>(&acc_emb[row * D + g * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (acc2_emb) *reinterpret_cast<float4 *>(&acc2_emb[row * D + g * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     } else {
       const uint64_t h = mix64(key ^ mix64(seed + (uint64_t)D));
       const float u = (float)(h >> 40) * (1.0f / 16777216.0f);
       w[row] = __fmul_rn(__fsub_rn(u, 0.5f), width);
       if (acc_w) acc_w[row] = 0.f;
+      if (acc2_w) acc2_w[row] = 0.f;
     }
   }
 }
@@ -241,6 +244,7 @@ __global__ __launch_bounds__(kBlock) void k_copy_values(const Ctrl *__restrict__
                                                          const int32_t *__restrict__ first_idx,
                                                          float *__restrict__ emb, float *__restrict__ w,
                                                          float *__restrict__ acc_emb, float *__restrict__ acc_w,
+                                                         float *__restrict__ acc2_emb, float *__restrict__ acc2_w,
                                                          int64_t capacity) {
   if (ctrl->status != 0) return;
   const long long n_new = ctrl->n_new, n_rows = ctrl->n_rows;
@@ -257,9 +261,11 @@ __global__ __launch_bounds__(kBlock) void k_copy_values(const Ctrl *__restrict__
     if (c < D) {
       emb[row * D + c] = val;
       if (acc_emb) acc_emb[row * D + c] = 0.f;
+      if (acc2_emb) acc2_emb[row * D + c] = 0.f;
     } else {
       w[row] = val;
       if (acc_w) acc_w[row] = 0.f;
+      if (acc2_w) acc2_w[row] = 0.f;
     }
   }
 }
@@ -338,7 +344,7 @@ des_status_t validate_cfg(const des_table_config_t *c) {
   if (c->capacity_rows < 1 || c->capacity_rows > 2147483646ll) return DES_ERR_INVALID_ARG;
   if (c->num_shards < 1 || c->num_shards > 256) return DES_ERR_INVALID_ARG;
   if (c->shard_policy != DES_SHARD_KEY_HASH && c->shard_policy != DES_SHARD_FIELD_MOD) return DES_ERR_INVALID_ARG;
-  if (c->opt != DES_OPT_NONE && c->opt != DES_OPT_SGD && c->opt != DES_OPT_ADAGRAD) return DES_ERR_INVALID_ARG;
+  if (c->opt < DES_OPT_NONE || c->opt > DES_OPT_FTRL) return DES_ERR_INVALID_ARG;
   if (!(c->init_scale >= 0.f)) return DES_ERR_INVALID_ARG;
   return DES_OK;
 }
@@ -455,6 +461,9 @@ des_status_t des_table_create(const des_table_config_t *cfg, des_table_t **out) 
   if (st != DES_OK) return st;
   if (!cfg->emb || !cfg->w || !cfg->row_keys || !cfg->slots || !cfg->workspace) return DES_ERR_INVALID_ARG;
   if (cfg->opt == DES_OPT_ADAGRAD && (!cfg->acc_emb || !cfg->acc_w)) return DES_ERR_INVALID_ARG;
+  if (cfg->opt == DES_OPT_ADAM && (!cfg->acc_emb || !cfg->acc_w || !cfg->acc2_emb || !cfg->acc2_w)) return DES_ERR_INVALID_ARG;
+  if (cfg->opt == DES_OPT_FTRL && (!cfg->acc_w || !cfg->acc2_w)) return DES_ERR_INVALID_ARG;
+  if ((cfg->acc2_emb && !aligned16(cfg->acc2_emb)) || ((uintptr_t)cfg->acc2_w & 3u)) return DES_ERR_INVALID_ARG;
   if (!aligned16(cfg->emb) || !aligned16(cfg->slots) || !aligned16(cfg->workspace) ||
       (cfg->acc_emb && !aligned16(cfg->acc_emb)) || ((uintptr_t)cfg->row_keys & 7u) || ((uintptr_t)cfg->w & 3u))
     return DES_ERR_INVALID_ARG;
@@ -532,11 +541,11 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
     ProfScope ps(KID_INIT_ROWS, s);
     if (values)
       hipLaunchKernelGGL(k_copy_values, dim3(grid_for(n * (c.dim + 1), kBlock, 2048)), dim3(kBlock), 0, s, t->ctrl,
-                         c.dim, values, first_idx, c.emb, c.w, c.acc_emb, c.acc_w, c.capacity_rows);
+                         c.dim, values, first_idx, c.emb, c.w, c.acc_emb, c.acc_w, c.acc2_emb, c.acc2_w, c.capacity_rows);
     else
       hipLaunchKernelGGL(k_init_rows, dim3(grid_for(n * (c.dim / 4 + 1), kBlock, 2048)), dim3(kBlock), 0, s, t->ctrl,
                          c.dim, c.init_seed, t->init_width, c.row_keys, c.emb, c.w, c.acc_emb, c.acc_w,
-                         c.capacity_rows);
+                         c.acc2_emb, c.acc2_w, c.capacity_rows);
   }
   {
     ProfScope ps(KID_PATCH, s);
@@ -643,33 +652,74 @@ des_status_t des_partial_forward_pool(des_table_t *t, const des_batch_t *batch, 
   return pool_dense_launch(t, batch, rows, P_pool, (hipStream_t)stream);
 }
 
+static bool state_ok(const des_table_config_t &c, int opt, bool emb) {
+  const float *s1 = emb ? c.acc_emb : c.acc_w, *s2 = emb ? c.acc2_emb : c.acc2_w;
+  switch (opt) {
+    case DES_OPT_SGD: return true;
+    case DES_OPT_ADAGRAD: return s1 != nullptr;
+    case DES_OPT_ADAM: return s1 != nullptr && s2 != nullptr;
+    case DES_OPT_FTRL: return !emb && s1 != nullptr && s2 != nullptr;
+  }
+  return false;
+}
+
 static des_status_t backward_api(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
-                                 const des_backward_io_t *io, int opt, float lr, float eps, void *stream) {
+                                 const des_backward_io_t *io, const des_optimizer_t *o, void *stream) {
   des_status_t st = check_batch(t, batch, rows);
   if (st != DES_OK) return st;
-  if (!io) return DES_ERR_INVALID_ARG;
+  if (!io || !o) return DES_ERR_INVALID_ARG;
   if ((io->g_fm == nullptr) != (io->A_sum == nullptr)) return DES_ERR_INVALID_ARG;
   if ((io->A_sum && !aligned16(io->A_sum)) || (io->g_pool && !aligned16(io->g_pool))) return DES_ERR_INVALID_ARG;
-  if (opt == DES_OPT_ADAGRAD && (!t->cfg.acc_emb || !t->cfg.acc_w || !(eps > 0.f))) return DES_ERR_INVALID_ARG;
-  if (opt != DES_OPT_NONE && !(lr == lr)) return DES_ERR_INVALID_ARG;
+  const bool merge_only = o->opt_emb == DES_OPT_NONE && o->opt_w == DES_OPT_NONE;
+  if (!merge_only) {
+    if (!state_ok(t->cfg, o->opt_emb, true) || !state_ok(t->cfg, o->opt_w, false)) return DES_ERR_INVALID_ARG;
+    const bool adagrad = o->opt_emb == DES_OPT_ADAGRAD || o->opt_w == DES_OPT_ADAGRAD;
+    const bool adam = o->opt_emb == DES_OPT_ADAM || o->opt_w == DES_OPT_ADAM;
+    if (!(o->lr == o->lr)) return DES_ERR_INVALID_ARG;
+    if ((adagrad || adam) && !(o->eps > 0.f)) return DES_ERR_INVALID_ARG;
+    if (adam && (!(o->beta1 >= 0.f && o->beta1 < 1.f) || !(o->beta2 >= 0.f && o->beta2 < 1.f) || o->step < 1))
+      return DES_ERR_INVALID_ARG;
+    if (o->opt_w == DES_OPT_FTRL && (!(o->ftrl_alpha > 0.f) || !(o->ftrl_beta >= 0.f) || !(o->ftrl_l1 >= 0.f) ||
+                                    !(o->ftrl_l2 >= 0.f)))
+      return DES_ERR_INVALID_ARG;
+  }
   if (256 + backward_ws_bytes(t->cfg.dim, batch->nnz) > t->cfg.workspace_bytes) return DES_ERR_WORKSPACE;
   t->last_stream = (hipStream_t)stream;
-  return backward_launch(t, batch, rows, io, opt, lr, eps, (hipStream_t)stream);
+  return backward_launch(t, batch, rows, io, o, (hipStream_t)stream);
+}
+
+static des_optimizer_t simple_optimizer(int opt, float lr, float eps) {
+  des_optimizer_t o;
+  memset(&o, 0, sizeof(o));
+  o.opt_emb = o.opt_w = opt;
+  o.lr = lr;
+  o.eps = eps;
+  o.step = 1;
+  return o;
 }
 
 des_status_t des_backward_update_sgd(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
                                      const des_backward_io_t *io, float lr, void *stream) {
-  return backward_api(t, batch, rows, io, DES_OPT_SGD, lr, 0.f, stream);
+  const des_optimizer_t o = simple_optimizer(DES_OPT_SGD, lr, 0.f);
+  return backward_api(t, batch, rows, io, &o, stream);
 }
 
 des_status_t des_backward_update_adagrad(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
                                          const des_backward_io_t *io, float lr, float eps, void *stream) {
-  return backward_api(t, batch, rows, io, DES_OPT_ADAGRAD, lr, eps, stream);
+  const des_optimizer_t o = simple_optimizer(DES_OPT_ADAGRAD, lr, eps);
+  return backward_api(t, batch, rows, io, &o, stream);
+}
+
+des_status_t des_backward_update(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
+                                 const des_backward_io_t *io, const des_optimizer_t *optimizer, void *stream) {
+  if (optimizer && (optimizer->opt_emb == DES_OPT_NONE) != (optimizer->opt_w == DES_OPT_NONE)) return DES_ERR_INVALID_ARG;
+  return backward_api(t, batch, rows, io, optimizer, stream);
 }
 
 des_status_t des_backward_merge(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
                                 const des_backward_io_t *io, void *stream) {
-  return backward_api(t, batch, rows, io, DES_OPT_NONE, 0.f, 0.f, stream);
+  const des_optimizer_t o = simple_optimizer(DES_OPT_NONE, 0.f, 0.f);
+  return backward_api(t, batch, rows, io, &o, stream);
 }
 
 }  // extern "C"

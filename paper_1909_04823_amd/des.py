@@ -19,14 +19,15 @@ _lib = C.CDLL(LIB_PATH)
 
 OK, ERR_INVALID_ARG, ERR_INVALID_KEY, ERR_FULL, ERR_WORKSPACE, ERR_DEVICE = range(6)
 SHARD_KEY_HASH, SHARD_FIELD_MOD = 0, 1
-OPT_NONE, OPT_SGD, OPT_ADAGRAD = 0, 1, 2
+OPT_NONE, OPT_SGD, OPT_ADAGRAD, OPT_ADAM, OPT_FTRL = 0, 1, 2, 3, 4
 MISS_ZERO, MISS_INSERT = 0, 1
 
 EXPORTS = [
     "des_table_query_bytes", "des_table_create", "des_table_destroy", "des_table_insert", "des_table_find",
     "des_table_size", "des_table_status", "des_partial_forward_lr", "des_partial_forward_fm",
     "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_fm_finalize",
-    "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_merge", "des_profile_enable",
+    "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge",
+    "des_profile_enable",
     "des_profile_read", "des_status_string",
 ]
 
@@ -36,7 +37,8 @@ class TableConfig(C.Structure):
                 ("shard_policy", C.c_int32), ("opt", C.c_int32), ("init_seed", C.c_uint64),
                 ("init_scale", C.c_float), ("emb", C.c_void_p), ("w", C.c_void_p), ("acc_emb", C.c_void_p),
                 ("acc_w", C.c_void_p), ("row_keys", C.c_void_p), ("slots", C.c_void_p), ("slots_bytes", C.c_size_t),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("acc2_emb", C.c_void_p), ("acc2_w", C.c_void_p)]
 
 
 class BatchDesc(C.Structure):
@@ -48,6 +50,13 @@ class BackwardIO(C.Structure):
     _fields_ = [("g_lr", C.c_void_p), ("g_fm", C.c_void_p), ("A_sum", C.c_void_p), ("g_pool", C.c_void_p),
                 ("uniq_rows_out", C.c_void_p), ("uniq_keys_out", C.c_void_p), ("counts_out", C.c_void_p),
                 ("merged_out", C.c_void_p), ("n_uniq_out", C.c_void_p)]
+
+
+class Optimizer(C.Structure):
+    """des_optimizer_t"""
+    _fields_ = [("opt_emb", C.c_int32), ("opt_w", C.c_int32), ("lr", C.c_float), ("eps", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("step", C.c_int64),
+                ("ftrl_alpha", C.c_float), ("ftrl_beta", C.c_float), ("ftrl_l1", C.c_float), ("ftrl_l2", C.c_float)]
 
 
 class KernelTime(C.Structure):
@@ -71,6 +80,7 @@ _sig = {
     "des_fm_finalize": [vp, vp, i64, i32, vp, vp],
     "des_backward_update_sgd": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), f32, vp],
     "des_backward_update_adagrad": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), f32, f32, vp],
+    "des_backward_update": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), C.POINTER(Optimizer), vp],
     "des_backward_merge": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), vp],
     "des_profile_enable": [i32],
     "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
@@ -130,7 +140,10 @@ class Table:
 
     def __init__(self, dim: int, capacity: int, num_shards: int = 1, shard_policy: int = SHARD_KEY_HASH,
                  opt: int = OPT_ADAGRAD, init_seed: int = 0, init_scale: float = 0.01, max_n: int = 1 << 20,
-                 device="cuda"):
+                 device="cuda", state_arrays=None):
+        """`opt` decides which optimizer state arrays are allocated (Adagrad: one per weight,
+        Adam: two, FTRL: two for the LR weight); `state_arrays=(n_emb, n_w)` overrides that for
+        mixed settings such as Adagrad embeddings with FTRL order-1 weights (1, 2)."""
         self.dim, self.capacity, self.K = int(dim), int(capacity), int(num_shards)
         self.max_n = int(max_n)
         cfg = TableConfig()
@@ -141,15 +154,25 @@ class Table:
         dev = torch.device(device)
         self.emb = torch.empty((self.capacity, self.dim), dtype=torch.float32, device=dev)
         self.w = torch.empty((self.capacity,), dtype=torch.float32, device=dev)
-        adagrad = opt == OPT_ADAGRAD
-        self.acc_emb = torch.empty((self.capacity, self.dim), dtype=torch.float32, device=dev) if adagrad else None
-        self.acc_w = torch.empty((self.capacity,), dtype=torch.float32, device=dev) if adagrad else None
+        # opt says which state arrays to allocate: ADAGRAD one per weight, ADAM two, FTRL two for the LR weight
+        if state_arrays is None:
+            n_emb = {OPT_ADAGRAD: 1, OPT_ADAM: 2}.get(opt, 0)
+            n_w = {OPT_ADAGRAD: 1, OPT_ADAM: 2, OPT_FTRL: 2}.get(opt, 0)
+        else:
+            n_emb, n_w = state_arrays
+            cfg.opt = OPT_NONE                     # each update call checks the arrays it needs
+        mk = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+        self.acc_emb = mk(self.capacity, self.dim) if n_emb >= 1 else None
+        self.acc2_emb = mk(self.capacity, self.dim) if n_emb >= 2 else None
+        self.acc_w = mk(self.capacity) if n_w >= 1 else None
+        self.acc2_w = mk(self.capacity) if n_w >= 2 else None
         self.row_keys = torch.empty((self.capacity,), dtype=torch.int64, device=dev)
         self.slots = torch.empty((sb.value,), dtype=torch.uint8, device=dev)
         self.workspace = torch.empty((wb.value,), dtype=torch.uint8, device=dev)
         cfg.emb, cfg.w, cfg.acc_emb, cfg.acc_w = _ptr(self.emb), _ptr(self.w), _ptr(self.acc_emb), _ptr(self.acc_w)
         cfg.row_keys, cfg.slots, cfg.slots_bytes = _ptr(self.row_keys), _ptr(self.slots), sb.value
         cfg.workspace, cfg.workspace_bytes = _ptr(self.workspace), wb.value
+        cfg.acc2_emb, cfg.acc2_w = _ptr(self.acc2_emb), _ptr(self.acc2_w)
         self.cfg = cfg
         torch.cuda.synchronize()
         h = vp()
@@ -221,6 +244,11 @@ class Table:
         io = self._io(g_lr, g_fm, A_sum, g_pool, dbg)
         _check(_lib.des_backward_update_adagrad(self._h, C.byref(batch.desc), _ptr(rows), C.byref(io), lr, eps,
                                                 _stream()), "des_backward_update_adagrad")
+
+    def backward_update(self, batch, rows, optimizer: Optimizer, g_lr=None, g_fm=None, A_sum=None, g_pool=None, dbg=None):
+        io = self._io(g_lr, g_fm, A_sum, g_pool, dbg)
+        _check(_lib.des_backward_update(self._h, C.byref(batch.desc), _ptr(rows), C.byref(io), C.byref(optimizer),
+                                        _stream()), "des_backward_update")
 
     def backward_merge(self, batch, rows, g_lr=None, g_fm=None, A_sum=None, g_pool=None, dbg=None):
         io = self._io(g_lr, g_fm, A_sum, g_pool, dbg)

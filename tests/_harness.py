@@ -47,12 +47,13 @@ def host_u64(t):
 class Pair:
     """An oracle table and a library table built from the same description."""
 
-    def __init__(self, oracle, des, D, capacity, K, policy, opt, seed=1234, init_scale=0.01, max_n=1 << 16):
+    def __init__(self, oracle, des, D, capacity, K, policy, opt, seed=1234, init_scale=0.01, max_n=1 << 16,
+                 state_arrays=None):
         self.oracle, self.des = oracle, des
         self.D, self.K, self.policy, self.opt = D, K, policy, opt
         self.ot = oracle.Table(D, capacity, seed=seed, init_scale=init_scale)
         self.gt = des.Table(D, capacity, num_shards=K, shard_policy=policy, opt=opt, init_seed=seed,
-                            init_scale=init_scale, max_n=max_n)
+                            init_scale=init_scale, max_n=max_n, state_arrays=state_arrays)
 
     def close(self):
         self.gt.close()
@@ -72,9 +73,10 @@ class Pair:
         cmp = assert_equal if exact else assert_close
         cmp(self.gt.emb[:n].cpu().numpy(), self.ot.emb, what + " emb")
         cmp(self.gt.w[:n].cpu().numpy(), self.ot.w, what + " w")
-        if self.gt.acc_emb is not None:
-            cmp(self.gt.acc_emb[:n].cpu().numpy(), self.ot.acc_emb, what + " acc_emb")
-            cmp(self.gt.acc_w[:n].cpu().numpy(), self.ot.acc_w, what + " acc_w")
+        for name in ("acc_emb", "acc_w", "acc2_emb", "acc2_w"):
+            g = getattr(self.gt, name)
+            if g is not None:
+                cmp(g[:n].cpu().numpy(), getattr(self.ot, name), what + " " + name)
 
     # ---- one batch through both sides ---------------------------------------------------------
     def find(self, batch, insert=True):
@@ -127,17 +129,22 @@ class Pair:
         self.fwd = {"A_lr": A_lr, "A_sum": A_sum, "fm2": fm2, "pool": pool_ref}
         return A_sum.astype(np.float32)
 
-    def backward(self, batch, g_lr, g_fm, A_sum, g_pool, lr=0.05, eps=1e-8, opt=None):
+    def backward(self, batch, g_lr, g_fm, A_sum, g_pool, lr=0.05, eps=1e-8, opt=None, optimizer=None):
+        """`optimizer`: dict of des_optimizer_t fields (separate optimizers for latent vectors and
+        LR weights); otherwise `opt`, `lr`, `eps` for both."""
         import torch
         o, d = self.oracle, self.des
         opt = self.opt if opt is None else opt
         B, F = batch.B, batch.F
+        o_opt = None if optimizer is None else o.Optimizer(**optimizer)
         ref = self.ot.backward_update(B, F, batch.offsets, self.rows_o, g_lr, g_fm, A_sum, g_pool, opt, lr, eps,
-                                      vals=batch.vals)
+                                      vals=batch.vals, optimizer=o_opt)
         dbg = self.gt.debug_buffers(max(batch.nnz, 1))
         args = dict(g_lr=dev(g_lr, torch), g_fm=dev(g_fm, torch), A_sum=dev(A_sum, torch), g_pool=dev(g_pool, torch),
                     dbg=dbg)
-        if opt == d.OPT_SGD:
+        if optimizer is not None:
+            self.gt.backward_update(self.gb, self.rows_g, d.Optimizer(**optimizer), **args)
+        elif opt == d.OPT_SGD:
             self.gt.backward_update_sgd(self.gb, self.rows_g, lr, **args)
         elif opt == d.OPT_ADAGRAD:
             self.gt.backward_update_adagrad(self.gb, self.rows_g, lr, eps, **args)

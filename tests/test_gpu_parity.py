@@ -255,6 +255,45 @@ def test_merge_segment_length_boundaries(oracle, des, D, with_vals):
     p.close()
 
 
+@pytest.mark.parametrize("emb,w_opt", [("ADAM", "ADAM"), ("ADAGRAD", "FTRL"), ("ADAM", "FTRL"), ("SGD", "FTRL")])
+def test_paper_optimizer_settings(oracle, des, emb, w_opt):
+    """FTRL for the order-1 weights with Adagrad or Adam for the embeddings (the setting of the
+    paper's experiments), and Adam for both: three steps on a growing table, so second moments,
+    the step counter and rows inserted later are all exercised."""
+    import torch
+    w = synth.workload(1, scale=1 / 32, D=32, K=4)
+    oe, ow = getattr(des, "OPT_" + emb), getattr(des, "OPT_" + w_opt)
+    nnz_hint = int(w.B * w.F * (w.mean_bag() * 1.3 + 2)) + 1024
+    p = Pair(oracle, des, w.D, w.capacity, w.K, 0, des.OPT_NONE, seed=w.seed, init_scale=w.init_std,
+             max_n=max(nnz_hint, w.preinsert + 16), state_arrays=(2, 2))
+    keys0 = synth.preinsert_keys(w)
+    p.ot.insert(keys0)
+    p.gt.insert(dev(keys0, torch))
+    p.check_table("pre-insert")
+    for step in range(3):
+        batch = synth.gen_batch(w, step)
+        p.find(batch, insert=True)
+        A_sum = p.forward(batch)
+        g_lr, g_fm, g_pool = synth.upstream_gradients(w, step)
+        opt = dict(opt_emb=oe, opt_w=ow, lr=0.01, eps=1e-8, beta1=0.9, beta2=0.999, step=step + 1,
+                   ftrl_alpha=0.05, ftrl_beta=1.0, ftrl_l1=1e-4, ftrl_l2=0.1)
+        p.backward(batch, g_lr, g_fm, A_sum, g_pool, optimizer=opt)
+        p.check_weights(f"{emb}/{w_opt} step {step}")
+    if w_opt == "FTRL":
+        n = p.ot.n_rows
+        assert (p.gt.w[:n] == 0).any() and (p.gt.w[:n] != 0).any()      # the l1 threshold is active on some rows
+    # an optimizer without its state arrays is refused before anything is enqueued
+    q = des.Table(8, 64, 1, opt=des.OPT_SGD, max_n=1024)
+    kb = des.Batch(1, 1, torch.tensor([5], dtype=torch.int64, device="cuda"), torch.tensor([0, 1], dtype=torch.int32, device="cuda"))
+    r = q.find(kb.keys, des.MISS_INSERT)
+    with pytest.raises(des.DesError) as e:
+        q.backward_update(kb, r, des.Optimizer(des.OPT_ADAM, des.OPT_ADAM, 0.01, 1e-8, 0.9, 0.999, 1, 0, 0, 0, 0),
+                          g_lr=torch.ones(1, device="cuda"))
+    assert e.value.code == des.ERR_INVALID_ARG
+    q.close()
+    p.close()
+
+
 def test_integers_are_deterministic_run_to_run(oracle, des):
     import torch
     w = synth.workload(3, scale=1 / 128)

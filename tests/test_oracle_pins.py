@@ -342,6 +342,81 @@ def test_sgd_and_adagrad_closed_forms(oracle):
     np.testing.assert_array_equal(np.concatenate([t.acc_emb, t.acc_w[:, None]], axis=1), a2.astype(np.float32))
 
 
+def _one_row_problem(oracle, D=2):
+    """One sample, one bag per key: row r's merged gradient is exactly g_pool[0, r, :] and g_lr[0]."""
+    t = oracle.Table(D, 4)
+    t.insert(np.array([7, 8], np.uint64), np.zeros((2, D + 1), np.float32))
+    keys = np.array([7, 8], np.uint64)
+    offsets = np.array([0, 1, 2], np.int32)
+    return t, keys, offsets, t.find(keys)
+
+
+def test_adam_constant_gradient_moves_by_lr_every_step(oracle):
+    """Adam with bias correction and a constant gradient g has m_hat = g and v_hat = g^2 at every
+    step, so each step moves the weight by exactly lr*g/(|g|+eps) (Kingma & Ba, Section 2:
+    the effective step is bounded by lr and equals it for a consistent gradient sign)."""
+    t, keys, offsets, rows = _one_row_problem(oracle)
+    g_pool = np.array([[[0.3, -2.0], [1e-3, 5.0]]], np.float32)
+    g_lr = np.array([0.7], np.float32)
+    lr, eps = 0.01, 1e-8
+    for step in range(1, 6):
+        o = oracle.Optimizer(oracle.OPT_ADAM, oracle.OPT_ADAM, lr, eps, 0.9, 0.999, step, 0, 0, 0, 0)
+        t.backward_update(1, 2, offsets, rows, g_lr, None, None, g_pool, optimizer=o)
+        G = g_pool[0].astype(np.float64)
+        np.testing.assert_allclose(t.emb, -step * lr * G / (np.abs(G) + eps), rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(t.w, -step * lr * 0.7 / (0.7 + eps) * np.ones(2), rtol=2e-6)
+        b1, b2 = float(np.float32(0.9)), float(np.float32(0.999))     # the rates as the fp32 arguments carry them
+        np.testing.assert_allclose(t.acc_emb, (1 - b1 ** step) * G, rtol=1e-6)             # first moment
+        np.testing.assert_allclose(t.acc2_emb, (1 - b2 ** step) * G * G, rtol=1e-6)        # second moment
+    # a step counter that does not advance breaks the invariant (the pin is sensitive to it)
+    o = oracle.Optimizer(oracle.OPT_ADAM, oracle.OPT_ADAM, lr, eps, 0.9, 0.999, 1, 0, 0, 0, 0)
+    before = t.emb.copy()
+    t.backward_update(1, 2, offsets, rows, g_lr, None, None, g_pool, optimizer=o)
+    assert np.abs((t.emb - before) / (lr * np.sign(g_pool[0])) + 1).max() > 0.5
+
+
+def test_ftrl_without_regularisation_is_per_coordinate_gradient_descent(oracle):
+    """FTRL-Proximal with l1 = l2 = 0, started from w = 0, produces the same iterates as online
+    gradient descent with the per-coordinate rate alpha/(beta + sqrt(sum g^2)) (McMahan et al.
+    2013, Section 3) -- evaluated here as that plain recurrence."""
+    t, keys, offsets, rows = _one_row_problem(oracle)
+    rng = np.random.default_rng(4)
+    alpha, beta = 0.1, 1.0
+    w_ref, n_ref = 0.0, 0.0
+    for step in range(8):
+        g = float(rng.standard_normal())
+        g_lr = np.array([g], np.float32)
+        o = oracle.Optimizer(oracle.OPT_SGD, oracle.OPT_FTRL, 0.0, 1e-8, 0, 0, 1, alpha, beta, 0.0, 0.0)
+        t.backward_update(1, 2, offsets, rows, g_lr, None, None, None, optimizer=o)
+        gf = float(np.float32(g))
+        n_ref += gf * gf
+        w_ref -= alpha / (beta + np.sqrt(n_ref)) * gf
+        np.testing.assert_allclose(t.w, [w_ref, w_ref], rtol=2e-5, atol=1e-7)
+        np.testing.assert_allclose(t.acc_w, [n_ref, n_ref], rtol=1e-6)
+    assert not t.emb.any()                                   # lr = 0 SGD leaves the latent vectors alone
+
+
+def test_ftrl_first_step_closed_form_and_l1_threshold(oracle):
+    t, keys, offsets, rows = _one_row_problem(oracle)
+    alpha, beta, l1, l2 = 0.05, 1.0, 0.5, 0.1
+    # sample 0 feeds both rows the same g_lr; use two calls with gradients below / above the threshold
+    for g, expect_zero in ((0.3, True), (2.0, False)):
+        t2, _, _, rows2 = _one_row_problem(oracle)
+        o = oracle.Optimizer(oracle.OPT_SGD, oracle.OPT_FTRL, 0.0, 1e-8, 0, 0, 1, alpha, beta, l1, l2)
+        t2.backward_update(1, 2, offsets, rows2, np.array([g], np.float32), None, None, None, optimizer=o)
+        gf = float(np.float32(g))
+        # from z = n = w = 0: sigma*w = 0, z = g, n = g^2
+        expect = 0.0 if expect_zero else -(gf - l1) / ((beta + abs(gf)) / alpha + l2)
+        np.testing.assert_allclose(t2.w, [expect, expect], rtol=1e-6, atol=0)
+        np.testing.assert_allclose(t2.acc2_w, [gf, gf], rtol=1e-7)
+        np.testing.assert_allclose(t2.acc_w, [gf * gf, gf * gf], rtol=1e-6)
+    # symmetric in the sign of the gradient
+    t3, _, _, rows3 = _one_row_problem(oracle)
+    o = oracle.Optimizer(oracle.OPT_SGD, oracle.OPT_FTRL, 0.0, 1e-8, 0, 0, 1, alpha, beta, l1, l2)
+    t3.backward_update(1, 2, offsets, rows3, np.array([-2.0], np.float32), None, None, None, optimizer=o)
+    np.testing.assert_allclose(t3.w, -t2.w, rtol=1e-7)
+
+
 def test_backward_uses_pre_update_weights_and_skips_absent_rows(oracle):
     D = 2
     t = oracle.Table(D, 4)
