@@ -66,6 +66,10 @@ def lib():
         L.oracle_backward_update_opt.restype = i64
         L.oracle_backward_update_opt.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, C.POINTER(Optimizer),
                                                  vp, vp, vp, vp]
+        L.oracle_dnn_partial_forward.restype = None
+        L.oracle_dnn_partial_forward.argtypes = [vp, vp, i64, i32, C.c_int, C.c_int, C.c_int, vp]
+        L.oracle_dnn_backward.restype = None
+        L.oracle_dnn_backward.argtypes = [vp, vp, vp, i64, i32, C.c_int, C.c_int, vp, vp]
         _lib = L
     return _lib
 
@@ -221,3 +225,28 @@ def fm_finalize(A_sum: np.ndarray, A_sq: np.ndarray) -> np.ndarray:
     out = np.empty(B, np.float64)
     lib().oracle_fm_finalize(_p(A_sum), _p(A_sq), B, D, _p(out))
     return out
+
+
+def dnn_partial_forward(pool: np.ndarray, W: np.ndarray, K: int) -> np.ndarray:
+    """Per-shard partials Y_partial[K,B,H] (float64) of the first fully-connected layer; pool is
+    [B,F,D] fp32, W is [F*D,H] fp32, shard of field f is f mod K."""
+    pool, W = _c(pool, np.float32), _c(W, np.float32)
+    B, F, D = pool.shape
+    H = W.shape[1]
+    if W.shape[0] != F * D:
+        raise ValueError("W must be [F*D, H]")
+    out = np.empty((K, B, H), np.float64)
+    lib().oracle_dnn_partial_forward(_p(pool), _p(W), B, F, D, H, K, _p(out))
+    return out
+
+
+def dnn_backward(pool: np.ndarray, W: np.ndarray, dY: np.ndarray):
+    """(g_pool[B,F,D], dW[F*D,H]) in float64 for the upstream gradient dY[B,H] of the aggregate."""
+    pool, W, dY = _c(pool, np.float32), _c(W, np.float32), _c(dY, np.float32)
+    B, F, D = pool.shape
+    H = W.shape[1]
+    if W.shape[0] != F * D or dY.shape != (B, H):
+        raise ValueError("shape mismatch")
+    g_pool = np.empty((B, F, D), np.float64); dW = np.empty((F * D, H), np.float64)
+    lib().oracle_dnn_backward(_p(pool), _p(W), _p(dY), B, F, D, H, _p(g_pool), _p(dW))
+    return g_pool, dW

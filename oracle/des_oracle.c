@@ -17,6 +17,7 @@
  *   FM partials M1, M2 and F ........... Section 4.2, Eq. (fm_m1m2), Eq. (des_fm2)
  *   per-field pooling .................. Section 4.3 (latent vectors aggregated by field)
  *   aggregation (+) .................... Section 3.2.1, Eq. (1); Algorithm 1
+ *   DNN first layer partial M1 ......... Section 4.3, Eq. (dnn_bmm), Eq. (dnn_des)
  *   backward ........................... Section 3.2.2, "Back-propagation Phase": the gradient
  *                                        of the aggregate reaches every sub-operator unchanged
  *
@@ -382,4 +383,47 @@ int64_t oracle_backward_update(oracle_table *t, int64_t B, int32_t F, const int3
   o.opt_emb = o.opt_w = opt; o.lr = lr; o.eps = eps; o.step = 1;
   return oracle_backward_update_opt(t, B, F, offsets, vals, rows, g_lr, g_fm, A_sum, g_pool, &o, uniq_rows,
                                     uniq_keys, counts, merged);
+}
+
+/* ------------------------------------------------------------------ DNN first layer ------ */
+
+/* Section 4.3, Eq. (dnn_bmm) / (dnn_des): V is the per-sample concatenation of the F pooled
+ * field vectors, pool[B][F][D] (so V^T is [B, F*D]), and W is [F*D][H].  Both are cut along the
+ * field dimension; the shard that holds field f (f mod K, the placement of Section 5) forms
+ * M1(V_s, W_s) = V_s^T W_s:  Y_partial[s][b][h] = sum over its fields f and d of
+ * pool[b][f][d] * W[f*D+d][h].  The aggregation sums the K partials. */
+void oracle_dnn_partial_forward(const float *pool, const float *W, int64_t B, int32_t F, int D, int H, int K,
+                                double *Y_partial) {
+  memset(Y_partial, 0, sizeof(double) * (size_t)K * (size_t)B * (size_t)H);
+  for (int64_t b = 0; b < B; ++b)
+    for (int32_t f = 0; f < F; ++f) {
+      const int s = f % K;
+      for (int d = 0; d < D; ++d) {
+        const double v = (double)pool[(b * F + f) * D + d];
+        const float *wrow = W + ((int64_t)f * D + d) * H;
+        for (int h = 0; h < H; ++h) Y_partial[((int64_t)s * B + b) * H + h] += v * (double)wrow[h];
+      }
+    }
+}
+
+/* Backward of the same layer (Section 3.2.2): the gradient dY[B][H] of the aggregate reaches every
+ * shard unchanged; each shard differentiates its own product, so over all shards
+ * g_pool[b][j] = sum_h dY[b][h] W[j][h]   and   dW[j][h] = sum_b pool[b][j] dY[b][h],  j = f*D+d. */
+void oracle_dnn_backward(const float *pool, const float *W, const float *dY, int64_t B, int32_t F, int D, int H,
+                         double *g_pool, double *dW) {
+  const int64_t J = (int64_t)F * D;
+  if (g_pool)
+    for (int64_t b = 0; b < B; ++b)
+      for (int64_t j = 0; j < J; ++j) {
+        double a = 0.0;
+        for (int h = 0; h < H; ++h) a += (double)dY[b * H + h] * (double)W[j * H + h];
+        g_pool[b * J + j] = a;
+      }
+  if (dW)
+    for (int64_t j = 0; j < J; ++j)
+      for (int h = 0; h < H; ++h) {
+        double a = 0.0;
+        for (int64_t b = 0; b < B; ++b) a += (double)pool[b * J + j] * (double)dY[b * H + h];
+        dW[j * H + h] = a;
+      }
 }

@@ -230,6 +230,68 @@ def test_partial_sizes_reproduce_printed_comm_saving_table(oracle):
         assert f"{100 * (1 - 2 * s_fm / (U * (8 + 4 * d))):.3f}" == r_fm
 
 
+# --------------------------------------------------------------------------- DNN layer -----
+def test_dnn_partials_are_the_blocks_of_the_blocked_product(oracle):
+    """Eq. (dnn_bmm): shard s's partial is the product restricted to its fields (f mod K == s),
+    and the partials add up to the unsplit V^T W (numpy float64 matmul)."""
+    pool = np.array([[[2.0], [3.0]]], np.float32)                  # B=1, F=2, D=1
+    W = np.array([[1.0, 10.0], [100.0, 1000.0]], np.float32)
+    assert oracle.dnn_partial_forward(pool, W, 2).tolist() == [[[2.0, 20.0]], [[300.0, 3000.0]]]
+    assert oracle.dnn_partial_forward(pool, W, 1).tolist() == [[[302.0, 3020.0]]]
+    rng = np.random.default_rng(11)
+    B, F, D, H = 5, 7, 4, 6
+    pool = rng.standard_normal((B, F, D)).astype(np.float32)
+    W = rng.standard_normal((F * D, H)).astype(np.float32)
+    full = pool.reshape(B, F * D).astype(np.float64) @ W.astype(np.float64)
+    for K in (1, 3, 4, 9):
+        Y = oracle.dnn_partial_forward(pool, W, K)
+        assert Y.shape == (K, B, H)
+        for s in range(K):
+            fs = [f for f in range(F) if f % K == s]
+            blk = np.zeros((B, H))
+            for f in fs:
+                blk += pool[:, f, :].astype(np.float64) @ W[f * D:(f + 1) * D].astype(np.float64)
+            np.testing.assert_allclose(Y[s], blk, rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(oracle.aggregate(Y), full, rtol=1e-13, atol=1e-13)
+
+
+def test_dnn_backward_is_the_adjoint_of_the_forward(oracle):
+    """The layer is bilinear, so with L = <dY, Y>: moving one input element by 1 changes L by exactly
+    that element's gradient.  Checked through the oracle's own sharded forward, element by element."""
+    rng = np.random.default_rng(12)
+    B, F, D, H, K = 3, 4, 4, 5, 3
+    pool = rng.integers(-4, 5, (B, F, D)).astype(np.float32)       # small integers: every sum is exact
+    W = rng.integers(-4, 5, (F * D, H)).astype(np.float32)
+    dY = rng.integers(-4, 5, (B, H)).astype(np.float32)
+    L = lambda p, w: float((oracle.aggregate(oracle.dnn_partial_forward(p, w, K)) * dY).sum())
+    g_pool, dW = oracle.dnn_backward(pool, W, dY)
+    L0 = L(pool, W)
+    for idx in np.ndindex(B, F, D):
+        p = pool.copy(); p[idx] += 1
+        assert L(p, W) - L0 == g_pool[idx]
+    for idx in np.ndindex(F * D, H):
+        w = W.copy(); w[idx] += 1
+        assert L(pool, w) - L0 == dW[idx]
+
+
+def test_dnn_partial_size_reproduces_printed_comm_saving_column(oracle):
+    """R_dnn = 1 - 2 S_M1 / (S_k + S_V + S_W) (Section 4.3) with S_M1 the bytes of one shard's [B,H]
+    fp32 partial.  The paper prints neither H nor S_W; H = 256 and the S_W that the first row implies
+    reproduce the other four printed rows to every digit, which a partial of any other shape
+    (per-field, or with the latent dimension in it) does not."""
+    d, H = 8, 256
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table2_comm_saving.txt"))
+            if l.strip() and not l.startswith("#")]
+    size = lambda B: oracle.dnn_partial_forward(np.zeros((B, 2, d), np.float32), np.zeros((2 * d, H), np.float32),
+                                                4)[0].size * 4
+    B0, U0, r0 = int(rows[0][0]), int(rows[0][1]), float(rows[0][4])
+    S_W = 2 * size(B0) / (1 - r0 / 100) - U0 * (8 + 4 * d)
+    for B, U, _, _, r in rows[1:]:
+        B, U = int(B), int(U)
+        got = 100 * (1 - 2 * size(B) / (U * (8 + 4 * d) + S_W))
+        assert abs(got - float(r)) < 1.5e-3, (B, got, r)
+
+
 # --------------------------------------------------------------------------- backward ------
 def scalar_objective(oracle, t, B, F, keys, offsets, vals, rows, c_lr, c_fm, c_pool):
     P = t.partial_forward(B, F, keys, offsets, rows, 3, 0, vals)
