@@ -152,6 +152,34 @@ des_status_t des_aggregate_partials(const float *P, int32_t K, int64_t n, float 
 des_status_t des_fm_finalize(const float *A_sum, const float *A_sq, int64_t B, int32_t D,
                              float *fm2, void *stream);
 
+/* First fully-connected layer of the DNN tower under DES, Section 4.3, Eq. (dnn_bmm) and Eq. (dnn_des).
+ * V^T (the pooled embeddings concatenated over fields, pool[B,F,D] = [B, F*D]) and W[F*D, H] are
+ * both cut along the field dimension; shard s = f mod K owns field f (the placement of Section 5)
+ * and forms M1(V_s, W_s) = V_s^T W_s:
+ *     Y_partial[s,b,h] = sum over fields f of shard s, d < D of  pool[b,f,d] * W[f*D+d, h].
+ * des_aggregate_partials(Y_partial, K, B*H) then gives the layer output.  A shard with no field
+ * (K > F) writes zeros.  fp32 in and out; products accumulate in fp32 on the matrix cores in
+ * ascending k within 16-wide tiles.
+ * pool, W, Y_partial: device, 16-byte aligned, row-major as written; Y_partial [K,B,H] is owned by
+ * the caller and fully overwritten.  D and H multiples of 4, 1 <= K <= 256, B < 2^31, F*D < 2^31,
+ * else DES_ERR_INVALID_ARG.  B == 0 is a no-op (for the backward too: dW is then left untouched). */
+des_status_t des_dnn_partial_forward(const float *pool, const float *W, int64_t B, int32_t F, int32_t D,
+                                     int32_t H, int32_t K, float *Y_partial, void *stream);
+
+/* Backward of that layer (Section 3.2.2: the gradient dY[B,H] of the aggregate reaches every shard
+ * unchanged, each shard differentiates its own block, nothing is exchanged):
+ *     g_pool[b, j] = sum_h dY[b,h] * W[j,h]        (the g_pool input of des_backward_update*)
+ *     dW[j, h]     = sum_b pool[b,j] * dY[b,h]      j = f*D + d
+ * Either output may be null (skipped), not both.  dW is computed in up to 16 slices of samples
+ * that are summed in double; the slices live in `workspace` (device, 16-byte aligned, at least
+ * des_dnn_backward_bytes() bytes; may be null when B <= 16).  Same shape rules as the forward;
+ * DES_ERR_WORKSPACE if the workspace is too small.  The weight update of W itself is the
+ * caller's (a dense optimizer step, outside the sparse path). */
+des_status_t des_dnn_backward_bytes(int64_t B, int32_t F, int32_t D, int32_t H, size_t *workspace_bytes);
+des_status_t des_dnn_backward(const float *pool, const float *W, const float *dY, int64_t B, int32_t F,
+                              int32_t D, int32_t H, float *g_pool, float *dW, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
 /* Backward (Section 3.2.2, back-propagation phase: the gradient of each aggregate goes
  * unchanged to every shard's sub-operator; no exchange), duplicate-key merge and optimizer
  * update (Section 5: "given the gradient of a weight, we apply it locally, and then update").

@@ -381,7 +381,8 @@ const char *kKernelNames[KID_COUNT] = {
     "forward_gather_pool", "forward_pool_dense", "aggregate_partials", "fm_finalize",
     "backward_expand", "sort_histogram", "sort_scan", "sort_scatter",
     "backward_segment_heads", "backward_classify", "backward_short_update", "backward_long_partial",
-    "backward_long_final", "backward_export", "fill"};
+    "backward_long_final", "backward_export", "fill",
+    "dnn_forward", "dnn_grad_pool", "dnn_grad_weights"};
 }  // namespace
 
 void prof_begin(int kid, hipStream_t s) {

@@ -27,8 +27,8 @@ EXPORTS = [
     "des_table_size", "des_table_status", "des_partial_forward_lr", "des_partial_forward_fm",
     "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_fm_finalize",
     "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge",
-    "des_profile_enable",
-    "des_profile_read", "des_status_string",
+    "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
+    "des_profile_enable", "des_profile_read", "des_status_string",
 ]
 
 
@@ -82,6 +82,9 @@ _sig = {
     "des_backward_update_adagrad": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), f32, f32, vp],
     "des_backward_update": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), C.POINTER(Optimizer), vp],
     "des_backward_merge": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), vp],
+    "des_dnn_partial_forward": [vp, vp, i64, i32, i32, i32, i32, vp, vp],
+    "des_dnn_backward_bytes": [i64, i32, i32, i32, C.POINTER(C.c_size_t)],
+    "des_dnn_backward": [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, C.c_size_t, vp],
     "des_profile_enable": [i32],
     "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
 }
@@ -279,6 +282,42 @@ def fm_finalize(A_sum: torch.Tensor, A_sq: torch.Tensor, out: Optional[torch.Ten
         out = torch.empty(B, dtype=torch.float32, device=A_sum.device)
     _check(_lib.des_fm_finalize(_ptr(A_sum), _ptr(A_sq), B, D, _ptr(out), _stream()), "des_fm_finalize")
     return out
+
+
+def dnn_partial_forward(pool: torch.Tensor, W: torch.Tensor, K: int,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y_partial[K,B,H] of the first fully-connected layer; pool [B,F,D], W [F*D,H], fp32 on the device."""
+    B, F, D = pool.shape
+    H = W.shape[1]
+    if W.shape[0] != F * D or not (pool.is_contiguous() and W.is_contiguous()):
+        raise ValueError("W must be [F*D, H]; both operands contiguous")
+    if out is None:
+        out = torch.empty((K, B, H), dtype=torch.float32, device=pool.device)
+    _check(_lib.des_dnn_partial_forward(_ptr(pool), _ptr(W), B, F, D, H, K, _ptr(out), _stream()),
+           "des_dnn_partial_forward")
+    return out
+
+
+def dnn_backward_bytes(B: int, F: int, D: int, H: int) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.des_dnn_backward_bytes(B, F, D, H, C.byref(n)), "des_dnn_backward_bytes")
+    return int(n.value)
+
+
+def dnn_backward(pool: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, g_pool: Optional[torch.Tensor],
+                 dW: Optional[torch.Tensor], workspace: Optional[torch.Tensor] = None):
+    """g_pool[B,F,D] = dY W^T and dW[F*D,H] = V dY into the given tensors (either may be None)."""
+    B, F, D = pool.shape
+    H = W.shape[1]
+    if W.shape[0] != F * D or tuple(dY.shape) != (B, H):
+        raise ValueError("shape mismatch")
+    for t in (pool, W, dY, g_pool, dW):
+        if t is not None and not t.is_contiguous():
+            raise ValueError("operands must be contiguous")
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.des_dnn_backward(_ptr(pool), _ptr(W), _ptr(dY), B, F, D, H, _ptr(g_pool), _ptr(dW),
+                                 _ptr(workspace), nbytes, _stream()), "des_dnn_backward")
+    return g_pool, dW
 
 
 def profile_enable(on: bool):

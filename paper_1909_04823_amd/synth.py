@@ -290,3 +290,14 @@ def head_weights(w: Workload) -> np.ndarray:
     """Fixed (untrained) [F, D] read-out of the pooled embeddings used by the tiny loss head."""
     rng = _step_rng(w, 0, stream=5)
     return (rng.standard_normal((w.F, w.D)) / np.sqrt(w.F * w.D)).astype(np.float32)
+
+
+def dnn_layer_inputs(seed: int, B: int, F: int, D: int, H: int):
+    """Inputs of the first fully-connected layer at the magnitudes training sees: pooled embeddings
+    pool[B,F,D] ~ N(0, 0.05^2) (a few initialised rows summed), weights W[F*D,H] ~ N(0, 1/(F*D))
+    (fan-in scaling) and an upstream gradient dY[B,H] ~ N(0, 0.01^2)."""
+    rng = np.random.default_rng((int(seed), 0xD77))
+    pool = (0.05 * rng.standard_normal((B, F, D), dtype=np.float32)).astype(np.float32)
+    W = (rng.standard_normal((F * D, H), dtype=np.float32) / np.float32(np.sqrt(F * D))).astype(np.float32)
+    dY = (0.01 * rng.standard_normal((B, H), dtype=np.float32)).astype(np.float32)
+    return pool, W, dY
