@@ -133,6 +133,9 @@ def main():
     ap.add_argument("--batches", type=int, default=0, help="distinct pre-generated batches (default 8, fewer for huge ones)")
     ap.add_argument("--cpu-lookups", type=float, default=1e7,
                     help="size of the oracle's timed sample, in lookups (about 10 s of single-thread CPU work)")
+    ap.add_argument("--dnn-hidden", type=int, default=256,
+                    help="width H of the first fully-connected layer measured after the sparse step and reported "
+                         "under \"dnn_layer\" (0 to skip)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -155,7 +158,64 @@ def main():
             r = run_workload(args, idx, cpu=False)
             out["also"].append({k: r[k] for k in ("value", "unit", "samples_per_s", "ms_per_step", "steps", "warmup",
                                                   "config", "roofline", "kernels")})
+    if args.dnn_hidden > 0:
+        torch.cuda.empty_cache()
+        out["dnn_layer"] = run_dnn_layer(args, args.config)
     print(json.dumps(out))
+
+
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def run_dnn_layer(args, index):
+    """The first fully-connected layer under DES at the workload's shape (outside `value`: it is the
+    dense step that follows the sparse path): K per-shard partials + their aggregation, then the
+    backward products g_pool = dY W^T and dW = V dY.  Timed per kernel with HIP events on the launch
+    stream; flops = 2*B*F*D*H per product, against the dense fp32 matrix-core peak."""
+    import torch
+    from paper_1909_04823_amd import des, synth
+    w = synth.workload(index, scale=args.scale)
+    B, F, D, K, H = w.B, w.F, w.D, w.K, args.dnn_hidden
+    gen = torch.Generator(device="cuda"); gen.manual_seed(7)
+    pool = torch.randn((B, F, D), device="cuda", generator=gen) * 0.05
+    W = torch.randn((F * D, H), device="cuda", generator=gen) / float(np.sqrt(F * D))
+    dY = torch.randn((B, H), device="cuda", generator=gen) * 0.01
+    Yp = torch.empty((K, B, H), device="cuda"); Y = torch.empty((B, H), device="cuda")
+    g_pool = torch.empty((B, F, D), device="cuda"); dW = torch.empty((F * D, H), device="cuda")
+    ws = torch.empty(des.dnn_backward_bytes(B, F, D, H), dtype=torch.uint8, device="cuda")
+
+    def layer():
+        des.dnn_partial_forward(pool, W, K, out=Yp)
+        des.aggregate_partials(Yp, Y)
+        des.dnn_backward(pool, W, dY, g_pool, dW, ws)
+
+    reps = max(3, min(args.steps, 10))
+    for _ in range(2):
+        layer()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        layer()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / reps
+    des.profile_enable(True)
+    for _ in range(reps):
+        layer()
+    prof = des.profile_read()
+    des.profile_enable(False)
+    flops = 2.0 * B * F * D * H
+    kernels = {}
+    for name, (launches, total_ms) in prof.items():
+        per = total_ms / reps
+        e = {"launches_per_pass": launches / reps, "ms_per_pass": round(per, 4)}
+        if name.startswith("dnn_") and per > 0:
+            e["TFLOPs"] = round(flops / (per * 1e-3) / 1e12, 2)
+            e["frac_of_fp32_mfma_peak"] = round(e["TFLOPs"] / FP32_MFMA_PEAK_TFLOPS, 4)
+        kernels[name] = e
+    assert bool(torch.isfinite(Y).all()) and bool(torch.isfinite(dW).all())
+    return {"workload": f"configs[{w.index}] {w.name}", "B": B, "F": F, "D": D, "H": H, "K": K, "dtype": "f32",
+            "ms_per_pass": round(ms, 4), "flops_per_product": flops, "peak_TFLOPs": FP32_MFMA_PEAK_TFLOPS,
+            "kernels": kernels}
 
 
 def run_workload(args, index, cpu):

@@ -240,13 +240,15 @@ def dnn_partial_forward(pool: np.ndarray, W: np.ndarray, K: int) -> np.ndarray:
     return out
 
 
-def dnn_backward(pool: np.ndarray, W: np.ndarray, dY: np.ndarray):
-    """(g_pool[B,F,D], dW[F*D,H]) in float64 for the upstream gradient dY[B,H] of the aggregate."""
+def dnn_backward(pool: np.ndarray, W: np.ndarray, dY: np.ndarray, want_g_pool: bool = True, want_dW: bool = True):
+    """(g_pool[B,F,D], dW[F*D,H]) in float64 for the upstream gradient dY[B,H] of the aggregate
+    (None for an output that is not wanted)."""
     pool, W, dY = _c(pool, np.float32), _c(W, np.float32), _c(dY, np.float32)
     B, F, D = pool.shape
     H = W.shape[1]
     if W.shape[0] != F * D or dY.shape != (B, H):
         raise ValueError("shape mismatch")
-    g_pool = np.empty((B, F, D), np.float64); dW = np.empty((F * D, H), np.float64)
+    g_pool = np.empty((B, F, D), np.float64) if want_g_pool else None
+    dW = np.empty((F * D, H), np.float64) if want_dW else None
     lib().oracle_dnn_backward(_p(pool), _p(W), _p(dY), B, F, D, H, _p(g_pool), _p(dW))
     return g_pool, dW

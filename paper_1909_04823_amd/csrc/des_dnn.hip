@@ -23,6 +23,8 @@ namespace {
 
 constexpr int BM = 128, BN = 128, BK = 16;
 constexpr int LDA = BM + 4, LDB = BN + 4;    // LDS row pitches (floats)
+constexpr int kFlushTiles = 8;               // 128 products per first-level run
+constexpr long long kTwoLevelDepth = 1024;
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -88,7 +90,7 @@ __device__ inline void store_tile(float *__restrict__ T, const float4 (&r)[2]) {
   }
 }
 
-template <bool kAKContig, bool kBKContig>
+template <bool kAKContig, bool kBKContig, bool kTwoLevel>
 __global__ __launch_bounds__(kBlock) void k_gemm(const GemmArgs g) {
   __shared__ __align__(16) float As[BK * LDA];
   __shared__ __align__(16) float Bs[BK * LDB];
@@ -96,13 +98,18 @@ __global__ __launch_bounds__(kBlock) void k_gemm(const GemmArgs g) {
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int z = blockIdx.z;
-  f32x16 acc[2][2];
+  // kTwoLevel (long contractions; the weight gradient sums over the whole batch): two-level fp32
+  // summation.  The matrix cores accumulate runs of kFlushTiles*BK products from zero and each run is
+  // then added into `total`, so small products are never added to a large running sum.  Short
+  // contractions keep the single accumulator and the registers that saves.
+  f32x16 acc[2][2], total[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; total[i][j][r] = 0.f; }
+  int run = 0;
 
   const int lrow = lane & 31, lk = lane >> 5;     // MFMA operand: row/column within the 32-block, k within the pair
   for (long long base = g.k_begin + (long long)z * g.k_shift; base < g.k_limit; base += g.blk_stride) {
@@ -131,8 +138,23 @@ __global__ __launch_bounds__(kBlock) void k_gemm(const GemmArgs g) {
 #pragma unroll
           for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
       }
+      if (kTwoLevel && ++run == kFlushTiles) {
+        run = 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            total[i][j] += acc[i][j];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+          }
+      }
     }
   }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) total[i][j] += acc[i][j];
   // accumulator element r of a 32x32 block sits at row (r/4)*8 + (lane/32)*4 + r%4, column lane%32
   float *C = g.C + (long long)z * g.c_slice;
 #pragma unroll
@@ -143,16 +165,20 @@ __global__ __launch_bounds__(kBlock) void k_gemm(const GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + lk * 4 + (r & 3);
-        if (row < g.M && col < g.N) C[(long long)row * g.c_rs + col] = acc[i][j][r];
+        if (row < g.M && col < g.N) C[(long long)row * g.c_rs + col] = total[i][j][r];
       }
     }
 }
 
+// `depth`: products summed per output element of one slice; above kTwoLevelDepth the two-level kernel runs.
 template <bool kAKContig, bool kBKContig>
-des_status_t launch(const GemmArgs &g, int slices, int kid, hipStream_t s) {
+des_status_t launch(const GemmArgs &g, int slices, long long depth, int kid, hipStream_t s) {
   const dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM), (unsigned)slices);
   ProfScope ps(kid, s);
-  hipLaunchKernelGGL((k_gemm<kAKContig, kBKContig>), grid, dim3(kBlock), 0, s, g);
+  if (depth > kTwoLevelDepth)
+    hipLaunchKernelGGL((k_gemm<kAKContig, kBKContig, true>), grid, dim3(kBlock), 0, s, g);
+  else
+    hipLaunchKernelGGL((k_gemm<kAKContig, kBKContig, false>), grid, dim3(kBlock), 0, s, g);
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
 }
 
@@ -178,7 +204,7 @@ des_status_t des_dnn_partial_forward(const float *pool, const float *W, int64_t 
   g.C = Y_partial; g.M = (int)B; g.N = H; g.c_rs = H; g.c_slice = (long long)B * H;
   // shard s: fields s, s+K, ... = k blocks of length D starting at s*D, K*D apart
   g.k_begin = 0; g.k_shift = D; g.blk_len = D; g.blk_stride = (long long)K * D; g.k_limit = (long long)F * D;
-  return launch<true, false>(g, K, KID_DNN_FORWARD, (hipStream_t)stream);
+  return launch<true, false>(g, K, (long long)((F + K - 1) / K) * D, KID_DNN_FORWARD, (hipStream_t)stream);
 }
 
 des_status_t des_dnn_backward_bytes(int64_t B, int32_t F, int32_t D, int32_t H, size_t *workspace_bytes) {
@@ -205,7 +231,7 @@ des_status_t des_dnn_backward(const float *pool, const float *W, const float *dY
     g.B = W; g.b_rs = 1; g.b_cs = H;
     g.C = g_pool; g.M = (int)B; g.N = (int)FD; g.c_rs = FD; g.c_slice = 0;
     g.k_begin = 0; g.k_shift = 0; g.blk_len = H; g.blk_stride = (1ll << 40); g.k_limit = H;
-    des_status_t st = launch<true, true>(g, 1, KID_DNN_GPOOL, s);
+    des_status_t st = launch<true, true>(g, 1, H, KID_DNN_GPOOL, s);
     if (st != DES_OK) return st;
   }
   if (dW) {                                       // dW[F*D, H] = pool^T x dY, split over slices of samples
@@ -220,7 +246,7 @@ des_status_t des_dnn_backward(const float *pool, const float *W, const float *dY
     g.B = dY; g.b_rs = H; g.b_cs = 1;
     g.C = Z > 1 ? (float *)workspace : dW; g.M = (int)FD; g.N = H; g.c_rs = H; g.c_slice = FD * H;
     g.k_begin = 0; g.k_shift = chunk; g.blk_len = chunk; g.blk_stride = (1ll << 40); g.k_limit = B;
-    des_status_t st = launch<false, false>(g, Z, KID_DNN_DW, s);
+    des_status_t st = launch<false, false>(g, Z, chunk, KID_DNN_DW, s);
     if (st != DES_OK) return st;
     if (Z > 1) return des_aggregate_partials((const float *)workspace, Z, FD * H, dW, stream);
   }

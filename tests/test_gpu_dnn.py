@@ -27,6 +27,10 @@ SHAPES = [
     (130, 5, 64, 132, 2),     # D of several k tiles
     (5000, 3, 4, 132, 1),     # many samples: sliced weight gradient
     (2049, 10, 32, 64, 16),
+    # contractions deeper than 1024 products take the two-level summation kernel
+    (40000, 2, 4, 8, 1),      # weight gradient, 2512 samples per slice
+    (64, 40, 32, 16, 1),      # forward, 1280 products per shard
+    (8, 2, 4, 1100, 2),       # g_pool, 1100 hidden units
 ]
 
 

@@ -212,3 +212,44 @@ def test_full_size_streaming_first_step(oracle, des):
 
 def test_full_size_large_table(oracle, des):
     run_full_size(oracle, des, 4, n_fwd_samples=48, n_bwd_keys=3000)
+
+
+@pytest.mark.parametrize("index", [2, 4])
+def test_dnn_layer_full_size_sampled(oracle, des, index):
+    """First fully-connected layer (Section 4.3) at the benchmark shapes, H = 256, in the launch
+    configuration bench.py times.  The oracle computes whole output rows for sampled samples
+    (every shard's partial and g_pool) and, for the weight gradient, whole rows of sampled fields
+    over a subset of the hidden units, each summed over the full batch."""
+    import torch
+    w = synth.workload(index)
+    B, F, D, K, H = w.B, w.F, w.D, w.K, 256
+    progress(f"dnn full size: workload {index} B={B} F={F} D={D} K={K} H={H}")
+    gen = torch.Generator(device="cuda"); gen.manual_seed(100 + index)
+    pool = torch.randn((B, F, D), device="cuda", generator=gen) * 0.05
+    W = torch.randn((F * D, H), device="cuda", generator=gen) / float(np.sqrt(F * D))
+    dY = torch.randn((B, H), device="cuda", generator=gen) * 0.01
+    Yp = des.dnn_partial_forward(pool, W, K)
+    Y = des.aggregate_partials(Yp)
+    g_pool = torch.empty((B, F, D), device="cuda"); dW = torch.empty((F * D, H), device="cuda")
+    ws = torch.empty(des.dnn_backward_bytes(B, F, D, H), dtype=torch.uint8, device="cuda")
+    des.dnn_backward(pool, W, dY, g_pool, dW, ws)
+    torch.cuda.synchronize()
+    progress("dnn full size: kernels done")
+    rng = np.random.default_rng(index)
+    bsel = np.unique(np.concatenate([[0, 127, 128, B - 1], rng.integers(0, B, 12)]))
+    bt = torch.from_numpy(bsel).cuda()
+    pool_s, dY_s, W_h = pool[bt].cpu().numpy(), dY[bt].cpu().numpy(), W.cpu().numpy()
+    Y_ref = oracle.dnn_partial_forward(pool_s, W_h, K)
+    assert_close(Yp[:, bt].cpu().numpy(), Y_ref, "Y_partial rows")
+    assert_close(Y[bt].cpu().numpy(), oracle.aggregate(Y_ref), "Y rows")
+    g_ref, _ = oracle.dnn_backward(pool_s, W_h, dY_s, want_dW=False)
+    assert_close(g_pool[bt].cpu().numpy(), g_ref, "g_pool rows")
+    progress("dnn full size: forward and g_pool rows checked")
+    fsel = np.array([0, F - 1])
+    hsel = np.unique(np.concatenate([[0, 127, 128, H - 1], rng.integers(0, H, 28)]))
+    ht = torch.from_numpy(hsel).cuda()
+    pool_f = pool[:, torch.from_numpy(fsel).cuda(), :].cpu().numpy()
+    jsel = np.concatenate([np.arange(f * D, (f + 1) * D) for f in fsel])
+    _, dW_ref = oracle.dnn_backward(pool_f, W_h[jsel][:, hsel], dY[:, ht].cpu().numpy(), want_g_pool=False)
+    assert_close(dW[torch.from_numpy(jsel).cuda()][:, ht].cpu().numpy(), dW_ref, "dW rows of sampled fields")
+    progress("dnn full size: dW rows checked")
