@@ -348,6 +348,9 @@ def run_workload(args, index, cpu):
                 "algorithmic_bytes_per_launch": int(per_launch_bytes), "avg_launch_ms": round(per_launch_s * 1e3, 4),
                 "distinct_rows_per_step": st["U"], "kernel_ms_sum_per_step": round(sum(v["ms_per_step"] for v in kernels.values()), 4)}
 
+        if roof["traffic"]:          # measured bytes (committed counter summary) over the live launch time
+            roof["traffic_GBps"] = round(roof["traffic"] / per_launch_s / 1e9, 1)
+
     cpu_res = None
     if cpu:
         n_cpu = max(1, min(B, int(np.ceil(args.cpu_lookups / max(1.0, host_batches[0].nnz / B)))))
