@@ -70,6 +70,13 @@ def lib():
         L.oracle_dnn_partial_forward.argtypes = [vp, vp, i64, i32, C.c_int, C.c_int, C.c_int, vp]
         L.oracle_dnn_backward.restype = None
         L.oracle_dnn_backward.argtypes = [vp, vp, vp, i64, i32, C.c_int, C.c_int, vp, vp]
+        L.oracle_bias_act.restype = None; L.oracle_bias_act.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp]
+        L.oracle_bias_act_backward.restype = None
+        L.oracle_bias_act_backward.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, vp]
+        L.oracle_head.restype = None
+        L.oracle_head.argtypes = [vp, vp, vp, vp, f32, vp, i64, C.c_int, vp, vp, vp, vp, vp, vp, vp]
+        L.oracle_dense_update.restype = None
+        L.oracle_dense_update.argtypes = [vp, vp, vp, vp, i64, C.POINTER(Optimizer)]
         _lib = L
     return _lib
 
@@ -252,3 +259,47 @@ def dnn_backward(pool: np.ndarray, W: np.ndarray, dY: np.ndarray, want_g_pool: b
     dW = np.empty((F * D, H), np.float64) if want_dW else None
     lib().oracle_dnn_backward(_p(pool), _p(W), _p(dY), B, F, D, H, _p(g_pool), _p(dW))
     return g_pool, dW
+
+
+def bias_act(Z: np.ndarray, bias: Optional[np.ndarray], relu: bool) -> np.ndarray:
+    """A = relu(Z + bias) (or Z + bias) in float64; Z is [B,H] float64 (an aggregate)."""
+    Z = _c(Z, np.float64); bias = _c(bias, np.float32)
+    B, H = Z.shape
+    A = np.empty((B, H), np.float64)
+    lib().oracle_bias_act(_p(Z), _p(bias), B, H, int(relu), _p(A))
+    return A
+
+
+def bias_act_backward(A: np.ndarray, dA: np.ndarray, relu: bool):
+    """(dZ[B,H], dbias[H]) in float64 from the fp32 forward output A and upstream gradient dA."""
+    A, dA = _c(A, np.float32), _c(dA, np.float32)
+    B, H = A.shape
+    dZ = np.empty((B, H), np.float64); dbias = np.empty(H, np.float64)
+    lib().oracle_bias_act_backward(_p(A), _p(dA), B, H, int(relu), _p(dZ), _p(dbias))
+    return dZ, dbias
+
+
+def head(labels: np.ndarray, A_lr=None, fm2=None, a=None, w_out=None, b0: float = 0.0):
+    """Output unit + mean log-loss + gradients; dict(logit, p, loss, g_logit, da, dw_out, db0), float64."""
+    labels = _c(labels, np.float32)
+    A_lr, fm2, a, w_out = (_c(x, np.float32) for x in (A_lr, fm2, a, w_out))
+    B = labels.shape[0]
+    H = 0 if a is None else a.shape[1]
+    if (a is None) != (w_out is None):
+        raise ValueError("a and w_out go together")
+    out = {"logit": np.empty(B), "p": np.empty(B), "g_logit": np.empty(B),
+           "da": None if a is None else np.empty((B, H)), "dw_out": None if a is None else np.empty(H)}
+    loss, db0 = C.c_double(0.0), C.c_double(0.0)
+    lib().oracle_head(_p(A_lr), _p(fm2), _p(a), _p(w_out), C.c_float(b0), _p(labels), B, H, _p(out["logit"]),
+                      _p(out["p"]), C.byref(loss), _p(out["g_logit"]), _p(out["da"]), _p(out["dw_out"]), C.byref(db0))
+    out["loss"], out["db0"] = loss.value, db0.value
+    return out
+
+
+def dense_update(theta: np.ndarray, grad: np.ndarray, optimizer: Optimizer, s1=None, s2=None):
+    """In-place optimizer step (optimizer.opt_emb) on fp32 arrays theta (and state s1, s2)."""
+    for x in (theta, s1, s2):
+        if x is not None and not (x.dtype == np.float32 and x.flags.c_contiguous):
+            raise ValueError("theta and state must be contiguous float32 (updated in place)")
+    grad = _c(grad, np.float32)
+    lib().oracle_dense_update(_p(theta), _p(grad), _p(s1), _p(s2), theta.size, C.byref(optimizer))

@@ -427,3 +427,75 @@ void oracle_dnn_backward(const float *pool, const float *W, const float *dY, int
         dW[j * H + h] = a;
       }
 }
+
+/* ------------------------------------------------------------------ dense tower and output unit ----
+ * What follows the aggregated weights-rich operators (Section 3.2.1: the layers after them see the
+ * same aggregated result on every process; Section 4, Table "common components": LR = first order,
+ * FM = first + second order, W&D = first + high order, DeepFM = all three; Section 4.1 for the
+ * sigmoid output).  The paper names these parts without formulas; they are the textbook ones:
+ *   hidden layer     A = relu(Z + bias)           Z = aggregated product of the layer
+ *   output unit      logit = b0 + A_lr + fm2 + <a, w_out>,  p = sigmoid(logit)
+ *   loss             mean over the batch of  -y log p - (1-y) log(1-p)
+ * "parity unpinned" for the choice of ReLU and of the mean log-loss: the paper reports log loss and
+ * AUC (Section 6) but prints neither the activation nor the reduction. */
+
+/* A[b,h] = Z[b,h] + bias[h], clamped at zero from below when relu != 0.  bias may be NULL. */
+void oracle_bias_act(const double *Z, const float *bias, int64_t B, int H, int relu, double *A) {
+  for (int64_t b = 0; b < B; ++b)
+    for (int h = 0; h < H; ++h) {
+      double z = Z[b * H + h] + (bias ? (double)bias[h] : 0.0);
+      A[b * H + h] = (relu && z < 0.0) ? 0.0 : z;
+    }
+}
+
+/* Backward of the same: dZ[b,h] = dA[b,h] where the unit was active (A > 0; everywhere without
+ * relu), else 0;  dbias[h] = sum_b dZ[b,h].  A is the forward output. */
+void oracle_bias_act_backward(const float *A, const float *dA, int64_t B, int H, int relu, double *dZ,
+                              double *dbias) {
+  for (int h = 0; h < H; ++h) dbias[h] = 0.0;
+  for (int64_t b = 0; b < B; ++b)
+    for (int h = 0; h < H; ++h) {
+      double g = (!relu || A[b * H + h] > 0.0f) ? (double)dA[b * H + h] : 0.0;
+      dZ[b * H + h] = g;
+      dbias[h] += g;
+    }
+}
+
+/* Output unit, loss and their gradients.  Any of A_lr, fm2, a (with w_out) may be NULL: the model
+ * then has no such component.  Outputs (all but g_logit nullable):
+ *   logit[B], p[B], *loss (mean log-loss), g_logit[b] = (p - y)/B = d loss / d logit[b] (which is
+ *   also the upstream gradient of A_lr[b] and of fm2[b]),  da[b,h] = g_logit[b] w_out[h],
+ *   dw_out[h] = sum_b g_logit[b] a[b,h],  *db0 = sum_b g_logit[b]. */
+void oracle_head(const float *A_lr, const float *fm2, const float *a, const float *w_out, float b0,
+                 const float *labels, int64_t B, int H, double *logit, double *p, double *loss,
+                 double *g_logit, double *da, double *dw_out, double *db0) {
+  double total = 0.0, gsum = 0.0;
+  if (dw_out) for (int h = 0; h < H; ++h) dw_out[h] = 0.0;
+  for (int64_t b = 0; b < B; ++b) {
+    double z = (double)b0;
+    if (A_lr) z += (double)A_lr[b];
+    if (fm2) z += (double)fm2[b];
+    if (a) for (int h = 0; h < H; ++h) z += (double)a[b * H + h] * (double)w_out[h];
+    const double y = (double)labels[b];
+    const double pb = 1.0 / (1.0 + exp(-z));
+    /* -y log p - (1-y) log(1-p) = log(1 + e^z) - y z, written so that neither e^z nor the log overflows */
+    total += (z > 0.0 ? z : 0.0) + log1p(exp(-fabs(z))) - y * z;
+    const double g = (pb - y) / (double)B;
+    if (logit) logit[b] = z;
+    if (p) p[b] = pb;
+    g_logit[b] = g;
+    gsum += g;
+    if (a && da) for (int h = 0; h < H; ++h) da[b * H + h] = g * (double)w_out[h];
+    if (a && dw_out) for (int h = 0; h < H; ++h) dw_out[h] += g * (double)a[b * H + h];
+  }
+  if (loss) *loss = B > 0 ? total / (double)B : 0.0;
+  if (db0) *db0 = gsum;
+}
+
+/* One optimizer step over a dense parameter array (every coordinate is touched every step):
+ * optimizer o->opt_emb with the arithmetic of optimizer_step. */
+void oracle_dense_update(float *theta, const float *grad, float *s1, float *s2, int64_t n,
+                         const oracle_optimizer *o) {
+  for (int64_t i = 0; i < n; ++i)
+    optimizer_step(o->opt_emb, o, (double)grad[i], theta + i, s1 ? s1 + i : NULL, s2 ? s2 + i : NULL);
+}

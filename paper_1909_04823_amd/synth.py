@@ -301,3 +301,34 @@ def dnn_layer_inputs(seed: int, B: int, F: int, D: int, H: int):
     W = (rng.standard_normal((F * D, H), dtype=np.float32) / np.float32(np.sqrt(F * D))).astype(np.float32)
     dY = (0.01 * rng.standard_normal((B, H), dtype=np.float32)).astype(np.float32)
     return pool, W, dY
+
+
+def tower_init(seed: int, F: int, D: int, hidden=(256, 128)):
+    """Initial dense parameters of the tower after the pooled embeddings: W1[F*D,H1], b1[H1],
+    W2[H1,H2], b2[H2], w_out[H2], b0[1].  Weights N(0, 2/fan_in) (the usual scaling before a ReLU),
+    hidden biases 0.01, output bias 0."""
+    rng = np.random.default_rng((int(seed), 0x70E))
+    H1, H2 = hidden
+    n = lambda rows, cols: (rng.standard_normal((rows, cols), dtype=np.float32) * np.float32(np.sqrt(2.0 / rows)))
+    return {"W1": n(F * D, H1), "b1": np.full(H1, 0.01, np.float32),
+            "W2": n(H1, H2), "b2": np.full(H2, 0.01, np.float32),
+            "w_out": (rng.standard_normal(H2, dtype=np.float32) * np.float32(np.sqrt(1.0 / H2))),
+            "b0": np.zeros(1, np.float32)}
+
+
+def planted_labels(batch: Batch, seed: int, base_rate_logit: float = -1.4, strength: float = 1.5) -> np.ndarray:
+    """Click labels a model can learn from the IDs: every ID carries a hidden weight in [-1,1)
+    (a scramble of the ID, centred on the batch's entry mean so that hot IDs do not shift every
+    sample alike), a sample's score is the sum of its entries' hidden weights over sqrt(n), n its
+    number of entries, and y ~ Bernoulli(sigmoid(base_rate_logit + strength * score))."""
+    hidden = (scramble64(batch.keys ^ np.uint64(0x5EEDF00D ^ int(seed))) >> np.uint64(11)).astype(np.float64)
+    hidden = hidden / float(1 << 52) - 1.0
+    hidden -= hidden.mean() if hidden.size else 0.0
+    ends = batch.offsets[batch.F::batch.F].astype(np.int64)
+    starts = batch.offsets[0:-1:batch.F].astype(np.int64)
+    csum = np.concatenate([[0.0], np.cumsum(hidden)])
+    n = np.maximum(ends - starts, 1)
+    score = (csum[ends] - csum[starts]) / np.sqrt(n)
+    p = 1.0 / (1.0 + np.exp(-(base_rate_logit + strength * score)))
+    rng = np.random.default_rng((int(seed), 0x1AB, int(batch.keys.shape[0])))
+    return (rng.random(batch.B) < p).astype(np.float32)

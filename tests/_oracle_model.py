@@ -1,0 +1,79 @@
+"""The CPU oracle's functions chained into one training step of LR / FM / W&D / DeepFM (test
+infrastructure only).  Between stages every tensor is rounded to fp32 once, because that is the
+precision in which the library's boundary hands tensors from one call to the next."""
+from __future__ import annotations
+
+import numpy as np
+
+f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+
+COMPONENTS = {"lr": ("lr",), "fm": ("lr", "fm"), "wd": ("lr", "dnn"), "deepfm": ("lr", "fm", "dnn")}
+
+
+class OracleModel:
+    def __init__(self, oracle, table, F, K, kind, tower, opt_sparse, opt_dense, policy=0):
+        """`tower`: dict from synth.tower_init (copied); opt_*: dicts of optimizer fields."""
+        self.o, self.t, self.F, self.K, self.policy = oracle, table, F, K, policy
+        self.parts = COMPONENTS[kind]
+        self.p = {k: v.copy() for k, v in tower.items()}
+        self.s1 = {k: np.zeros_like(v) for k, v in tower.items()}
+        self.s2 = {k: np.zeros_like(v) for k, v in tower.items()}
+        self.opt_sparse, self.opt_dense = dict(opt_sparse), dict(opt_dense)
+        self.step_no = 0
+
+    def forward(self, batch, rows, labels):
+        o, t, p, F, K = self.o, self.t, self.p, self.F, self.K
+        B, D = batch.B, t.D
+        c = {}
+        P = t.partial_forward(B, F, batch.keys, batch.offsets, rows, K, self.policy, batch.vals, pool=False)
+        c["A_lr"] = f32(o.aggregate(P["P_lr"])) if "lr" in self.parts else None
+        c["A_sum"] = f32(o.aggregate(P["P_sum"]))
+        c["fm2"] = f32(o.fm_finalize(o.aggregate(P["P_sum"]), o.aggregate(P["P_sq"]))) if "fm" in self.parts else None
+        if "dnn" in self.parts:
+            pool = t.partial_forward(B, F, batch.keys, batch.offsets, rows, 1, self.policy, batch.vals,
+                                     lr=False, fm=False, pool=True)["P_pool"][0]
+            c["pool"] = f32(pool)
+            c["a1"] = f32(o.bias_act(o.aggregate(o.dnn_partial_forward(c["pool"], p["W1"], K)), p["b1"], True))
+            c["a2"] = f32(o.bias_act(o.dnn_partial_forward(c["a1"][:, None, :], p["W2"], 1)[0], p["b2"], True))
+        c["head"] = o.head(labels, c["A_lr"], c["fm2"], c.get("a2"), p["w_out"] if "dnn" in self.parts else None,
+                           float(p["b0"][0]))
+        return c
+
+    def loss(self, batch, rows, labels):
+        return self.forward(batch, rows, labels)["head"]["loss"]
+
+    def gradients(self, batch, rows, labels):
+        """Forward cache plus dense gradients (float64) and the upstream gradients of the sparse path."""
+        o, p = self.o, self.p
+        c = self.forward(batch, rows, labels)
+        h = c["head"]
+        g = {"b0": np.array([h["db0"]])}
+        c["g_logit"] = f32(h["g_logit"])
+        c["g_pool"] = None
+        if "dnn" in self.parts:
+            g["w_out"] = h["dw_out"]
+            dZ2, g["b2"] = o.bias_act_backward(c["a2"], f32(h["da"]), True)
+            da1, g["W2"] = o.dnn_backward(c["a1"][:, None, :], p["W2"], f32(dZ2))
+            dZ1, g["b1"] = o.bias_act_backward(c["a1"], f32(da1[:, 0, :]), True)
+            g_pool, g["W1"] = o.dnn_backward(c["pool"], p["W1"], f32(dZ1))
+            c["g_pool"] = f32(g_pool)
+        c["dense_grads"] = g
+        return c
+
+    def train_step(self, batch, labels, insert=True):
+        o, t = self.o, self.t
+        self.step_no += 1
+        rows = t.find(batch.keys, insert_missing=insert)
+        c = self.gradients(batch, rows, labels)
+        gl = c["g_logit"]
+        sp = o.Optimizer(**dict(self.opt_sparse, step=self.step_no))
+        c["merge"] = t.backward_update(batch.B, self.F, batch.offsets, rows,
+                                       gl if "lr" in self.parts else None,
+                                       gl if "fm" in self.parts else None,
+                                       c["A_sum"] if "fm" in self.parts else None,
+                                       c["g_pool"], vals=batch.vals, optimizer=sp)
+        dn = o.Optimizer(**dict(self.opt_dense, step=self.step_no))
+        for k, grad in c["dense_grads"].items():
+            o.dense_update(self.p[k], f32(grad), dn, self.s1[k], self.s2[k])
+        c["rows"] = rows
+        return c

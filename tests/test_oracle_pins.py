@@ -541,3 +541,126 @@ def test_streaming_generator_mirrors_row_assignment(oracle):
         np.testing.assert_array_equal(t.row_keys, gen.row_keys)      # generator's mirror == table
         fresh_fraction.append((t.n_rows - n0) / np.unique(batch.keys).size)
     assert 0.05 < np.mean(fresh_fraction) < 0.6
+
+
+# --------------------------------------------------------------------------- tower, output unit ----
+def test_head_closed_forms_and_stability(oracle):
+    y = np.array([1, 0, 1, 0], np.float32)
+    h = oracle.head(y)                                           # no component: logit = b0 = 0
+    assert h["loss"] == pytest.approx(np.log(2.0), rel=1e-15)
+    assert h["p"].tolist() == [0.5] * 4 and h["g_logit"].tolist() == [-0.125, 0.125, -0.125, 0.125]
+    assert h["db0"] == 0.0
+    # moderate logits against the literal formula; huge ones stay finite and equal |z| or 0
+    z = np.array([-3.0, 0.25, 2.0, 7.5], np.float32)
+    h = oracle.head(y, A_lr=z)
+    p = 1 / (1 + np.exp(-z.astype(np.float64)))
+    assert h["loss"] == pytest.approx(float(np.mean(-(y * np.log(p) + (1 - y) * np.log(1 - p)))), rel=1e-13)
+    np.testing.assert_allclose(h["p"], p, rtol=1e-15)
+    np.testing.assert_allclose(h["g_logit"], (p - y) / 4, rtol=1e-13)
+    h = oracle.head(np.array([1, 0, 0, 1], np.float32), fm2=np.array([800, -800, 800, -800], np.float32))
+    assert h["loss"] == pytest.approx(400.0, rel=1e-15)          # two right (0), two wrong (800 each)
+    # the three components and the bias simply add up in the logit
+    a = np.array([[1, 2], [3, 4], [5, 6], [7, 8]], np.float32); wv = np.array([0.5, -0.25], np.float32)
+    h = oracle.head(y, A_lr=z, fm2=2 * z, a=a, w_out=wv, b0=0.125)
+    np.testing.assert_allclose(h["logit"], 0.125 + 3 * z.astype(np.float64) + a.astype(np.float64) @ wv, rtol=1e-15)
+
+
+def test_head_gradients_match_finite_differences(oracle):
+    rng = np.random.default_rng(21)
+    B, H = 5, 3
+    y = (rng.random(B) < 0.5).astype(np.float32)
+    A_lr, fm2 = rng.standard_normal(B).astype(np.float32), rng.standard_normal(B).astype(np.float32)
+    a, wv = rng.standard_normal((B, H)).astype(np.float32), rng.standard_normal(H).astype(np.float32)
+    base = oracle.head(y, A_lr, fm2, a, wv, 0.3)
+    eps = 2.0 ** -10                                             # exact in fp32 for these magnitudes
+
+    def fd(arr, idx, **kw):
+        hi, lo = arr.copy(), arr.copy(); hi[idx] += eps; lo[idx] -= eps
+        args = dict(A_lr=A_lr, fm2=fm2, a=a, w_out=wv, b0=0.3)
+        up = oracle.head(y, **{**args, **{kw["name"]: hi}})["loss"]
+        dn = oracle.head(y, **{**args, **{kw["name"]: lo}})["loss"]
+        return (up - dn) / (hi[idx].astype(np.float64) - lo[idx].astype(np.float64))
+
+    for b in range(B):
+        assert fd(A_lr, b, name="A_lr") == pytest.approx(base["g_logit"][b], rel=1e-5)
+        assert fd(fm2, b, name="fm2") == pytest.approx(base["g_logit"][b], rel=1e-5)
+        for h in range(H):
+            assert fd(a, (b, h), name="a") == pytest.approx(base["da"][b, h], rel=1e-5, abs=1e-9)
+    for h in range(H):
+        assert fd(wv, h, name="w_out") == pytest.approx(base["dw_out"][h], rel=1e-5, abs=1e-9)
+    up = oracle.head(y, A_lr, fm2, a, wv, 0.3 + eps)["loss"]; dn = oracle.head(y, A_lr, fm2, a, wv, 0.3 - eps)["loss"]
+    assert (up - dn) / (float(np.float32(0.3 + eps)) - float(np.float32(0.3 - eps))) == pytest.approx(base["db0"], rel=1e-5)
+
+
+def test_bias_relu_and_its_backward(oracle):
+    Z = np.array([[1.0, -2.0, 0.5], [-1.0, 3.0, -0.5]])
+    bias = np.array([0.5, 1.0, -0.5], np.float32)
+    assert oracle.bias_act(Z, bias, True).tolist() == [[1.5, 0.0, 0.0], [0.0, 4.0, 0.0]]
+    assert oracle.bias_act(Z, bias, False).tolist() == [[1.5, -1.0, 0.0], [-0.5, 4.0, -1.0]]
+    assert oracle.bias_act(Z, None, False).tolist() == Z.tolist()
+    A = oracle.bias_act(Z, bias, True).astype(np.float32)
+    dA = np.array([[10, 20, 30], [40, 50, 60]], np.float32)
+    dZ, db = oracle.bias_act_backward(A, dA, True)
+    assert dZ.tolist() == [[10, 0, 0], [0, 50, 0]] and db.tolist() == [10, 50, 0]
+    dZ, db = oracle.bias_act_backward(A, dA, False)
+    assert dZ.tolist() == dA.tolist() and db.tolist() == [50, 70, 90]
+
+
+def test_dense_update_closed_forms(oracle):
+    th = np.array([1.0, -2.0, 0.5], np.float32); g = np.array([0.5, 0.25, -1.0], np.float32)
+    t1 = th.copy(); oracle.dense_update(t1, g, oracle.Optimizer(opt_emb=oracle.OPT_SGD, lr=0.5))
+    assert t1.tolist() == [0.75, -2.125, 1.0]
+    t2, s = th.copy(), np.zeros(3, np.float32)
+    oracle.dense_update(t2, g, oracle.Optimizer(opt_emb=oracle.OPT_ADAGRAD, lr=0.5, eps=0.0), s)
+    assert s.tolist() == (g * g).tolist() and t2.tolist() == [0.5, -2.5, 1.0]      # first step: lr*sign(g)
+    t3, m, v = th.copy(), np.zeros(3, np.float32), np.zeros(3, np.float32)
+    oracle.dense_update(t3, g, oracle.Optimizer(opt_emb=oracle.OPT_ADAM, lr=0.125, eps=0.0, beta1=0.5, beta2=0.75,
+                                                step=1), m, v)
+    np.testing.assert_allclose(t3, th - 0.125 * np.sign(g), rtol=1e-6)                # first Adam step: lr*sign(g)
+    assert m.tolist() == (0.5 * g).tolist() and v.tolist() == (0.25 * g * g).tolist()
+
+
+@pytest.mark.parametrize("kind", ["lr", "fm", "wd", "deepfm"])
+def test_whole_model_gradients_match_finite_differences(oracle, kind):
+    """The chained step (sparse operators -> first layer under DES -> tower -> output unit -> loss and
+    all the way back) against central differences of its own loss: every dense parameter class and the
+    merged sparse gradient, i.e. the glue between the stages (g_lr = g_fm = dL/dlogit, g_pool = dZ1 W1^T, ...)."""
+    from _oracle_model import OracleModel
+    rng = np.random.default_rng(31)
+    B, F, D, K = 6, 3, 4, 2
+    vocab, keys, offsets, vals = random_batch(rng, B, F, 3, 12, with_vals=True, min_len=1)
+    t = make_table(oracle, rng, vocab, D, scale=0.5)
+    batch = synth.Batch(B, F, keys, offsets, vals)
+    tower = synth.tower_init(5, F, D, hidden=(8, 4))
+    for k in ("b1", "b2"):
+        tower[k] = (0.3 * rng.standard_normal(tower[k].shape)).astype(np.float32)     # units on both sides of 0
+    labels = (rng.random(B) < 0.5).astype(np.float32)
+    m = OracleModel(oracle, t, F, K, kind, tower, dict(opt_emb=0, opt_w=0), dict(opt_emb=0))
+    rows = t.find(keys)
+    c = m.gradients(batch, rows, labels)
+    # stages hand fp32 tensors to each other, so the loss carries ~1e-8 of rounding noise: the step is
+    # large enough to lift the difference quotient two to three digits above it
+    eps = 2.0 ** -7
+    checked = 0
+    for name, grad in c["dense_grads"].items():
+        flat = m.p[name].reshape(-1)
+        for i in rng.choice(flat.size, size=min(flat.size, 6), replace=False):
+            old = flat[i]
+            flat[i] = old + eps; up = m.loss(batch, rows, labels); hi = float(flat[i])
+            flat[i] = old - eps; dn = m.loss(batch, rows, labels); lo = float(flat[i])
+            flat[i] = old
+            assert (up - dn) / (hi - lo) == pytest.approx(np.asarray(grad).reshape(-1)[i], rel=1e-2, abs=2e-6), (name, i)
+            checked += 1
+    gl = c["g_logit"]
+    out = t.backward_update(B, F, offsets, rows, gl if "lr" in m.parts else None, gl if "fm" in m.parts else None,
+                            c["A_sum"] if "fm" in m.parts else None, c["g_pool"], oracle.OPT_NONE, vals=vals)
+    emb, wv = t.emb, t.w
+    for j, r in enumerate(out["uniq_rows"]):
+        for col in range(D + 1):
+            ref = emb[r, col:col + 1] if col < D else wv[r:r + 1]
+            old = ref[0]
+            ref[0] = old + eps; up = m.loss(batch, rows, labels); hi = float(ref[0])
+            ref[0] = old - eps; dn = m.loss(batch, rows, labels); lo = float(ref[0])
+            ref[0] = old
+            assert (up - dn) / (hi - lo) == pytest.approx(out["merged"][j, col], rel=1e-2, abs=2e-6), (r, col)
+    assert checked >= 1
