@@ -231,6 +231,48 @@ des_status_t des_backward_update(des_table_t *t, const des_batch_t *batch, const
 des_status_t des_backward_merge(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
                                 const des_backward_io_t *io, void *stream);
 
+/* ---- The dense remainder of a model step --------------------------------------------------------
+ * After the aggregated weights-rich operators every process computes the same thing (Section 3.2.1);
+ * Section 4's models differ in which components feed the output (LR: first order; FM: + second
+ * order; W&D: first + high order; DeepFM: all three) and Section 4.1 gives the sigmoid output.  The
+ * paper prints no formula for the tower's activation or the loss reduction; ReLU and the mean
+ * log-loss (the quantity Section 6 reports) are used.  All pointers device, fp32, row-major. */
+
+/* Hidden-layer epilogue fused into the aggregation of Eq. (1):
+ *     out[r,h] = act( sum_s P[s,r,h] + bias[h] ),  act = max(.,0) when relu != 0, identity otherwise.
+ * P [K,rows,H], bias [H] or null, out [rows,H]; H a multiple of 4, all 16-byte aligned.  Shard sum in
+ * double, rounded once. */
+des_status_t des_aggregate_bias_act(const float *P, int32_t K, int64_t rows, int32_t H, const float *bias,
+                                    int32_t relu, float *out, void *stream);
+
+/* Bytes of the workspace the three calls below take, for layers up to H_max wide. */
+des_status_t des_dense_workspace_bytes(int32_t H_max, size_t *workspace_bytes);
+
+/* Backward of that epilogue: dZ[r,h] = dA[r,h] where A[r,h] > 0 (everywhere when relu == 0), else 0;
+ * dbias[h] = sum_r dZ[r,h] (double, fixed order).  A is the forward output.  dZ may alias dA. */
+des_status_t des_bias_act_backward(const float *A, const float *dA, int64_t rows, int32_t H, int32_t relu,
+                                   float *dZ, float *dbias, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Output unit, loss and gradients for one batch:
+ *     logit[b] = b0 + A_lr[b] + fm2[b] + <a[b,:], w_out>        (absent components: null pointers)
+ *     p = 1/(1+exp(-logit));   loss = mean_b( -y log p - (1-y) log(1-p) ), evaluated as
+ *     log(1+e^z) - y z in an overflow-free form;   g_logit[b] = (p[b]-y[b])/B,
+ * which is d loss/d logit and therefore also the upstream gradient g_lr and g_fm of
+ * des_backward_update*;  da[b,h] = g_logit[b] w_out[h];  dw_out[h] = sum_b g_logit[b] a[b,h];
+ * db0 = sum_b g_logit[b].  Arithmetic in double, outputs fp32.  a [B,H] with w_out [H] (both or
+ * neither); b0, loss_out, db0_out point to one float; labels [B] in {0,1}.  logit_out, p_out,
+ * loss_out, da, dw_out, db0_out may be null.  B >= 1. */
+des_status_t des_head(const float *A_lr, const float *fm2, const float *a, const float *w_out, const float *b0,
+                      const float *labels, int64_t B, int32_t H, float *logit_out, float *p_out, float *loss_out,
+                      float *g_logit, float *da, float *dw_out, float *db0_out, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/* One optimizer step on a dense parameter array (every coordinate, every step): optimizer->opt_emb
+ * (SGD, ADAGRAD, ADAM or FTRL) with the formulas given at des_optimizer_t; s1 = Adagrad accumulator /
+ * Adam m / FTRL n, s2 = Adam v / FTRL z (null when the optimizer keeps no such state).  In place. */
+des_status_t des_dense_update(float *theta, const float *grad, float *s1, float *s2, int64_t n,
+                              const des_optimizer_t *optimizer, void *stream);
+
 /* Per-kernel timing with HIP events recorded on the caller's stream around every launch.
  * enable != 0 starts collecting and clears earlier records.  des_profile_read synchronises,
  * then fills up to `max` records (kernel name, launches, total milliseconds) and returns the

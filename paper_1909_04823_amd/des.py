@@ -28,6 +28,7 @@ EXPORTS = [
     "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_fm_finalize",
     "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge",
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
+    "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
     "des_profile_enable", "des_profile_read", "des_status_string",
 ]
 
@@ -85,6 +86,11 @@ _sig = {
     "des_dnn_partial_forward": [vp, vp, i64, i32, i32, i32, i32, vp, vp],
     "des_dnn_backward_bytes": [i64, i32, i32, i32, C.POINTER(C.c_size_t)],
     "des_dnn_backward": [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, C.c_size_t, vp],
+    "des_aggregate_bias_act": [vp, i32, i64, i32, vp, i32, vp, vp],
+    "des_dense_workspace_bytes": [i32, C.POINTER(C.c_size_t)],
+    "des_bias_act_backward": [vp, vp, i64, i32, i32, vp, vp, vp, C.c_size_t, vp],
+    "des_head": [vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp],
+    "des_dense_update": [vp, vp, vp, vp, i64, C.POINTER(Optimizer), vp],
     "des_profile_enable": [i32],
     "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
 }
@@ -318,6 +324,50 @@ def dnn_backward(pool: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, g_pool: 
     _check(_lib.des_dnn_backward(_ptr(pool), _ptr(W), _ptr(dY), B, F, D, H, _ptr(g_pool), _ptr(dW),
                                  _ptr(workspace), nbytes, _stream()), "des_dnn_backward")
     return g_pool, dW
+
+
+def aggregate_bias_act(P: torch.Tensor, bias: Optional[torch.Tensor], relu: bool,
+                       out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[r,h] = act(sum_s P[s,r,h] + bias[h]); P is [K, rows, H]."""
+    K, rows, H = P.shape
+    if out is None:
+        out = torch.empty((rows, H), dtype=torch.float32, device=P.device)
+    _check(_lib.des_aggregate_bias_act(_ptr(P), K, rows, H, _ptr(bias), int(relu), _ptr(out), _stream()),
+           "des_aggregate_bias_act")
+    return out
+
+
+def dense_workspace_bytes(H_max: int) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.des_dense_workspace_bytes(H_max, C.byref(n)), "des_dense_workspace_bytes")
+    return int(n.value)
+
+
+def _nbytes(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def bias_act_backward(A: torch.Tensor, dA: torch.Tensor, relu: bool, dZ: torch.Tensor, dbias: torch.Tensor,
+                      workspace: torch.Tensor):
+    rows, H = A.shape
+    _check(_lib.des_bias_act_backward(_ptr(A), _ptr(dA), rows, H, int(relu), _ptr(dZ), _ptr(dbias), _ptr(workspace),
+                                      _nbytes(workspace), _stream()), "des_bias_act_backward")
+    return dZ, dbias
+
+
+def head(labels: torch.Tensor, g_logit: torch.Tensor, workspace: torch.Tensor, A_lr=None, fm2=None, a=None,
+         w_out=None, b0=None, logit=None, p=None, loss=None, da=None, dw_out=None, db0=None):
+    """Output unit + mean log-loss + gradients (see des_head); every tensor is a device fp32 tensor."""
+    B = labels.shape[0]
+    H = 0 if a is None else a.shape[1]
+    _check(_lib.des_head(_ptr(A_lr), _ptr(fm2), _ptr(a), _ptr(w_out), _ptr(b0), _ptr(labels), B, H, _ptr(logit),
+                         _ptr(p), _ptr(loss), _ptr(g_logit), _ptr(da), _ptr(dw_out), _ptr(db0), _ptr(workspace),
+                         _nbytes(workspace), _stream()), "des_head")
+
+
+def dense_update(theta: torch.Tensor, grad: torch.Tensor, optimizer: Optimizer, s1=None, s2=None):
+    _check(_lib.des_dense_update(_ptr(theta), _ptr(grad), _ptr(s1), _ptr(s2), theta.numel(), C.byref(optimizer),
+                                 _stream()), "des_dense_update")
 
 
 def profile_enable(on: bool):

@@ -1,0 +1,149 @@
+"""One training step of LR / FM / W&D / DeepFM under DES on one MI355X, as a sequence of library calls.
+
+Nothing is computed here: every tensor operation is a call into libdes (``des.py``); this module only
+owns the device buffers and fixes the order of the calls --
+
+    find -> partial_forward -> aggregate x3, fm_finalize                    (sparse operators, Sections 4.1-4.2, 5)
+         -> dnn_partial_forward -> aggregate_bias_act -> dense layer -> head  (Section 4.3, tower, output unit)
+         -> head backward -> tower backward -> dnn_backward -> backward_update -> dense_update
+
+Model kinds follow the paper's table of shared components (Section 4): "lr" first order; "fm" first and
+second order; "wd" first and high order; "deepfm" all three.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import des
+
+COMPONENTS = {"lr": ("lr",), "fm": ("lr", "fm"), "wd": ("lr", "dnn"), "deepfm": ("lr", "fm", "dnn")}
+
+
+class Model:
+    def __init__(self, table: des.Table, F: int, kind: str, tower: Optional[Dict[str, np.ndarray]], B_max: int,
+                 opt_sparse: dict, opt_dense: dict):
+        """`table`: a des.Table whose state arrays fit `opt_sparse`; `tower`: initial dense parameters
+        (W1[F*D,H1], b1, W2[H1,H2], b2, w_out[H2], b0[1]) as numpy arrays; opt_*: des_optimizer_t fields."""
+        self.t, self.F, self.D, self.K = table, int(F), table.dim, table.K
+        self.parts = COMPONENTS[kind]
+        self.opt_sparse, self.opt_dense = dict(opt_sparse), dict(opt_dense)
+        self.step_no = 0
+        dev = table.emb.device
+        f = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+        z = lambda *shape: torch.zeros(shape, dtype=torch.float32, device=dev)
+        B, D, K = int(B_max), self.D, self.K
+        self.B_max = B
+        self.P_lr, self.P_sum, self.P_sq = f(K, B), f(K, B, D), f(K, B)
+        self.A_lr, self.A_sum, self.A_sq, self.fm2 = f(B), f(B, D), f(B), f(B)
+        self.logit, self.p, self.g_logit, self.loss, self.db0 = f(B), f(B), f(B), f(1), f(1)
+        self.n_uniq = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.rows = torch.empty(table.max_n, dtype=torch.int32, device=dev)
+        self.dnn = "dnn" in self.parts
+        H_max = 4
+        if self.dnn:
+            self.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(dev) for k, v in tower.items()}
+            H1, H2 = self.params["W1"].shape[1], self.params["W2"].shape[1]
+            self.H1, self.H2 = H1, H2
+            H_max = max(H1, H2)
+            self.pool, self.g_pool = f(B, F, D), f(B, F, D)
+            self.Y1p, self.a1, self.da1 = f(K, B, H1), f(B, H1), f(B, H1)
+            self.Y2p, self.a2, self.da2 = f(1, B, H2), f(B, H2), f(B, H2)
+            self.dnn_ws = torch.empty(max(des.dnn_backward_bytes(B, F, D, H1), des.dnn_backward_bytes(B, 1, H1, H2)),
+                                      dtype=torch.uint8, device=dev)
+        else:
+            self.params = {"b0": torch.from_numpy(np.ascontiguousarray(tower["b0"] if tower else np.zeros(1), dtype=np.float32)).to(dev)}
+        self.grads = {k: torch.empty_like(v) for k, v in self.params.items()}
+        self.s1 = {k: torch.zeros_like(v) for k, v in self.params.items()}
+        self.s2 = {k: torch.zeros_like(v) for k, v in self.params.items()}
+        self.ws = torch.empty(des.dense_workspace_bytes(H_max), dtype=torch.uint8, device=dev)
+
+    # ------------------------------------------------------------------------------------------
+    def forward(self, batch: des.Batch, rows: torch.Tensor, labels: torch.Tensor, backward_head: bool = True):
+        """Forward pass and the output unit's gradients for `batch` (B <= B_max); returns views."""
+        B, F, D = batch.B, self.F, self.D
+        if B != self.B_max:
+            raise ValueError("this driver keeps fixed-size buffers: batch.B must equal B_max")
+        p = self.params
+        fm = "fm" in self.parts
+        self.t.partial_forward(batch, rows, self.P_lr, self.P_sum if fm else None, self.P_sq if fm else None,
+                               self.pool if self.dnn else None)
+        des.aggregate_partials(self.P_lr, self.A_lr)
+        if fm:
+            des.aggregate_partials(self.P_sum, self.A_sum)
+            des.aggregate_partials(self.P_sq, self.A_sq)
+            des.fm_finalize(self.A_sum, self.A_sq, self.fm2)
+        if self.dnn:
+            des.dnn_partial_forward(self.pool, p["W1"], self.K, out=self.Y1p)
+            des.aggregate_bias_act(self.Y1p, p["b1"], True, self.a1)
+            des.dnn_partial_forward(self.a1.view(B, 1, self.H1), p["W2"], 1, out=self.Y2p)
+            des.aggregate_bias_act(self.Y2p, p["b2"], True, self.a2)
+        des.head(labels, self.g_logit, self.ws,
+                 A_lr=self.A_lr if "lr" in self.parts else None,
+                 fm2=self.fm2 if "fm" in self.parts else None,
+                 a=self.a2 if self.dnn else None, w_out=p["w_out"] if self.dnn else None, b0=p["b0"],
+                 logit=self.logit, p=self.p, loss=self.loss,
+                 da=self.da2 if (self.dnn and backward_head) else None,
+                 dw_out=self.grads["w_out"] if (self.dnn and backward_head) else None,
+                 db0=self.grads["b0"])
+        return self.loss
+
+    def backward(self, batch: des.Batch, rows: torch.Tensor, dbg: Optional[dict] = None):
+        """Tower backward, sparse backward + update, dense update.  Call after forward()."""
+        self.backward_tower(batch)
+        self.update(batch, rows, dbg)
+
+    def backward_tower(self, batch: des.Batch):
+        """Gradients of the dense parameters (self.grads) and of the pooled embeddings (self.g_pool)."""
+        p, g = self.params, self.grads
+        B = batch.B
+        if self.dnn:
+            des.bias_act_backward(self.a2, self.da2, True, self.da2, g["b2"], self.ws)               # da2 becomes dZ2
+            des.dnn_backward(self.a1.view(B, 1, self.H1), p["W2"], self.da2, self.da1.view(B, 1, self.H1), g["W2"],
+                             self.dnn_ws)
+            des.bias_act_backward(self.a1, self.da1, True, self.da1, g["b1"], self.ws)               # da1 becomes dZ1
+            des.dnn_backward(self.pool, p["W1"], self.da1, self.g_pool, g["W1"], self.dnn_ws)
+
+    def update(self, batch: des.Batch, rows: torch.Tensor, dbg: Optional[dict] = None):
+        """Sparse backward with merge and row update, then the dense optimizer step."""
+        g = self.grads
+        self.step_no += 1
+        sp = des.Optimizer(**dict(self.opt_sparse, step=self.step_no))
+        gl = self.g_logit
+        self.t.backward_update(batch, rows, sp,
+                               g_lr=gl if "lr" in self.parts else None,
+                               g_fm=gl if "fm" in self.parts else None,
+                               A_sum=self.A_sum if "fm" in self.parts else None,
+                               g_pool=self.g_pool if self.dnn else None,
+                               dbg=dbg if dbg is not None else {"n_uniq": self.n_uniq})
+        dn = des.Optimizer(**dict(self.opt_dense, step=self.step_no))
+        for k in self.params:
+            des.dense_update(self.params[k], g[k], dn, self.s1[k], self.s2[k])
+
+    def train_step(self, batch: des.Batch, labels: torch.Tensor, insert: bool = True):
+        rows = self.rows[:batch.nnz]
+        self.t.find(batch.keys, des.MISS_INSERT if insert else des.MISS_ZERO, rows)
+        self.forward(batch, rows, labels)
+        self.backward(batch, rows)
+        return self.loss
+
+
+def auc(labels: np.ndarray, scores: np.ndarray) -> float:
+    """Area under the ROC curve from host copies of labels and predictions (rank statistic with
+    ties sharing their mean rank).  An evaluation metric for reports, not part of the training path."""
+    labels = np.asarray(labels) > 0.5
+    scores = np.asarray(scores, dtype=np.float64)
+    order = np.argsort(scores, kind="stable")
+    s = scores[order]
+    ranks = np.empty(s.size, dtype=np.float64)
+    i = 0
+    bounds = np.flatnonzero(np.concatenate([[True], s[1:] != s[:-1], [True]]))
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        ranks[lo:hi] = 0.5 * (lo + hi - 1) + 1.0
+    r = np.empty_like(ranks); r[order] = ranks
+    n_pos, n_neg = int(labels.sum()), int((~labels).sum())
+    if n_pos == 0 or n_neg == 0:
+        return float("nan")
+    return float((r[labels].sum() - n_pos * (n_pos + 1) / 2.0) / (n_pos * n_neg))
