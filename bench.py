@@ -136,6 +136,9 @@ def main():
     ap.add_argument("--dnn-hidden", type=int, default=256,
                     help="width H of the first fully-connected layer measured after the sparse step and reported "
                          "under \"dnn_layer\" (0 to skip)")
+    ap.add_argument("--model", type=str, default="deepfm", choices=["none", "lr", "fm", "wd", "deepfm"],
+                    help="after the sparse steps, also time whole training steps of this model (tower widths "
+                         "--dnn-hidden and half of it) on the main workload; reported under \"model_step\"")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -356,6 +359,12 @@ def run_workload(args, index, cpu):
         n_cpu = max(1, min(B, int(np.ceil(args.cpu_lookups / max(1.0, host_batches[0].nnz / B)))))
         cpu_res = cpu_baseline(w, host_batches[0], n_cpu, 1 if w.opt == "sgd" else 2)
 
+    model_res = None
+    if args.model != "none" and index == args.config and not streaming and args.dnn_hidden >= 8:
+        del pool, g_pool, P_sum, P_lr, P_sq
+        torch.cuda.empty_cache()
+        model_res = run_model_step(args, w, table, batches, opt, eps)
+
     out = {
         "metric": "sparse lookups/sec, DES fwd+bwd step (samples/sec alongside)",
         "value": lookups / dt, "unit": "lookups/s", "samples_per_s": args.steps * B / dt,
@@ -368,9 +377,56 @@ def run_workload(args, index, cpu):
                    "find_policy": "insert" if miss == des.MISS_INSERT else "lookup", "setup_s": round(setup_s, 1)},
         "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
+    if model_res is not None:
+        out["model_step"] = model_res
     table.close()
-    del table, batches, pool, P_sum, g_pool
+    del table, batches
     return out
+
+
+def run_model_step(args, w, table, batches, opt, eps):
+    """Whole training steps of `--model` on the workload's table and batches: the sparse path as above
+    plus the first layer under DES, the tower (H, H/2), the output unit with log-loss on random
+    Bernoulli(0.2) labels, all backward passes and both optimizers.  Outside `value`."""
+    import torch
+    from paper_1909_04823_amd import des, synth
+    from paper_1909_04823_amd.model import Model
+    H = args.dnn_hidden
+    tower = synth.tower_init(w.seed, w.F, w.D, hidden=(H, max(4, H // 2 // 4 * 4)))
+    # small learning rates: with hundreds of entries per sample the workload's own rate makes the
+    # logits of random-label training blow up within a few steps, which says nothing about speed
+    m = Model(table, w.F, args.model, tower, w.B, dict(opt_emb=opt, opt_w=opt, lr=1e-3, eps=eps),
+              dict(opt_emb=des.OPT_ADAGRAD, lr=1e-3, eps=1e-8))
+    gen = torch.Generator(device="cuda"); gen.manual_seed(11)
+    labels = (torch.rand(w.B, device="cuda", generator=gen) < 0.2).float()
+    insert = w.preinsert < w.key_space
+    reps = max(3, min(args.steps, 5))
+    for i in range(2):
+        m.train_step(batches[i % len(batches)], labels, insert=insert)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    lookups = 0
+    for i in range(reps):
+        b = batches[i % len(batches)]
+        m.train_step(b, labels, insert=insert)
+        lookups += b.nnz
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    des.profile_enable(True)
+    for i in range(reps):
+        m.train_step(batches[i % len(batches)], labels, insert=insert)
+    prof = des.profile_read()
+    des.profile_enable(False)
+    assert table.status() == 0 and bool(torch.isfinite(m.loss).all())
+    flops = 2.0 * w.B * w.F * w.D * H
+    kernels = {}
+    for name, (launches, total_ms) in prof.items():
+        e = {"launches_per_step": launches / reps, "ms_per_step": round(total_ms / reps, 4)}
+        kernels[name] = e
+    return {"model": args.model, "hidden": [H, max(4, H // 2 // 4 * 4)], "steps": reps,
+            "ms_per_step": round(1e3 * dt / reps, 4), "lookups_per_s": lookups / dt, "samples_per_s": reps * w.B / dt,
+            "first_layer_flops_per_product": flops, "loss_last_step": float(m.loss.item()),
+            "kernel_ms_sum_per_step": round(sum(v["ms_per_step"] for v in kernels.values()), 4), "kernels": kernels}
 
 
 if __name__ == "__main__":
