@@ -395,7 +395,7 @@ def run_model_step(args, w, table, batches, opt, eps):
     tower = synth.tower_init(w.seed, w.F, w.D, hidden=(H, max(4, H // 2 // 4 * 4)))
     # small learning rates: with hundreds of entries per sample the workload's own rate makes the
     # logits of random-label training blow up within a few steps, which says nothing about speed
-    m = Model(table, w.F, args.model, tower, w.B, dict(opt_emb=opt, opt_w=opt, lr=1e-3, eps=eps),
+    m = Model(table, w.F, args.model, tower, w.B, dict(opt_emb=opt, opt_w=opt, lr=1e-5, eps=eps),
               dict(opt_emb=des.OPT_ADAGRAD, lr=1e-3, eps=1e-8))
     gen = torch.Generator(device="cuda"); gen.manual_seed(11)
     labels = (torch.rand(w.B, device="cuda", generator=gen) < 0.2).float()

@@ -77,6 +77,7 @@ def lib():
         L.oracle_head.argtypes = [vp, vp, vp, vp, f32, vp, i64, C.c_int, vp, vp, vp, vp, vp, vp, vp]
         L.oracle_dense_update.restype = None
         L.oracle_dense_update.argtypes = [vp, vp, vp, vp, i64, C.POINTER(Optimizer)]
+        L.oracle_table_migrate.restype = vp; L.oracle_table_migrate.argtypes = [vp, vp, i64]
         _lib = L
     return _lib
 
@@ -154,6 +155,20 @@ class Table:
     def acc2_emb(self): return self._view("acc2_emb", C.c_float, (self.n_rows, self.D))
     @property
     def acc2_w(self): return self._view("acc2_w", C.c_float, (self.n_rows,))
+
+    def migrate(self, keep=None, new_capacity: Optional[int] = None) -> "Table":
+        """New table holding the rows r with keep[r] != 0 (all when keep is None), renumbered in
+        ascending old-row order, weights and optimizer state unchanged; capacity `new_capacity`."""
+        cap = self.capacity if new_capacity is None else int(new_capacity)
+        keep = None if keep is None else _c(np.asarray(keep) != 0, np.uint8)
+        if keep is not None and keep.shape[0] != self.n_rows:
+            raise ValueError("keep must have one flag per row")
+        h = lib().oracle_table_migrate(self._h, _p(keep), cap)
+        if not h:
+            raise OracleError(ERR_FULL)
+        t = Table.__new__(Table)
+        t.D, t.capacity, t._h = self.D, cap, h
+        return t
 
     def insert(self, keys, values=None) -> np.ndarray:
         keys = _c(keys, np.uint64)

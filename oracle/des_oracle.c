@@ -499,3 +499,41 @@ void oracle_dense_update(float *theta, const float *grad, float *s1, float *s2, 
   for (int64_t i = 0; i < n; ++i)
     optimizer_step(o->opt_emb, o, (double)grad[i], theta + i, s1 ? s1 + i : NULL, s2 ? s2 + i : NULL);
 }
+
+/* ------------------------------------------------------------------ growth and eviction ---
+ * Section 1 ("Dynamic Features": the parameter set of a streaming recommender changes over time and
+ * keeps growing) and Section 5 (dynamic hash table).  The paper states the requirement, not a
+ * mechanism; this build's mechanism is a migration: the rows to keep move, in ascending row order,
+ * into a new table of any capacity that holds them.  Row i of the result is the i-th kept row of the
+ * source with its key, weights and optimizer state unchanged; keys of dropped rows are absent
+ * afterwards (looking one up with insertion creates a fresh row with initialiser weights).
+ * keep == NULL keeps every row (pure growth).  "parity unpinned" for the row order of the result
+ * (stable), which nothing in the paper fixes.  Returns NULL if the kept rows exceed new_capacity. */
+oracle_table *oracle_table_migrate(const oracle_table *src, const uint8_t *keep, int64_t new_capacity) {
+  if (!src) return NULL;
+  int64_t kept = 0;
+  for (int64_t r = 0; r < src->n_rows; ++r) kept += (!keep || keep[r]) ? 1 : 0;
+  if (kept > new_capacity) return NULL;
+  oracle_table *dst = oracle_table_create(src->D, new_capacity, src->seed, src->init_scale);
+  if (!dst) return NULL;
+  const int D = src->D;
+  int64_t n = 0;
+  for (int64_t r = 0; r < src->n_rows; ++r) {
+    if (keep && !keep[r]) continue;
+    dst->row_keys[n] = src->row_keys[r];
+    memcpy(dst->emb + n * D, src->emb + r * D, sizeof(float) * (size_t)D);
+    memcpy(dst->acc_emb + n * D, src->acc_emb + r * D, sizeof(float) * (size_t)D);
+    memcpy(dst->acc2_emb + n * D, src->acc2_emb + r * D, sizeof(float) * (size_t)D);
+    dst->w[n] = src->w[r]; dst->acc_w[n] = src->acc_w[r]; dst->acc2_w[n] = src->acc2_w[r];
+    ++n;
+  }
+  dst->n_rows = n;
+  /* key -> row map of the result: (key, row) pairs in ascending key order (insertion sort by
+   * repeated binary search would be quadratic; sort pairs instead) */
+  newkey_t *pairs = (newkey_t *)malloc(sizeof(newkey_t) * (size_t)(n > 0 ? n : 1));
+  for (int64_t i = 0; i < n; ++i) { pairs[i].key = dst->row_keys[i]; pairs[i].first = i; }
+  qsort(pairs, (size_t)n, sizeof(newkey_t), cmp_newkey);
+  for (int64_t i = 0; i < n; ++i) { dst->skeys[i] = pairs[i].key; dst->srows[i] = (int32_t)pairs[i].first; }
+  free(pairs);
+  return dst;
+}

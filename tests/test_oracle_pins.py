@@ -664,3 +664,49 @@ def test_whole_model_gradients_match_finite_differences(oracle, kind):
             ref[0] = old
             assert (up - dn) / (hi - lo) == pytest.approx(out["merged"][j, col], rel=1e-2, abs=2e-6), (r, col)
     assert checked >= 1
+
+
+# --------------------------------------------------------------------------- growth / eviction ----
+def test_migrate_against_python_dict(oracle):
+    """Eviction and growth against the plain description: surviving keys keep their weights and state and
+    are renumbered in their old order, dropped keys are gone and come back as fresh rows at the end."""
+    rng = np.random.default_rng(41)
+    D = 3
+    keys = np.unique(rng.integers(1, 2**63, 40, dtype=np.uint64))
+    rng.shuffle(keys)
+    t = oracle.Table(D, keys.size + 4, seed=9, init_scale=0.1)
+    vals = rng.standard_normal((keys.size, D + 1)).astype(np.float32)
+    t.insert(keys, vals)
+    # give every state array distinct contents through one Adam step on all rows
+    off = np.arange(keys.size + 1, dtype=np.int32)
+    t.backward_update(keys.size, 1, off, t.find(keys), g_lr=rng.standard_normal(keys.size).astype(np.float32),
+                      g_pool=rng.standard_normal((keys.size, 1, D)).astype(np.float32),
+                      optimizer=oracle.Optimizer(opt_emb=3, opt_w=3, lr=0.1, eps=1e-8, beta1=0.9, beta2=0.99, step=1))
+    snap = {int(k): (t.emb[r].copy(), t.w[r], t.acc_emb[r].copy(), t.acc_w[r], t.acc2_emb[r].copy(), t.acc2_w[r])
+            for r, k in enumerate(t.row_keys)}
+    keep = rng.random(keys.size) < 0.6
+    keep[0], keep[-1] = False, True
+    m = t.migrate(keep, new_capacity=keys.size * 2)
+    kept_keys = t.row_keys[keep]
+    assert m.n_rows == int(keep.sum()) and m.capacity == keys.size * 2
+    assert m.row_keys.tolist() == kept_keys.tolist()                     # stable renumbering
+    assert m.find(keys).tolist() == [int(np.flatnonzero(kept_keys == k)[0]) if k in set(kept_keys.tolist()) else -1
+                                     for k in keys]
+    for r, k in enumerate(m.row_keys):
+        e, wv, a, aw, a2, aw2 = snap[int(k)]
+        assert (m.emb[r] == e).all() and m.w[r] == wv and (m.acc_emb[r] == a).all() and m.acc_w[r] == aw
+        assert (m.acc2_emb[r] == a2).all() and m.acc2_w[r] == aw2
+    # a dropped key returns as a new row with initialiser weights and zero state
+    gone = t.row_keys[~keep][:2]
+    rows = m.find(gone, insert_missing=True)
+    assert rows.tolist() == [m.n_rows - 2, m.n_rows - 1]
+    for r, k in zip(rows, gone):
+        assert m.w[r] == np.float32(oracle.init_value(int(k), D, 9, 0.1)) and (m.acc_emb[r] == 0).all()
+    # the source is untouched; keeping everything reproduces it; too small a target is refused
+    assert t.n_rows == keys.size and t.find(keys).tolist() == list(range(keys.size))
+    g = t.migrate(None, new_capacity=keys.size)
+    assert g.row_keys.tolist() == t.row_keys.tolist() and (g.emb == t.emb).all() and (g.acc2_w == t.acc2_w).all()
+    with pytest.raises(oracle.OracleError):
+        t.migrate(None, new_capacity=keys.size - 1)
+    e = t.migrate(np.zeros(keys.size, bool))
+    assert e.n_rows == 0 and e.find(keys[:3]).tolist() == [-1, -1, -1]
