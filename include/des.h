@@ -124,7 +124,36 @@ des_status_t des_table_find(des_table_t *t, const uint64_t *keys, int64_t n, int
                             int32_t *rows_out, void *stream);
 
 des_status_t des_table_size(des_table_t *t, int64_t *n_rows_host);   /* synchronises */
-des_status_t des_table_status(des_table_t *t);                       /* synchronises; sticky device status */
+des_status_t des_table_status(des_table_t *t);
+
+/* ---- Growth and eviction (Section 1, "Dynamic Features": the parameter set of a streaming
+ * recommender changes and grows over time; Section 5).  The paper gives the requirement, not a
+ * mechanism; here rows migrate into a second table.
+ *
+ * des_table_migrate moves the rows r of `src` with keep[r] != 0 (keep: device, one byte per row of
+ * src; null keeps all = pure growth) into `dst`, a table created with des_table_create that is still
+ * empty, of the same dim and of any capacity that holds the kept rows.  Row i of dst is the i-th
+ * kept row of src (ascending row order) with its key, weights and every optimizer-state array both
+ * tables have; state arrays only dst has are zeroed for the moved rows.  dst's hash slots are built
+ * from the moved keys; src is left untouched (destroy it, or keep it as a snapshot).  src_aux /
+ * dst_aux (device, one uint32 per row, both or dst only or neither) is a caller array moved along
+ * with the rows, e.g. the last_seen stamps below.  The arrays of the two tables must not overlap.
+ * dst's workspace must hold des_table_migrate_bytes(rows of src) bytes, else DES_ERR_WORKSPACE.
+ * If the kept rows exceed dst's capacity nothing is moved and DES_ERR_FULL is returned (dst stays
+ * empty and usable).  A maintenance call: it synchronises with the stream and returns when the
+ * migration is complete; *n_rows_out (host, may be null) = rows of dst. */
+des_status_t des_table_migrate_bytes(int64_t n_rows, size_t *workspace_bytes);
+des_status_t des_table_migrate(des_table_t *src, const uint8_t *keep, des_table_t *dst, const uint32_t *src_aux,
+                               uint32_t *dst_aux, int64_t *n_rows_out, void *stream);
+
+/* Helpers for a least-recently-seen eviction policy.  last_seen: device, one uint32 per row, owned
+ * and zero-initialised by the caller.  mark_seen: last_seen[rows[e]] = stamp for every e < n with
+ * rows[e] >= 0 (rows as written by des_table_find).  select_recent: keep[r] = last_seen[r] >= min_stamp
+ * for r < n_rows. */
+des_status_t des_table_mark_seen(const int32_t *rows, int64_t n, uint32_t stamp, uint32_t *last_seen, void *stream);
+des_status_t des_table_select_recent(const uint32_t *last_seen, int64_t n_rows, uint32_t min_stamp, uint8_t *keep,
+                                     void *stream);
+                       /* synchronises; sticky device status */
 
 /* Sub-operators (Algorithm 1: M_j(w_i, x_i) for every shard i), rows from des_table_find.
  * Entries with row -1 contribute nothing.  Outputs are fully overwritten.

@@ -318,3 +318,15 @@ def dense_update(theta: np.ndarray, grad: np.ndarray, optimizer: Optimizer, s1=N
             raise ValueError("theta and state must be contiguous float32 (updated in place)")
     grad = _c(grad, np.float32)
     lib().oracle_dense_update(_p(theta), _p(grad), _p(s1), _p(s2), theta.size, C.byref(optimizer))
+
+
+def mark_seen(last_seen: np.ndarray, rows: np.ndarray, stamp: int) -> None:
+    """Least-recently-seen bookkeeping, the definition written out: every row that occurs in `rows`
+    (entries with row -1 are absent keys) gets `stamp`; in place on a uint32 array."""
+    rows = np.asarray(rows)
+    last_seen[rows[rows >= 0]] = np.uint32(stamp)
+
+
+def select_recent(last_seen: np.ndarray, n_rows: int, min_stamp: int) -> np.ndarray:
+    """keep[r] = last_seen[r] >= min_stamp for the first n_rows rows."""
+    return (np.asarray(last_seen[:n_rows]) >= np.uint32(min_stamp)).astype(np.uint8)

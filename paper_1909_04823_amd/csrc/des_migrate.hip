@@ -1,0 +1,203 @@
+// Growth and eviction of a table (Section 1, "Dynamic Features": the parameter set of a streaming
+// recommender changes and grows over time; Section 5: dynamic hash table).  The paper states the
+// requirement, not a mechanism.  Here the rows to keep move, in ascending row order, into a second,
+// empty table of any capacity that holds them, and that table's hash slots are built from the moved
+// keys: flags -> exclusive prefix sum (new row numbers) -> coalesced row copy -> parallel re-insert.
+// A maintenance operation, not part of the training step: it synchronises with the host twice to
+// size its launches and to refuse a target that is too small before anything is written.
+#include "des_internal.h"
+
+namespace des {
+namespace {
+
+inline unsigned blocks_for(int64_t n, int64_t cap = 1 << 20) {
+  int64_t g = (n + kBlock - 1) / kBlock;
+  return (unsigned)(g < 1 ? 1 : (g > cap ? cap : g));
+}
+
+__global__ __launch_bounds__(kBlock) void k_keep_flags(const uint8_t *__restrict__ keep, int64_t n,
+                                                        unsigned long long *__restrict__ flags) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += stride)
+    flags[r] = (!keep || keep[r]) ? 1ull : 0ull;
+}
+
+struct MoveArgs {
+  const uint64_t *src_keys; uint64_t *dst_keys;
+  const float *src_vec[3]; float *dst_vec[3];     // emb, acc_emb, acc2_emb  ([rows, D])
+  const float *src_sc[3]; float *dst_sc[3];       // w, acc_w, acc2_w        ([rows])
+  const uint32_t *src_aux; uint32_t *dst_aux;     // optional caller array, one word per row
+  const uint8_t *keep;
+  const unsigned long long *new_row;              // exclusive prefix sum of the keep flags
+  int64_t n;
+  int D;
+};
+
+// One lane group of D/4 lanes per source row: 16-byte loads and stores of the three vector arrays,
+// lane 0 of the group moves the key, the scalars and the caller's word.  A state array that only the
+// target has is zeroed for the moved rows; one that only the source has is dropped.
+__global__ __launch_bounds__(kBlock) void k_move_rows(const MoveArgs a) {
+  const int G = a.D / 4;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t r = gid / G;
+  const int sub = (int)(gid % G);
+  if (r >= a.n) return;
+  if (a.keep && !a.keep[r]) return;
+  const int64_t d = (int64_t)a.new_row[r];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    if (!a.dst_vec[i]) continue;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (a.src_vec[i]) v = *reinterpret_cast<const float4 *>(a.src_vec[i] + r * a.D + sub * 4);
+    *reinterpret_cast<float4 *>(a.dst_vec[i] + d * a.D + sub * 4) = v;
+  }
+  if (sub == 0) {
+    a.dst_keys[d] = a.src_keys[r];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+      if (a.dst_sc[i]) a.dst_sc[i][d] = a.src_sc[i] ? a.src_sc[i][r] : 0.f;
+    if (a.dst_aux) a.dst_aux[d] = a.src_aux ? a.src_aux[r] : 0u;
+  }
+}
+
+// Re-insert: row d's key claims the first empty slot of its probe sequence.  All keys are distinct,
+// so a claimed slot is never claimed twice; the row is stored after the claim (nothing reads the
+// slots until the stream has drained this kernel).
+__global__ __launch_bounds__(kBlock) void k_rehash(Slot *__restrict__ slots, uint64_t slot_mask,
+                                                    const uint64_t *__restrict__ row_keys, int64_t n,
+                                                    Ctrl *__restrict__ ctrl) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; d < n; d += stride) {
+    const uint64_t key = row_keys[d];
+    uint64_t idx = mix64(key) & slot_mask;
+    bool placed = false;
+    for (uint64_t probe = 0; probe <= slot_mask; ++probe) {
+      const unsigned long long old =
+          atomicCAS(reinterpret_cast<unsigned long long *>(&slots[idx].key), kEmptyKey, key);
+      if (old == kEmptyKey) {
+        slots[idx].row = (int32_t)d;
+        placed = true;
+        break;
+      }
+      idx = (idx + 1) & slot_mask;
+    }
+    if (!placed) atomicCAS(&ctrl->status, 0, (int)DES_ERR_FULL);
+  }
+}
+
+__global__ void k_set_rows(Ctrl *ctrl, long long n) { ctrl->n_rows = n; }
+
+__global__ __launch_bounds__(kBlock) void k_mark_seen(const int32_t *__restrict__ rows, int64_t n, uint32_t stamp,
+                                                       uint32_t *__restrict__ last_seen) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) {
+    const int32_t r = rows[e];
+    if (r >= 0) last_seen[r] = stamp;               // entries of one row all store the same value
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_select_recent(const uint32_t *__restrict__ last_seen, int64_t n,
+                                                           uint32_t min_stamp, uint8_t *__restrict__ keep) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n; r += stride)
+    keep[r] = last_seen[r] >= min_stamp ? 1 : 0;
+}
+
+bool overlap(const void *a, size_t na, const void *b, size_t nb) {
+  if (!a || !b) return false;
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+}  // namespace
+}  // namespace des
+
+using namespace des;
+
+extern "C" {
+
+des_status_t des_table_migrate_bytes(int64_t n_rows, size_t *workspace_bytes) {
+  if (!workspace_bytes || n_rows < 0) return DES_ERR_INVALID_ARG;
+  *workspace_bytes = 256 + align_up((size_t)(n_rows > 0 ? n_rows : 1) * 8, 256) + scan_scratch_bytes(n_rows > 0 ? n_rows : 1);
+  return DES_OK;
+}
+
+des_status_t des_table_migrate(des_table_t *src, const uint8_t *keep, des_table_t *dst, const uint32_t *src_aux,
+                               uint32_t *dst_aux, int64_t *n_rows_out, void *stream) {
+  if (!src || !dst || src == dst) return DES_ERR_INVALID_ARG;
+  const des_table_config_t &sc = src->cfg, &dc = dst->cfg;
+  if (sc.dim != dc.dim || ((uintptr_t)src_aux & 3u) || ((uintptr_t)dst_aux & 3u)) return DES_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  int64_t n = 0, n_dst = 0;
+  des_status_t st = des_table_size(src, &n);
+  if (st != DES_OK) return st;
+  st = des_table_size(dst, &n_dst);
+  if (st != DES_OK) return st;
+  if (n_dst != 0 || des_table_status(dst) != DES_OK || des_table_status(src) != DES_OK) return DES_ERR_INVALID_ARG;
+  const size_t row_bytes = (size_t)sc.dim * 4;
+  if (overlap(sc.emb, (size_t)sc.capacity_rows * row_bytes, dc.emb, (size_t)dc.capacity_rows * row_bytes) ||
+      overlap(sc.row_keys, (size_t)sc.capacity_rows * 8, dc.row_keys, (size_t)dc.capacity_rows * 8) ||
+      overlap(sc.w, (size_t)sc.capacity_rows * 4, dc.w, (size_t)dc.capacity_rows * 4) ||
+      overlap(sc.slots, sc.slots_bytes, dc.slots, dc.slots_bytes))
+    return DES_ERR_INVALID_ARG;
+  if (n_rows_out) *n_rows_out = 0;
+  src->last_stream = s;
+  dst->last_stream = s;
+  if (n == 0) return DES_OK;
+  size_t need = 0;
+  (void)des_table_migrate_bytes(n, &need);
+  if (dst->ws_bytes + 256 < need) return DES_ERR_WORKSPACE;
+  unsigned long long *flags = (unsigned long long *)dst->ws;
+  void *scan_scratch = dst->ws + align_up((size_t)n * 8, 256);
+  ProfScope ps(KID_MIGRATE, s);
+  hipLaunchKernelGGL(k_keep_flags, dim3(blocks_for(n)), dim3(kBlock), 0, s, keep, n, flags);
+  // the total lands in the target's row counter, which is exactly what it is
+  exclusive_scan_u64(flags, n, (unsigned long long *)&dst->ctrl->n_rows, scan_scratch, s);
+  long long kept = 0;
+  if (hipMemcpyAsync(&kept, &dst->ctrl->n_rows, sizeof(kept), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return DES_ERR_DEVICE;
+  if (kept > dc.capacity_rows) {                       // refuse before anything is moved
+    hipLaunchKernelGGL(k_set_rows, dim3(1), dim3(1), 0, s, dst->ctrl, 0ll);
+    (void)hipStreamSynchronize(s);
+    return DES_ERR_FULL;
+  }
+  MoveArgs a;
+  a.src_keys = sc.row_keys; a.dst_keys = dc.row_keys;
+  a.src_vec[0] = sc.emb; a.src_vec[1] = sc.acc_emb; a.src_vec[2] = sc.acc2_emb;
+  a.dst_vec[0] = dc.emb; a.dst_vec[1] = dc.acc_emb; a.dst_vec[2] = dc.acc2_emb;
+  a.src_sc[0] = sc.w; a.src_sc[1] = sc.acc_w; a.src_sc[2] = sc.acc2_w;
+  a.dst_sc[0] = dc.w; a.dst_sc[1] = dc.acc_w; a.dst_sc[2] = dc.acc2_w;
+  a.src_aux = src_aux; a.dst_aux = dst_aux;
+  a.keep = keep; a.new_row = flags; a.n = n; a.D = sc.dim;
+  const int64_t threads = n * (sc.dim / 4);
+  hipLaunchKernelGGL(k_move_rows, dim3((unsigned)((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, a);
+  if (kept > 0)
+    hipLaunchKernelGGL(k_rehash, dim3(blocks_for(kept, 1 << 16)), dim3(kBlock), 0, s, dst->slots, dst->n_slots - 1,
+                       (const uint64_t *)dc.row_keys, (int64_t)kept, dst->ctrl);
+  if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return DES_ERR_DEVICE;
+  if (n_rows_out) *n_rows_out = kept;
+  return (des_status_t)des_table_status(dst);
+}
+
+des_status_t des_table_mark_seen(const int32_t *rows, int64_t n, uint32_t stamp, uint32_t *last_seen, void *stream) {
+  if (n < 0 || (n > 0 && (!rows || !last_seen)) || ((uintptr_t)rows & 3u) || ((uintptr_t)last_seen & 3u))
+    return DES_ERR_INVALID_ARG;
+  if (n == 0) return DES_OK;
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope ps(KID_MIGRATE, s);
+  hipLaunchKernelGGL(k_mark_seen, dim3(blocks_for(n)), dim3(kBlock), 0, s, rows, n, stamp, last_seen);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+des_status_t des_table_select_recent(const uint32_t *last_seen, int64_t n_rows, uint32_t min_stamp, uint8_t *keep,
+                                     void *stream) {
+  if (n_rows < 0 || (n_rows > 0 && (!last_seen || !keep)) || ((uintptr_t)last_seen & 3u)) return DES_ERR_INVALID_ARG;
+  if (n_rows == 0) return DES_OK;
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope ps(KID_MIGRATE, s);
+  hipLaunchKernelGGL(k_select_recent, dim3(blocks_for(n_rows)), dim3(kBlock), 0, s, last_seen, n_rows, min_stamp, keep);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+}  // extern "C"

@@ -28,6 +28,7 @@ EXPORTS = [
     "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_fm_finalize",
     "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge",
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
+    "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
     "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
     "des_profile_enable", "des_profile_read", "des_status_string",
 ]
@@ -91,6 +92,10 @@ _sig = {
     "des_bias_act_backward": [vp, vp, i64, i32, i32, vp, vp, vp, C.c_size_t, vp],
     "des_head": [vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp],
     "des_dense_update": [vp, vp, vp, vp, i64, C.POINTER(Optimizer), vp],
+    "des_table_migrate_bytes": [i64, C.POINTER(C.c_size_t)],
+    "des_table_migrate": [vp, vp, vp, vp, vp, C.POINTER(i64), vp],
+    "des_table_mark_seen": [vp, i64, C.c_uint32, vp, vp],
+    "des_table_select_recent": [vp, i64, C.c_uint32, vp, vp],
     "des_profile_enable": [i32],
     "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
 }
@@ -211,6 +216,15 @@ class Table:
         _check(_lib.des_table_find(self._h, _ptr(keys), keys.numel(), miss, _ptr(rows_out), _stream()), "des_table_find")
         return rows_out
 
+    def migrate_into(self, dst: "Table", keep: Optional[torch.Tensor] = None, src_aux: Optional[torch.Tensor] = None,
+                     dst_aux: Optional[torch.Tensor] = None) -> int:
+        """Move the rows with keep[r] != 0 (uint8 device tensor; None = all) into the empty table `dst`
+        (des_table_migrate); returns dst's row count."""
+        n = i64(0)
+        _check(_lib.des_table_migrate(self._h, _ptr(keep), dst._h, _ptr(src_aux), _ptr(dst_aux), C.byref(n), _stream()),
+               "des_table_migrate")
+        return int(n.value)
+
     def size(self) -> int:
         n = i64(0)
         _check(_lib.des_table_size(self._h, C.byref(n)), "des_table_size")
@@ -271,6 +285,25 @@ class Table:
                 "counts": torch.empty(nnz, dtype=torch.int32, device=dev),
                 "merged": torch.empty((nnz, self.dim + 1), dtype=torch.float32, device=dev),
                 "n_uniq": torch.zeros(1, dtype=torch.int64, device=dev)}
+
+
+def migrate_bytes(n_rows: int) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.des_table_migrate_bytes(n_rows, C.byref(n)), "des_table_migrate_bytes")
+    return int(n.value)
+
+
+def mark_seen(rows: torch.Tensor, stamp: int, last_seen: torch.Tensor):
+    """last_seen[rows[e]] = stamp for the entries with a row (last_seen: int32 tensor holding uint32 stamps)."""
+    _check(_lib.des_table_mark_seen(_ptr(rows), rows.numel(), stamp, _ptr(last_seen), _stream()), "des_table_mark_seen")
+
+
+def select_recent(last_seen: torch.Tensor, n_rows: int, min_stamp: int, keep: Optional[torch.Tensor] = None):
+    if keep is None:
+        keep = torch.empty(n_rows, dtype=torch.uint8, device=last_seen.device)
+    _check(_lib.des_table_select_recent(_ptr(last_seen), n_rows, min_stamp, _ptr(keep), _stream()),
+           "des_table_select_recent")
+    return keep
 
 
 def aggregate_partials(P: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
