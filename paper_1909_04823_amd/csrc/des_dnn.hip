@@ -236,8 +236,19 @@ des_status_t des_dnn_backward(const float *pool, const float *W, const float *dY
   }
   if (dW) {                                       // dW[F*D, H] = pool^T x dY, split over slices of samples
     const long long tiles = ((FD + BM - 1) / BM) * ((H + BN - 1) / BN);
-    int Z = (int)((1024 + tiles - 1) / tiles);
-    if (Z > 16) Z = 16;
+    // Slices of samples: enough workgroups to fill the chip, chosen so that the last round of resident
+    // workgroups (two per CU for the two-level kernel, 256 CUs) is as full as possible; fewer slices win ties
+    // (less partial-sum traffic).  At most 16 slices, at least BK samples each.
+    int Z = 1;
+    {
+      const long long per_round = 2 * 256;
+      double best = -1.0;
+      for (int z = 1; z <= 16 && (long long)z * BK <= (B > BK ? B : BK); ++z) {
+        const long long blocks = tiles * z, rounds = (blocks + per_round - 1) / per_round;
+        const double fill = (double)blocks / (double)(rounds * per_round);
+        if (fill > best + 0.02) { best = fill; Z = z; }
+      }
+    }
     long long chunk = ((B + Z - 1) / Z + BK - 1) / BK * BK;
     Z = (int)((B + chunk - 1) / chunk);
     if (Z > 1 && (!workspace || workspace_bytes < (size_t)Z * FD * H * sizeof(float))) return DES_ERR_WORKSPACE;

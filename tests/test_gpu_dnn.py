@@ -73,9 +73,10 @@ def test_dnn_layer_argument_checks(des):
     dY = torch.zeros((4, 8), device="cuda")
     with pytest.raises(des.DesError):
         des.dnn_backward(pool, W, dY, None, None)                  # no output asked for
-    big = torch.zeros((64, 2, 4), device="cuda")
-    with pytest.raises(des.DesError):                              # sliced dW without a workspace
-        des.dnn_backward(big, W, torch.zeros((64, 8), device="cuda"), None, torch.zeros((8, 8), device="cuda"), None)
+    big = torch.zeros((5000, 2, 4), device="cuda")
+    with pytest.raises(des.DesError) as e:                         # dW summed over slices of samples needs the workspace
+        des.dnn_backward(big, W, torch.zeros((5000, 8), device="cuda"), None, torch.zeros((8, 8), device="cuda"), None)
+    assert e.value.code == des.ERR_WORKSPACE
     # empty batch: nothing launched, nothing written
     out = des.dnn_partial_forward(torch.zeros((0, 2, 4), device="cuda"), W, 2)
     assert out.shape == (2, 0, 8)
