@@ -1,6 +1,7 @@
 /*
- * libdes -- sparse hot path of Distributed Equivalent Substitution (DES) training
- * (arXiv 1909.04823) for one AMD MI355X (gfx950).  Plain C interface.
+ * libdes -- the hot path of Distributed Equivalent Substitution (DES) training
+ * (arXiv 1909.04823) for one AMD MI355X (gfx950): the sparse operators and their table, the first
+ * fully-connected layer under DES, and the dense remainder of a model step.  Plain C interface.
  *
  * A DES worker owns one shard of the sparse weights of a CTR model and replaces each
  * weights-rich operator by a sub-operator on its shard whose small result is aggregated
@@ -12,9 +13,9 @@
  *   - Every pointer named "device" is a device (HBM) pointer owned by the caller; it must
  *     stay valid until the stream the call was given has drained.  Pointers named "host"
  *     are ordinary host pointers.  The library allocates no device memory: all storage,
- *     including scratch, is handed over in des_table_config_t.
+ *     including scratch, is handed over in des_table_config_t or in a workspace argument.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
- *     enqueue work and return, except des_table_create/size/status/destroy and
+ *     enqueue work and return, except des_table_create/size/status/destroy/migrate and
  *     des_profile_read, which synchronise.
  *   - Errors the host can see (null pointers, bad sizes, buffers too small) return at once
  *     and enqueue nothing.  Errors only the device can see (table full, reserved key) set a
@@ -70,7 +71,7 @@ typedef enum { DES_MISS_ZERO = 0, DES_MISS_INSERT = 1 } des_miss_t;
 /* Table description.  The caller allocates every buffer (16-byte aligned). */
 typedef struct {
   int32_t dim;                 /* D, latent dimension                                        */
-  int64_t capacity_rows;       /* the table never rehashes or grows beyond this              */
+  int64_t capacity_rows;       /* fixed for the table's life; to grow, des_table_migrate      */
   int32_t num_shards;          /* K logical DES workers                                      */
   int32_t shard_policy;        /* des_shard_policy_t                                         */
   int32_t opt;                 /* des_opt_t; ADAGRAD requires acc_emb and acc_w              */
@@ -188,7 +189,9 @@ des_status_t des_fm_finalize(const float *A_sum, const float *A_sq, int64_t B, i
  *     Y_partial[s,b,h] = sum over fields f of shard s, d < D of  pool[b,f,d] * W[f*D+d, h].
  * des_aggregate_partials(Y_partial, K, B*H) then gives the layer output.  A shard with no field
  * (K > F) writes zeros.  fp32 in and out; products accumulate in fp32 on the matrix cores in
- * ascending k within 16-wide tiles.
+ * ascending k; a contraction deeper than 1024 products is summed in runs of 128 products that are
+ * then added up (two-level fp32 summation), which keeps a sum over a whole batch within the
+ * 1e-5 / 1e-6 bound of the rest of the library.
  * pool, W, Y_partial: device, 16-byte aligned, row-major as written; Y_partial [K,B,H] is owned by
  * the caller and fully overwritten.  D and H multiples of 4, 1 <= K <= 256, B < 2^31, F*D < 2^31,
  * else DES_ERR_INVALID_ARG.  B == 0 is a no-op (for the backward too: dW is then left untouched). */
@@ -201,9 +204,10 @@ des_status_t des_dnn_partial_forward(const float *pool, const float *W, int64_t 
  *     dW[j, h]     = sum_b pool[b,j] * dY[b,h]      j = f*D + d
  * Either output may be null (skipped), not both.  dW is computed in up to 16 slices of samples
  * that are summed in double; the slices live in `workspace` (device, 16-byte aligned, at least
- * des_dnn_backward_bytes() bytes; may be null when B <= 16).  Same shape rules as the forward;
- * DES_ERR_WORKSPACE if the workspace is too small.  The weight update of W itself is the
- * caller's (a dense optimizer step, outside the sparse path). */
+ * des_dnn_backward_bytes() bytes; not needed, and may be null, when dW is not asked for or the
+ * batch is so small that one slice is used).  Same shape rules as the forward; DES_ERR_WORKSPACE if
+ * the workspace is too small.  W itself is updated by des_dense_update with dW.  A plain dense layer
+ * Y = X W (X [B,Hin]) is the same pair of calls with F = 1, D = Hin, K = 1. */
 des_status_t des_dnn_backward_bytes(int64_t B, int32_t F, int32_t D, int32_t H, size_t *workspace_bytes);
 des_status_t des_dnn_backward(const float *pool, const float *W, const float *dY, int64_t B, int32_t F,
                               int32_t D, int32_t H, float *g_pool, float *dW, void *workspace,
