@@ -139,6 +139,9 @@ def main():
     ap.add_argument("--model", type=str, default="deepfm", choices=["none", "lr", "fm", "wd", "deepfm"],
                     help="after the sparse steps, also time whole training steps of this model (tower widths "
                          "--dnn-hidden and half of it) on the main workload; reported under \"model_step\"")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="run the whole step on one stream (default: the backward pass's sort runs on a second "
+                         "stream beside the forward pass)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -280,16 +283,30 @@ def run_workload(args, index, cpu):
     eps = w.eps if w.eps else 1e-8
     setup_s = time.perf_counter() - t_setup
 
+    # the row-sorting half of the backward pass needs only the rows, so it runs on a second stream
+    # (default priority) beside the forward pass; events order find -> sort -> update
+    main, aux = torch.cuda.current_stream(), torch.cuda.Stream()
+    ev_found, ev_sorted = torch.cuda.Event(), torch.cuda.Event()
+    overlap = not args.no_overlap
+
     def step(i):
         b = batches[i % len(batches)]
         r = rows[:b.nnz]
         table.find(b.keys, miss, r)
+        if overlap:
+            ev_found.record(main)
+            aux.wait_event(ev_found)
+            with torch.cuda.stream(aux):
+                table.backward_prepare(b, r)
+                ev_sorted.record(aux)
         table.partial_forward(b, r, P_lr, P_sum, P_sq, pool)
         des.aggregate_partials(P_lr, A_lr)
         des.aggregate_partials(P_sum, A_sum)
         des.aggregate_partials(P_sq, A_sq)
         des.fm_finalize(A_sum, A_sq, fm2)
         dbg = {"n_uniq": n_uniq}
+        if overlap:
+            main.wait_event(ev_sorted)
         if opt == des.OPT_SGD:
             table.backward_update_sgd(b, r, w.lr, g_lr, g_fm, A_sum, g_pool, dbg=dbg)
         else:
@@ -379,7 +396,8 @@ def run_workload(args, index, cpu):
         "config": {"workload": f"configs[{w.index}] {w.name}" + ("" if args.scale == 1.0 else f" scaled x{args.scale}"),
                    "B": B, "F": F, "D": D, "K": K, "optimizer": w.opt, "nnz_per_step": lookups / args.steps,
                    "table_rows": rows_before, "table_rows_after": table.size(), "distinct_batches": len(batches),
-                   "find_policy": "insert" if miss == des.MISS_INSERT else "lookup", "setup_s": round(setup_s, 1)},
+                   "find_policy": "insert" if miss == des.MISS_INSERT else "lookup", "setup_s": round(setup_s, 1),
+                   "streams": 2 if overlap else 1},
         "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
     if model_res is not None:

@@ -235,6 +235,16 @@ typedef struct {
   int64_t *n_uniq_out;
 } des_backward_io_t;
 
+/* Optional first half of the calls below, for overlap.  Sorting the batch's entries by row and cutting
+ * the sorted list into segments needs the batch and `rows` only, not the gradients, so it can run on a
+ * second stream while the forward pass and the loss head run on the first.  The sorted form stays in
+ * the table's workspace; the next des_backward_update* / des_backward_merge call for the same batch
+ * (same offsets, vals and rows pointers, same sizes) skips that half, any other call recomputes it.
+ * A des_table_insert or a des_table_find with DES_MISS_INSERT in between discards it (same
+ * workspace).  The caller orders the streams: prepare after the find that wrote `rows`, the update
+ * after prepare.  Results are identical with and without this call. */
+des_status_t des_backward_prepare(des_table_t *t, const des_batch_t *batch, const int32_t *rows, void *stream);
+
 des_status_t des_backward_update_sgd(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
                                      const des_backward_io_t *io, float lr, void *stream);
 des_status_t des_backward_update_adagrad(des_table_t *t, const des_batch_t *batch, const int32_t *rows,

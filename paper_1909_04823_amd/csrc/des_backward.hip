@@ -612,55 +612,22 @@ int bits_for(uint64_t max_value) {
   return b;
 }
 
-}  // namespace
-
-size_t backward_ws_bytes(int D, int64_t max_n) { return layout_for(D, max_n).total; }
-
-des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *rows, const des_backward_io_t *io,
-                             const des_optimizer_t *opt, hipStream_t s) {
-  const int64_t n = b->nnz;
-  const int D = t->cfg.dim;
-  if (n == 0) {
-    if (io->n_uniq_out) hipLaunchKernelGGL(k_set_i64, dim3(1), dim3(1), 0, s, io->n_uniq_out, (int64_t)0);
-    return DES_OK;
-  }
-  const Layout L = layout_for(D, n);
+// Row-sorting half of the backward pass: CSR -> (row, bag) pairs, sort by row, segment heads, split into
+// short and long segments.  Needs the batch and its rows only, not the gradients.  Returns which sort
+// buffer holds the sorted pairs.
+int sort_stage(des_table *t, BwdArgs &a, const Layout &L, hipStream_t s) {
   char *ws = t->ws;
-  BwdArgs a;
-  a.offsets = b->offsets; a.vals = b->vals; a.rows = rows;
-  a.g_lr = io->g_lr; a.g_fm = io->g_fm; a.A_sum = io->A_sum; a.g_pool = io->g_pool;
-  a.n = n; a.nbags = b->B * (int64_t)b->F; a.F = b->F;
-  a.missing = (uint32_t)t->cfg.capacity_rows;
-  a.emb = t->cfg.emb; a.w = t->cfg.w; a.acc_emb = t->cfg.acc_emb; a.acc_w = t->cfg.acc_w;
-  a.acc2_emb = t->cfg.acc2_emb; a.acc2_w = t->cfg.acc2_w;
-  a.row_keys = t->cfg.row_keys; a.ctrl = t->ctrl;
-  a.bag_of = (int32_t *)(ws + L.bag_of);
-  a.seg_off = (int32_t *)(ws + L.seg_off); a.uniq_rows = (int32_t *)(ws + L.uniq_rows);
-  a.first_pay = (uint32_t *)(ws + L.first_pay);
-  a.head_sums = (uint32_t *)(ws + L.head_sums);
-  a.long_seg = (int32_t *)(ws + L.long_seg); a.long_c0 = (uint32_t *)(ws + L.long_c0);
-  a.chunk_owner = (int32_t *)(ws + L.chunk_owner); a.partials = (double *)(ws + L.partials);
-  a.opt_emb = opt->opt_emb; a.opt_w = opt->opt_w; a.lr = opt->lr; a.eps = opt->eps;
-  a.b1 = opt->beta1; a.b2 = opt->beta2;
-  const double t_step = (double)(opt->step > 0 ? opt->step : 1);
-  a.c1 = (float)(1.0 / (1.0 - pow((double)opt->beta1, t_step)));
-  a.c2 = (float)(1.0 / (1.0 - pow((double)opt->beta2, t_step)));
-  a.f_alpha = opt->ftrl_alpha; a.f_beta = opt->ftrl_beta; a.f_l1 = opt->ftrl_l1; a.f_l2 = opt->ftrl_l2;
-  a.uniq_rows_out = io->uniq_rows_out; a.uniq_keys_out = io->uniq_keys_out; a.counts_out = io->counts_out;
-  a.merged_out = io->merged_out; a.n_uniq_out = io->n_uniq_out;
-  a.key_sorted = nullptr; a.pay_sorted = nullptr;
-
-  uint32_t *key_a = (uint32_t *)(ws + L.key_a), *key_b = (uint32_t *)(ws + L.key_b);
-  uint32_t *pay_a = (uint32_t *)(ws + L.pay_a), *pay_b = (uint32_t *)(ws + L.pay_b);
+  const int64_t n = a.n;
+  uint32_t *key_a = (uint32_t *)(ws + L.key_a), *pay_a = (uint32_t *)(ws + L.pay_a);
   {
     ProfScope ps(KID_EXPAND, s);
     if (a.vals) hipLaunchKernelGGL(k_expand<true>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);
     else hipLaunchKernelGGL(k_expand<false>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);  // one workgroup per kBlock bags
   }
-  SortBuffers sb{key_a, key_b, pay_a, pay_b};
+  SortBuffers sb{key_a, (uint32_t *)(ws + L.key_b), pay_a, (uint32_t *)(ws + L.pay_b)};
   const int side = radix_sort_u32_pairs(sb, n, bits_for((uint64_t)t->cfg.capacity_rows), ws + L.sort_scratch, s);
-  a.key_sorted = side ? key_b : key_a;
-  a.pay_sorted = side ? pay_b : pay_a;
+  a.key_sorted = (uint32_t *)(ws + (side ? L.key_b : L.key_a));
+  a.pay_sorted = (uint32_t *)(ws + (side ? L.pay_b : L.pay_a));
   {
     ProfScope ps(KID_HEADS, s);
     const int64_t nb = (n + kHeadTile - 1) / kHeadTile;
@@ -673,6 +640,77 @@ des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *
     hipLaunchKernelGGL(k_classify, dim3((unsigned)((n + kHeadTile - 1) / kHeadTile)), dim3(kBlock), 0, s, a);
     const int64_t max_long = n / (kShortMax + 1) + 1;
     hipLaunchKernelGGL(k_chunk_owner, dim3((unsigned)(max_long < 65536 ? max_long : 65536)), dim3(kBlock), 0, s, a);
+  }
+  return side;
+}
+
+void batch_args(des_table *t, const des_batch_t *b, const int32_t *rows, const Layout &L, BwdArgs &a) {
+  char *ws = t->ws;
+  a = BwdArgs{};
+  a.offsets = b->offsets; a.vals = b->vals; a.rows = rows;
+  a.n = b->nnz; a.nbags = b->B * (int64_t)b->F; a.F = b->F;
+  a.missing = (uint32_t)t->cfg.capacity_rows;
+  a.emb = t->cfg.emb; a.w = t->cfg.w; a.acc_emb = t->cfg.acc_emb; a.acc_w = t->cfg.acc_w;
+  a.acc2_emb = t->cfg.acc2_emb; a.acc2_w = t->cfg.acc2_w;
+  a.row_keys = t->cfg.row_keys; a.ctrl = t->ctrl;
+  a.bag_of = (int32_t *)(ws + L.bag_of);
+  a.seg_off = (int32_t *)(ws + L.seg_off); a.uniq_rows = (int32_t *)(ws + L.uniq_rows);
+  a.first_pay = (uint32_t *)(ws + L.first_pay);
+  a.head_sums = (uint32_t *)(ws + L.head_sums);
+  a.long_seg = (int32_t *)(ws + L.long_seg); a.long_c0 = (uint32_t *)(ws + L.long_c0);
+  a.chunk_owner = (int32_t *)(ws + L.chunk_owner); a.partials = (double *)(ws + L.partials);
+}
+
+__global__ void k_report_n_uniq(const Ctrl *ctrl, int64_t *out) { *out = ctrl->n_uniq; }
+
+}  // namespace
+
+size_t backward_ws_bytes(int D, int64_t max_n) { return layout_for(D, max_n).total; }
+
+des_status_t backward_prepare_launch(des_table *t, const des_batch_t *b, const int32_t *rows, hipStream_t s) {
+  t->prep.valid = false;
+  if (b->nnz == 0) return DES_OK;
+  const Layout L = layout_for(t->cfg.dim, b->nnz);
+  BwdArgs a;
+  batch_args(t, b, rows, L, a);
+  const int side = sort_stage(t, a, L, s);
+  if (hipGetLastError() != hipSuccess) return DES_ERR_DEVICE;
+  t->prep.valid = true;
+  t->prep.offsets = b->offsets; t->prep.rows = rows; t->prep.vals = b->vals;
+  t->prep.nnz = b->nnz; t->prep.B = b->B; t->prep.F = b->F; t->prep.side = side;
+  return DES_OK;
+}
+
+des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *rows, const des_backward_io_t *io,
+                             const des_optimizer_t *opt, hipStream_t s) {
+  const int64_t n = b->nnz;
+  const int D = t->cfg.dim;
+  const bool prepared = t->prep.valid && t->prep.offsets == b->offsets && t->prep.rows == rows &&
+                        t->prep.vals == b->vals && t->prep.nnz == n && t->prep.B == b->B && t->prep.F == b->F;
+  t->prep.valid = false;                          // the update consumes the sorted form
+  if (n == 0) {
+    if (io->n_uniq_out) hipLaunchKernelGGL(k_set_i64, dim3(1), dim3(1), 0, s, io->n_uniq_out, (int64_t)0);
+    return DES_OK;
+  }
+  const Layout L = layout_for(D, n);
+  char *ws = t->ws;
+  BwdArgs a;
+  batch_args(t, b, rows, L, a);
+  a.g_lr = io->g_lr; a.g_fm = io->g_fm; a.A_sum = io->A_sum; a.g_pool = io->g_pool;
+  a.opt_emb = opt->opt_emb; a.opt_w = opt->opt_w; a.lr = opt->lr; a.eps = opt->eps;
+  a.b1 = opt->beta1; a.b2 = opt->beta2;
+  const double t_step = (double)(opt->step > 0 ? opt->step : 1);
+  a.c1 = (float)(1.0 / (1.0 - pow((double)opt->beta1, t_step)));
+  a.c2 = (float)(1.0 / (1.0 - pow((double)opt->beta2, t_step)));
+  a.f_alpha = opt->ftrl_alpha; a.f_beta = opt->ftrl_beta; a.f_l1 = opt->ftrl_l1; a.f_l2 = opt->ftrl_l2;
+  a.uniq_rows_out = io->uniq_rows_out; a.uniq_keys_out = io->uniq_keys_out; a.counts_out = io->counts_out;
+  a.merged_out = io->merged_out; a.n_uniq_out = io->n_uniq_out;
+  if (prepared) {
+    a.key_sorted = (uint32_t *)(ws + (t->prep.side ? L.key_b : L.key_a));
+    a.pay_sorted = (uint32_t *)(ws + (t->prep.side ? L.pay_b : L.pay_a));
+    if (io->n_uniq_out) hipLaunchKernelGGL(k_report_n_uniq, dim3(1), dim3(1), 0, s, t->ctrl, io->n_uniq_out);
+  } else {
+    sort_stage(t, a, L, s);
   }
   switch (D) {
     case 4: launch_update_v<4>(a, s); break;

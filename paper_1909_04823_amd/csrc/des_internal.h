@@ -83,6 +83,15 @@ struct des_table {
   int64_t max_n;             // largest n the workspace was sized for (derived)
   float init_width;          // (float)(2*sqrt(3)*init_scale)
   hipStream_t last_stream;
+  // Row-sorted form of a batch left in the workspace by des_backward_prepare: which batch it was
+  // built for and which sort buffer holds the result.  Any call that reuses the workspace clears it.
+  struct {
+    bool valid;
+    const int32_t *offsets, *rows;
+    const float *vals;
+    int64_t nnz, B;
+    int F, side;
+  } prep;
 };
 
 namespace des {
@@ -91,6 +100,7 @@ des_status_t forward_launch(des_table *t, const des_batch_t *b, const int32_t *r
 des_status_t pool_dense_launch(des_table *t, const des_batch_t *b, const int32_t *rows, float *P_pool, hipStream_t s);
 des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *rows, const des_backward_io_t *io,
                              const des_optimizer_t *opt, hipStream_t s);
+des_status_t backward_prepare_launch(des_table *t, const des_batch_t *b, const int32_t *rows, hipStream_t s);
 size_t backward_ws_bytes(int D, int64_t max_n);
 size_t insert_ws_bytes(int64_t max_n);
 }  // namespace des

@@ -143,6 +143,7 @@ des_status_t des_table_migrate(des_table_t *src, const uint8_t *keep, des_table_
   if (n_rows_out) *n_rows_out = 0;
   src->last_stream = s;
   dst->last_stream = s;
+  dst->prep.valid = false;
   if (n == 0) return DES_OK;
   size_t need = 0;
   (void)des_table_migrate_bytes(n, &need);

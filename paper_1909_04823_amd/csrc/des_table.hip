@@ -483,6 +483,7 @@ des_status_t des_table_create(const des_table_config_t *cfg, des_table_t **out) 
   t->max_n = 0;
   t->init_width = (float)(2.0 * sqrt(3.0) * (double)cfg->init_scale);
   t->last_stream = nullptr;
+  t->prep.valid = false;
   // empty slot = all-ones key, row -1: one 16-byte pattern of 0xFF
   const uint4 ones = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
   hipLaunchKernelGGL(k_fill_u64x2, dim3(grid_for((int64_t)n_slots, kBlock, 65536)), dim3(kBlock), 0, nullptr,
@@ -508,6 +509,7 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
   if (!t || n < 0 || n >= 2147483647ll || (n > 0 && !keys)) return DES_ERR_INVALID_ARG;
   if (((uintptr_t)keys & 7u) || ((uintptr_t)rows_out & 3u) || ((uintptr_t)values & 3u)) return DES_ERR_INVALID_ARG;
   t->last_stream = s;
+  if (insert) t->prep.valid = false;             // inserts and a prepared batch share the workspace
   if (n == 0) return DES_OK;
   if (insert && insert_ws_bytes(n) > t->ws_bytes) return DES_ERR_WORKSPACE;
   const uint64_t mask = t->n_slots - 1;
@@ -716,6 +718,13 @@ des_status_t des_backward_update(des_table_t *t, const des_batch_t *batch, const
                                  const des_backward_io_t *io, const des_optimizer_t *optimizer, void *stream) {
   if (optimizer && (optimizer->opt_emb == DES_OPT_NONE) != (optimizer->opt_w == DES_OPT_NONE)) return DES_ERR_INVALID_ARG;
   return backward_api(t, batch, rows, io, optimizer, stream);
+}
+
+des_status_t des_backward_prepare(des_table_t *t, const des_batch_t *batch, const int32_t *rows, void *stream) {
+  des_status_t st = check_batch(t, batch, rows);
+  if (st != DES_OK) return st;
+  if (256 + backward_ws_bytes(t->cfg.dim, batch->nnz) > t->cfg.workspace_bytes) return DES_ERR_WORKSPACE;
+  return backward_prepare_launch(t, batch, rows, (hipStream_t)stream);
 }
 
 des_status_t des_backward_merge(des_table_t *t, const des_batch_t *batch, const int32_t *rows,

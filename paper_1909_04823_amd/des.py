@@ -26,7 +26,7 @@ EXPORTS = [
     "des_table_query_bytes", "des_table_create", "des_table_destroy", "des_table_insert", "des_table_find",
     "des_table_size", "des_table_status", "des_partial_forward_lr", "des_partial_forward_fm",
     "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_fm_finalize",
-    "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge",
+    "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge", "des_backward_prepare",
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
     "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
     "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
@@ -84,6 +84,7 @@ _sig = {
     "des_backward_update_adagrad": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), f32, f32, vp],
     "des_backward_update": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), C.POINTER(Optimizer), vp],
     "des_backward_merge": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), vp],
+    "des_backward_prepare": [vp, C.POINTER(BatchDesc), vp, vp],
     "des_dnn_partial_forward": [vp, vp, i64, i32, i32, i32, i32, vp, vp],
     "des_dnn_backward_bytes": [i64, i32, i32, i32, C.POINTER(C.c_size_t)],
     "des_dnn_backward": [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, C.c_size_t, vp],
@@ -272,6 +273,10 @@ class Table:
         io = self._io(g_lr, g_fm, A_sum, g_pool, dbg)
         _check(_lib.des_backward_update(self._h, C.byref(batch.desc), _ptr(rows), C.byref(io), C.byref(optimizer),
                                         _stream()), "des_backward_update")
+
+    def backward_prepare(self, batch, rows):
+        """Row-sorting half of the next backward call for this batch, on the current stream."""
+        _check(_lib.des_backward_prepare(self._h, C.byref(batch.desc), _ptr(rows), _stream()), "des_backward_prepare")
 
     def backward_merge(self, batch, rows, g_lr=None, g_fm=None, A_sum=None, g_pool=None, dbg=None):
         io = self._io(g_lr, g_fm, A_sum, g_pool, dbg)

@@ -78,6 +78,18 @@ class Pair:
             if g is not None:
                 cmp(g[:n].cpu().numpy(), getattr(self.ot, name), what + " " + name)
 
+    def sync_weights(self):
+        """Overwrite the library's weights and state with the oracle's, so that a test of several
+        steps checks each step's arithmetic from a common state instead of the drift of two fp32
+        trajectories (differences within tolerance are amplified by sums over hundreds of terms and
+        by the first Adagrad / Adam step of a row)."""
+        import torch
+        n = self.ot.n_rows
+        for name in ("emb", "w", "acc_emb", "acc_w", "acc2_emb", "acc2_w"):
+            g = getattr(self.gt, name)
+            if g is not None:
+                g[:n].copy_(torch.from_numpy(np.ascontiguousarray(getattr(self.ot, name))))
+
     # ---- one batch through both sides ---------------------------------------------------------
     def find(self, batch, insert=True):
         import torch
@@ -129,10 +141,21 @@ class Pair:
         self.fwd = {"A_lr": A_lr, "A_sum": A_sum, "fm2": fm2, "pool": pool_ref}
         return A_sum.astype(np.float32)
 
-    def backward(self, batch, g_lr, g_fm, A_sum, g_pool, lr=0.05, eps=1e-8, opt=None, optimizer=None):
+    def backward(self, batch, g_lr, g_fm, A_sum, g_pool, lr=0.05, eps=1e-8, opt=None, optimizer=None,
+                 prepare_stream=None):
         """`optimizer`: dict of des_optimizer_t fields (separate optimizers for latent vectors and
-        LR weights); otherwise `opt`, `lr`, `eps` for both."""
+        LR weights); otherwise `opt`, `lr`, `eps` for both.  `prepare_stream`: run the row-sorting
+        half (des_backward_prepare) on that stream first, ordered by events."""
         import torch
+        if prepare_stream is not None:
+            main = torch.cuda.current_stream()
+            found, sorted_ = torch.cuda.Event(), torch.cuda.Event()
+            found.record(main)
+            prepare_stream.wait_event(found)
+            with torch.cuda.stream(prepare_stream):
+                self.gt.backward_prepare(self.gb, self.rows_g)
+                sorted_.record(prepare_stream)
+            main.wait_event(sorted_)
         o, d = self.oracle, self.des
         opt = self.opt if opt is None else opt
         B, F = batch.B, batch.F

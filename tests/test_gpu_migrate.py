@@ -31,14 +31,6 @@ def train_step(p, w, step, last_seen_o=None, last_seen_g=None, oracle=None, des=
     return batch
 
 
-def sync_weights(p, torch):
-    """Continue both sides from the oracle's state (differences within tolerance would otherwise be
-    amplified by the next Adagrad step of rarely seen rows)."""
-    n = p.ot.n_rows
-    for name in ("emb", "w", "acc_emb", "acc_w"):
-        getattr(p.gt, name)[:n].copy_(torch.from_numpy(np.ascontiguousarray(getattr(p.ot, name))))
-
-
 @pytest.mark.parametrize("roomy", [True, False])
 def test_evict_least_recently_seen_then_keep_training(oracle, des, roomy):
     import torch
@@ -50,7 +42,7 @@ def test_evict_least_recently_seen_then_keep_training(oracle, des, roomy):
     ls_g = torch.zeros(w.capacity, dtype=torch.int32, device="cuda")
     for step in range(3):
         train_step(p, w, step, ls_o, ls_g, oracle, des)
-        sync_weights(p, torch)
+        p.sync_weights()
     n = p.check_table("before migration")
     assert_equal(ls_g[:n].cpu().numpy().view(np.uint32), ls_o[:n], "last_seen")
     # keep what was seen in the last two steps (stamps 2 and 3)

@@ -337,3 +337,42 @@ def test_host_side_argument_checks(des):
     assert e.value.code == des.ERR_INVALID_ARG
     assert t.status() == 0 and t.size() == 0
     t.close()
+
+
+def test_backward_prepare_on_a_second_stream(oracle, des):
+    """The row-sorting half of the backward pass issued ahead of time on another stream: same results
+    as without it (against the oracle, all integer outputs equal), also when the prepared batch is not
+    the one the update is then called for, and when an insert in between discards it."""
+    import torch
+    w = synth.workload(2, scale=1 / 64)
+    p = build_pair(oracle, des, w)
+    aux = torch.cuda.Stream()
+    try:
+        for step in range(3):
+            batch = synth.gen_batch(w, step, with_vals=(step == 1))
+            p.find(batch, insert=True)
+            A_sum = p.forward(batch)
+            g_lr, g_fm, g_pool = synth.upstream_gradients(w, step)
+            if step == 2:
+                # prepare, then grow the table (discards the sorted form), then update: must recompute
+                main = torch.cuda.current_stream()
+                p.gt.backward_prepare(p.gb, p.rows_g)
+                extra = np.array([3, 5, 7], np.uint64)
+                p.ot.insert(extra); p.gt.insert(dev(extra, torch))
+                p.backward(batch, g_lr, g_fm, A_sum, g_pool, lr=w.lr, eps=w.eps)
+            else:
+                p.backward(batch, g_lr, g_fm, A_sum, g_pool, lr=w.lr, eps=w.eps, prepare_stream=aux)
+            p.check_weights(f"step {step}")
+            p.sync_weights()
+        # a sorted form left by a different batch is not used
+        b0, b1 = synth.gen_batch(w, 10), synth.gen_batch(w, 11)
+        p.find(b0, insert=False)
+        gb0, rows0 = p.gb, p.rows_g
+        p.gt.backward_prepare(gb0, rows0)
+        p.find(b1, insert=False)
+        A_sum = p.forward(b1)
+        g_lr, g_fm, g_pool = synth.upstream_gradients(w, 11)
+        p.backward(b1, g_lr, g_fm, A_sum, g_pool, lr=w.lr, eps=w.eps)
+        p.check_weights("after a stale prepare")
+    finally:
+        p.close()
