@@ -287,13 +287,13 @@ def run_workload(args, index, cpu):
     # (default priority) beside the forward pass; events order find -> sort -> update
     main, aux = torch.cuda.current_stream(), torch.cuda.Stream()
     ev_found, ev_sorted = torch.cuda.Event(), torch.cuda.Event()
-    overlap = not args.no_overlap
+    overlap = [not args.no_overlap]      # the per-kernel pass below switches it off: concurrent kernels stretch each other
 
     def step(i):
         b = batches[i % len(batches)]
         r = rows[:b.nnz]
         table.find(b.keys, miss, r)
-        if overlap:
+        if overlap[0]:
             ev_found.record(main)
             aux.wait_event(ev_found)
             with torch.cuda.stream(aux):
@@ -305,7 +305,7 @@ def run_workload(args, index, cpu):
         des.aggregate_partials(P_sq, A_sq)
         des.fm_finalize(A_sum, A_sq, fm2)
         dbg = {"n_uniq": n_uniq}
-        if overlap:
+        if overlap[0]:
             main.wait_event(ev_sorted)
         if opt == des.OPT_SGD:
             table.backward_update_sgd(b, r, w.lr, g_lr, g_fm, A_sum, g_pool, dbg=dbg)
@@ -340,10 +340,12 @@ def run_workload(args, index, cpu):
     if not args.no_kernel_pass:
         first = total_steps if streaming else args.warmup
         des.profile_enable(True)
+        overlap[0] = False
         for i in range(first, first + args.steps):
             step(i)
         prof = des.profile_read()
         des.profile_enable(False)
+        overlap[0] = not args.no_overlap
         used = sorted({i % len(batches) for i in range(first, first + args.steps)})
         stats = [batch_stats(host_batches[i].keys) for i in used[:2]]
         st = {k: float(np.mean([s[k] for s in stats])) for k in stats[0]}
@@ -397,7 +399,7 @@ def run_workload(args, index, cpu):
                    "B": B, "F": F, "D": D, "K": K, "optimizer": w.opt, "nnz_per_step": lookups / args.steps,
                    "table_rows": rows_before, "table_rows_after": table.size(), "distinct_batches": len(batches),
                    "find_policy": "insert" if miss == des.MISS_INSERT else "lookup", "setup_s": round(setup_s, 1),
-                   "streams": 2 if overlap else 1},
+                   "streams": 1 if args.no_overlap else 2},
         "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
     if model_res is not None:
