@@ -129,21 +129,34 @@ __global__ __launch_bounds__(kBlock) void k_radix_hist(const KeyT *__restrict__ 
   for (int d = threadIdx.x; d < radix; d += kBlock) hist[(size_t)d * nblocks + blockIdx.x] = cnt[d];
 }
 
+// Scatter of one pass.  The tile is first put in digit order inside LDS (rank of an item = items of
+// smaller digits in the tile + items of its digit in earlier waves + earlier rounds of its wave +
+// lower lanes of its round, which is item order, so the pass is stable); then consecutive threads
+// write consecutive sorted items, so the items of one digit leave as one contiguous run instead of
+// one 4-byte store per lane.
 template <typename KeyT, bool kHasPayload>
 __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict__ keys_in,
                                                            const uint32_t *__restrict__ pay_in,
                                                            KeyT *__restrict__ keys_out, uint32_t *__restrict__ pay_out,
                                                            int64_t n, const long long *__restrict__ n_dev, int shift,
                                                            int bits, const uint32_t *__restrict__ offsets, int nblocks) {
-  __shared__ uint32_t cnt[kWavesPerBlock][kMaxRadix];
+  __shared__ uint32_t cnt[kWavesPerBlock][kMaxRadix];   // per wave and digit: count, then start inside the digit's run
+  __shared__ uint32_t dig_base[kMaxRadix];              // first sorted index of the digit inside the tile
+  __shared__ uint32_t gofs[kMaxRadix];                  // where the tile's run of the digit starts in the output
+  __shared__ uint32_t scan_lds[kWavesPerBlock];
+  __shared__ KeyT skey[kSortTile];
+  __shared__ uint32_t spay[kHasPayload ? kSortTile : 1];
   const int64_t n_eff = n_dev ? (int64_t)min((long long)n, *n_dev) : n;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t tile = (int64_t)blockIdx.x * kSortTile;
   if (tile >= n_eff) return;                         // uniform per workgroup
+  const int tile_n = (int)min((int64_t)kSortTile, n_eff - tile);
   const int radix = 1 << bits;
-  for (int d = threadIdx.x; d < radix; d += kBlock)
+  for (int d = threadIdx.x; d < radix; d += kBlock) {
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w) cnt[w][d] = 0;
+    gofs[d] = offsets[(size_t)d * nblocks + blockIdx.x];
+  }
   __syncthreads();
 
   const uint32_t mask = (1u << bits) - 1u;
@@ -177,26 +190,46 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict
     rank[r] = prev + before;
   }
   __syncthreads();
-  // per digit: exclusive prefix over the waves, on top of the tile's global offset
-  for (int d = threadIdx.x; d < radix; d += kBlock) {
-    uint32_t run = offsets[(size_t)d * nblocks + blockIdx.x];
+  // per digit: exclusive prefix over the waves; then exclusive prefix of the digit totals over the digits
+  // (two digits per thread: kMaxRadix <= 2 * kBlock)
+  static_assert(kMaxRadix <= 2 * kBlock, "two digits per thread");
+  uint32_t tot[2] = {0u, 0u};
 #pragma unroll
-    for (int w = 0; w < kWavesPerBlock; ++w) {
-      const uint32_t c = cnt[w][d];
-      cnt[w][d] = run;
-      run += c;
+  for (int j = 0; j < 2; ++j) {
+    const int d = threadIdx.x * 2 + j;
+    if (d < radix) {
+      uint32_t run = 0;
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) {
+        const uint32_t c = cnt[w][d];
+        cnt[w][d] = run;
+        run += c;
+      }
+      tot[j] = run;
     }
   }
+  uint32_t total;
+  const uint32_t ex = block_exclusive_scan<uint32_t>(tot[0] + tot[1], scan_lds, total);
+  if (threadIdx.x * 2 < radix) dig_base[threadIdx.x * 2] = ex;
+  if (threadIdx.x * 2 + 1 < radix) dig_base[threadIdx.x * 2 + 1] = ex + tot[0];
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < kSortItems; ++r) {
     const int64_t idx = wbase + r * kWave + lane;
     if (idx < n_eff) {
       const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
-      const uint32_t pos = cnt[wave][d] + rank[r];
-      keys_out[pos] = key[r];
-      if (kHasPayload) pay_out[pos] = pay[r];
+      const uint32_t li = dig_base[d] + cnt[wave][d] + rank[r];
+      skey[li] = key[r];
+      if (kHasPayload) spay[li] = pay[r];
     }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < tile_n; i += kBlock) {
+    const KeyT k = skey[i];
+    const uint32_t d = (uint32_t)(k >> shift) & mask;
+    const uint32_t pos = gofs[d] + ((uint32_t)i - dig_base[d]);
+    keys_out[pos] = k;
+    if (kHasPayload) pay_out[pos] = spay[i];
   }
 }
 
