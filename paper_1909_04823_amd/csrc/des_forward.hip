@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   extern __shared__ __align__(16) double lds[];
   constexpr int G = D / 4;                 // lanes per row = entries per chunk
   constexpr int NG = kWave / G;            // lane groups per wave
-  constexpr int U = G < 4 ? G : 4;         // row gathers in flight per lane
+  constexpr int U = G >= 16 ? 8 : (G < 4 ? G : 4);   // row gathers in flight per lane (measured: 8 pays from D = 64 on)
   constexpr int kLrLane = G > 1 ? 1 : 0;   // lane of a group that fetches and adds the LR weight
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / G, sub = lane % G;
