@@ -21,6 +21,7 @@ namespace {
 
 constexpr int kShortMax = 32;              // segments up to this many entries are reduced by one lane group
 constexpr int kChunk = 512;                // entries per chunk of a longer segment (one wave per chunk)
+constexpr int kShortGrid = 65536;          // most workgroups of the short-segment kernel (it strides over the segments)
 constexpr int kHeadItems = 8;
 constexpr int kHeadTile = kBlock * kHeadItems;
 constexpr int kWavesPerBlock = kBlock / kWave;
@@ -280,44 +281,67 @@ struct Acc {
 };
 __device__ inline Acc acc_zero() { Acc r; r.v[0] = r.v[1] = r.v[2] = r.v[3] = 0.0; r.s2 = 0.0; r.gw = 0.0; return r; }
 
+// Adds the terms of up to U entries whose bags (and values) are already known: all their upstream
+// gradient rows are requested before the first is used.
+template <int D, int U>
+__device__ inline void accumulate_batch(const BwdArgs &a, const uint32_t (&bag)[U], const bool (&live)[U],
+                                        const float (&x)[U], int sub, Acc &acc) {
+  float gf[U], gl[U];
+  float4 gp[U], as[U];
+#pragma unroll
+  for (int k = 0; k < U; ++k) {
+    const uint32_t b = bag[k] / (uint32_t)a.F;
+    gp[k] = (live[k] && a.g_pool) ? ld4(a.g_pool + (int64_t)bag[k] * D + sub * 4) : f4zero();
+    as[k] = (live[k] && a.g_fm) ? ld4(a.A_sum + (int64_t)b * D + sub * 4) : f4zero();
+    gf[k] = (live[k] && a.g_fm) ? a.g_fm[b] : 0.f;
+    gl[k] = (live[k] && a.g_lr) ? a.g_lr[b] : 0.f;
+  }
+#pragma unroll
+  for (int k = 0; k < U; ++k) {
+    if (!live[k]) continue;
+    const double xd = (double)x[k];
+    const double xg = xd * (double)gf[k];
+    acc.v[0] += xd * (double)gp[k].x + xg * (double)as[k].x;
+    acc.v[1] += xd * (double)gp[k].y + xg * (double)as[k].y;
+    acc.v[2] += xd * (double)gp[k].z + xg * (double)as[k].z;
+    acc.v[3] += xd * (double)gp[k].w + xg * (double)as[k].w;
+    acc.s2 += xd * xg;
+    acc.gw += xd * (double)gl[k];
+  }
+}
+
+// Bags (and values) of the sorted entries i .. i+U-1, clipped at i1.
+template <bool kHasVals, int U>
+__device__ inline void load_batch_meta(const BwdArgs &a, int i, int i1, uint32_t (&bag)[U], bool (&live)[U], float (&x)[U]) {
+#pragma unroll
+  for (int k = 0; k < U; ++k) {
+    live[k] = i + k < i1;
+    uint32_t p = live[k] ? a.pay_sorted[i + k] : 0u;
+    x[k] = 1.f;
+    if (kHasVals) {
+      if (live[k]) x[k] = a.vals[p];
+      p = live[k] ? (uint32_t)a.bag_of[p] : 0u;
+    }
+    bag[k] = p;
+  }
+}
+
+// Sums over the sorted entries [i0, i1), U at a time; the payloads of the next U entries are requested
+// before the gradient rows of the current ones, so a batch costs one memory round trip, not two.
 template <int D, bool kHasVals, int U>
 __device__ inline void reduce_entries(const BwdArgs &a, int i0, int i1, int sub, Acc &acc) {
+  uint32_t nbag[U];
+  bool nlive[U];
+  float nx[U];
+  if (i0 < i1) load_batch_meta<kHasVals, U>(a, i0, i1, nbag, nlive, nx);
   for (int i = i0; i < i1; i += U) {
     uint32_t bag[U];
     bool live[U];
-    float x[U], gf[U], gl[U];
-    float4 gp[U], as[U];
+    float x[U];
 #pragma unroll
-    for (int k = 0; k < U; ++k) {
-      live[k] = i + k < i1;
-      uint32_t p = live[k] ? a.pay_sorted[i + k] : 0u;
-      x[k] = 1.f;
-      if (kHasVals) {
-        if (live[k]) x[k] = a.vals[p];
-        p = live[k] ? (uint32_t)a.bag_of[p] : 0u;
-      }
-      bag[k] = p;
-    }
-#pragma unroll
-    for (int k = 0; k < U; ++k) {
-      const uint32_t b = bag[k] / (uint32_t)a.F;
-      gp[k] = (live[k] && a.g_pool) ? ld4(a.g_pool + (int64_t)bag[k] * D + sub * 4) : f4zero();
-      as[k] = (live[k] && a.g_fm) ? ld4(a.A_sum + (int64_t)b * D + sub * 4) : f4zero();
-      gf[k] = (live[k] && a.g_fm) ? a.g_fm[b] : 0.f;
-      gl[k] = (live[k] && a.g_lr) ? a.g_lr[b] : 0.f;
-    }
-#pragma unroll
-    for (int k = 0; k < U; ++k) {
-      if (!live[k]) continue;
-      const double xd = (double)x[k];
-      const double xg = xd * (double)gf[k];
-      acc.v[0] += xd * (double)gp[k].x + xg * (double)as[k].x;
-      acc.v[1] += xd * (double)gp[k].y + xg * (double)as[k].y;
-      acc.v[2] += xd * (double)gp[k].z + xg * (double)as[k].z;
-      acc.v[3] += xd * (double)gp[k].w + xg * (double)as[k].w;
-      acc.s2 += xd * xg;
-      acc.gw += xd * (double)gl[k];
-    }
+    for (int k = 0; k < U; ++k) { bag[k] = nbag[k]; live[k] = nlive[k]; x[k] = nx[k]; }
+    if (i + U < i1) load_batch_meta<kHasVals, U>(a, i + U, i1, nbag, nlive, nx);
+    accumulate_batch<D, U>(a, bag, live, x, sub, acc);
   }
 }
 
@@ -441,19 +465,56 @@ __device__ inline void add_entry(const BwdArgs &a, uint32_t p, int sub, Acc &acc
 template <int D, bool kHasVals>
 __global__ __launch_bounds__(kBlock) void k_short_update(const BwdArgs a) {
   constexpr int G = D / 4;
+  constexpr int U = 4;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t u = gid / G;
   const int sub = (int)(gid % G);
-  if (u >= a.ctrl->n_uniq) return;
-  const int i0 = a.seg_off[u], i1 = a.seg_off[u + 1];
-  const int row = a.uniq_rows[u];
-  const uint32_t p0 = a.first_pay[u];
-  if (i1 - i0 > kShortMax) return;
-  const RowState st = load_row<D>(a, row, sub);
-  Acc acc = acc_zero();
-  add_entry<D, kHasVals>(a, p0, sub, acc);
-  reduce_entries<D, kHasVals, 2>(a, i0 + 1, i1, sub, acc);
-  apply_row<D>(a, u, row, sub, st, acc);
+  const int64_t ngroups = (int64_t)gridDim.x * blockDim.x / G;
+  const int64_t n_uniq = a.ctrl->n_uniq;
+  // grid-stride over the segments: the grid is sized on the host for the chip, not for the (device-side) segment count
+  for (int64_t u = gid / G; u < n_uniq; u += ngroups) {
+    const int i0 = a.seg_off[u], i1 = a.seg_off[u + 1];
+    const int row = a.uniq_rows[u];
+    const uint32_t p0 = a.first_pay[u];
+    const int len = i1 - i0;
+    if (len > kShortMax) continue;
+    Acc acc = acc_zero();
+    if (G >= U) {
+      // The payloads of the next G entries are fetched lane by lane in the same round trip as the row state and
+      // the first entry's gradients, so a segment of up to G+1 entries costs 2 + ceil((len-1)/U) round trips.
+      uint32_t mine = (1 + sub < len) ? a.pay_sorted[i0 + 1 + sub] : 0u;
+      float myx = 1.f;
+      const RowState st = load_row<D>(a, row, sub);
+      add_entry<D, kHasVals>(a, p0, sub, acc);
+      const int glane = (int)(threadIdx.x & (kWave - 1)) - sub;       // first lane of this group in the wave
+      for (int base = 1; base < len; base += G) {
+        if (base > 1) mine = (base + sub < len) ? a.pay_sorted[i0 + base + sub] : 0u;
+        if (kHasVals) {
+          const bool have = base + sub < len;
+          myx = have ? a.vals[mine] : 1.f;
+          mine = have ? (uint32_t)a.bag_of[mine] : 0u;
+        }
+        const int cnt = min(G, len - base);
+        for (int j0 = 0; j0 < cnt; j0 += U) {
+          uint32_t bag[U];
+          bool live[U];
+          float x[U];
+#pragma unroll
+          for (int k = 0; k < U; ++k) {
+            live[k] = j0 + k < cnt;
+            bag[k] = __shfl(mine, glane + ((j0 + k) & (G - 1)), kWave);
+            x[k] = kHasVals ? __shfl(myx, glane + ((j0 + k) & (G - 1)), kWave) : 1.f;
+          }
+          accumulate_batch<D, U>(a, bag, live, x, sub, acc);
+        }
+      }
+      apply_row<D>(a, u, row, sub, st, acc);
+    } else {
+      const RowState st = load_row<D>(a, row, sub);
+      add_entry<D, kHasVals>(a, p0, sub, acc);
+      reduce_entries<D, kHasVals, 2>(a, i0 + 1, i1, sub, acc);
+      apply_row<D>(a, u, row, sub, st, acc);
+    }
+  }
 }
 
 // (4b) one wave per chunk of a long segment: the chunk is split evenly over the wave's lane
@@ -566,7 +627,7 @@ void launch_update(const BwdArgs &a, hipStream_t s) {
   const int64_t max_chunks = a.n / kChunk + max_long + 1;
   {
     ProfScope ps(KID_SHORT_UPDATE, s);
-    hipLaunchKernelGGL((k_short_update<D, kHasVals>), dim3(blocks_for(a.n * G)), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((k_short_update<D, kHasVals>), dim3(blocks_for(a.n * G, kShortGrid)), dim3(kBlock), 0, s, a);
   }
   {
     ProfScope ps(KID_LONG_PARTIAL, s);
