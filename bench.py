@@ -139,6 +139,9 @@ def main():
     ap.add_argument("--model", type=str, default="deepfm", choices=["none", "lr", "fm", "wd", "deepfm"],
                     help="after the sparse steps, also time whole training steps of this model (tower widths "
                          "--dnn-hidden and half of it) on the main workload; reported under \"model_step\"")
+    ap.add_argument("--policy", type=str, default="key", choices=["key", "field"],
+                    help="shard rule of the K logical shards: hash of the ID (default) or field index mod K "
+                         "(the placement of the paper's Section 5)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="run the whole step on one stream (default: the backward pass's sort runs on a second "
                          "stream beside the forward pass)")
@@ -250,7 +253,8 @@ def run_workload(args, index, cpu):
         host_batches = [synth.gen_batch(w, i) for i in range(n_batches)]
     max_nnz = max(b.nnz for b in host_batches)
     chunk = 1 << 22
-    table = des.Table(w.D, w.capacity, w.K, des.SHARD_KEY_HASH, opt, init_seed=w.seed, init_scale=w.init_std,
+    policy = des.SHARD_KEY_HASH if args.policy == "key" else des.SHARD_FIELD_MOD
+    table = des.Table(w.D, w.capacity, w.K, policy, opt, init_seed=w.seed, init_scale=w.init_std,
                       max_n=max(max_nnz, min(chunk, w.preinsert)))
     if streaming:
         for lo in range(0, first_keys.size, chunk):
@@ -399,7 +403,7 @@ def run_workload(args, index, cpu):
                    "B": B, "F": F, "D": D, "K": K, "optimizer": w.opt, "nnz_per_step": lookups / args.steps,
                    "table_rows": rows_before, "table_rows_after": table.size(), "distinct_batches": len(batches),
                    "find_policy": "insert" if miss == des.MISS_INSERT else "lookup", "setup_s": round(setup_s, 1),
-                   "streams": 1 if args.no_overlap else 2},
+                   "streams": 1 if args.no_overlap else 2, "shard_policy": args.policy},
         "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
     if model_res is not None:
