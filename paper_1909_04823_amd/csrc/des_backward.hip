@@ -519,7 +519,8 @@ __global__ __launch_bounds__(kBlock) void k_short_update(const BwdArgs a) {
 
 // (4b) one wave per chunk of a long segment: the chunk is split evenly over the wave's lane
 // groups, the groups' sums are combined with cross-lane shuffles, and the wave writes
-// partials[c] = (s1[D], s2, gw, 0, 0) in double
+// partials[c] = (s1[D], s2, gw, 0, 0) in double -- or, when the segment has no other chunk (33 .. 512
+// entries, most long segments), updates the row at once
 template <int D, bool kHasVals>
 __global__ __launch_bounds__(kBlock) void k_long_partial(const BwdArgs a) {
   constexpr int G = D / 4;
@@ -544,15 +545,21 @@ __global__ __launch_bounds__(kBlock) void k_long_partial(const BwdArgs a) {
     acc.gw += __shfl_xor(acc.gw, m, kWave);
   }
   if (g == 0) {
-    double *p = a.partials + c * (D + 4);
-    *reinterpret_cast<double2 *>(p + sub * 4) = make_double2(acc.v[0], acc.v[1]);
-    *reinterpret_cast<double2 *>(p + sub * 4 + 2) = make_double2(acc.v[2], acc.v[3]);
-    if (sub == 0) *reinterpret_cast<double2 *>(p + D) = make_double2(acc.s2, acc.gw);
+    if (a.seg_off[u + 1] - a.seg_off[u] <= kChunk) {
+      // the segment is this one chunk: the wave holds its whole sum and updates the row itself
+      const int row = a.uniq_rows[u];
+      apply_row<D>(a, u, row, sub, load_row<D>(a, row, sub), acc);
+    } else {
+      double *p = a.partials + c * (D + 4);
+      *reinterpret_cast<double2 *>(p + sub * 4) = make_double2(acc.v[0], acc.v[1]);
+      *reinterpret_cast<double2 *>(p + sub * 4 + 2) = make_double2(acc.v[2], acc.v[3]);
+      if (sub == 0) *reinterpret_cast<double2 *>(p + D) = make_double2(acc.s2, acc.gw);
+    }
   }
 }
 
-// (4c) one workgroup per long segment: lane groups stride over the chunk partials, an LDS tree
-// combines the groups, group 0 updates the row
+// (4c) one workgroup per long segment of several chunks: lane groups stride over the chunk partials, an
+// LDS tree combines the groups, group 0 updates the row
 template <int D>
 __global__ __launch_bounds__(kBlock) void k_long_final(const BwdArgs a) {
   constexpr int G = D / 4;
@@ -563,6 +570,7 @@ __global__ __launch_bounds__(kBlock) void k_long_final(const BwdArgs a) {
   for (int64_t j = blockIdx.x; j < NL; j += gridDim.x) {
     const int u = a.long_seg[j];
     const int nch = (a.seg_off[u + 1] - a.seg_off[u] + kChunk - 1) / kChunk;
+    if (nch == 1) continue;                    // updated by the wave that reduced its only chunk (uniform per workgroup)
     const double *p0 = a.partials + (int64_t)a.long_c0[j] * (D + 4);
     Acc acc = acc_zero();
     for (int c = grp; c < nch; c += NGB) {
