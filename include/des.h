@@ -316,6 +316,15 @@ des_status_t des_head(const float *A_lr, const float *fm2, const float *a, const
 des_status_t des_dense_update(float *theta, const float *grad, float *s1, float *s2, int64_t n,
                               const des_optimizer_t *optimizer, void *stream);
 
+/* Checks the part of the contract the other calls take on trust, for callers that cannot vouch for
+ * their batches (the kernels index memory with these values; a broken batch makes them fault):
+ * offsets[0] == 0, offsets non-decreasing, offsets[B*F] == nnz, and, when `rows` is given, every
+ * rows[e] in [-1, rows of the table).  Reads the whole batch on the device and synchronises.
+ * Returns DES_OK, or DES_ERR_INVALID_ARG with *first_bad (host, may be null) = index of the first
+ * offending offset (0 .. B*F), or B*F + 1 + e for the first offending rows[e]. */
+des_status_t des_batch_validate(des_table_t *t, const des_batch_t *batch, const int32_t *rows, int64_t *first_bad,
+                                void *stream);
+
 /* Per-kernel timing with HIP events recorded on the caller's stream around every launch.
  * enable != 0 starts collecting and clears earlier records.  des_profile_read synchronises,
  * then fills up to `max` records (kernel name, launches, total milliseconds) and returns the

@@ -28,6 +28,7 @@ struct Ctrl {
   long long n_chunks;      // chunks those long segments were cut into
   int status;              // sticky des_status_t
   int pad[5];
+  unsigned long long first_bad;   // verdict word of des_batch_validate
 };
 static_assert(sizeof(Ctrl) <= 256, "control block must fit its reserved 256 bytes");
 

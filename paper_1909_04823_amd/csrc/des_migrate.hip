@@ -103,6 +103,27 @@ __global__ __launch_bounds__(kBlock) void k_select_recent(const uint32_t *__rest
     keep[r] = last_seen[r] >= min_stamp ? 1 : 0;
 }
 
+// Smallest index whose value breaks the batch contract (see des_batch_validate); kept with an atomic minimum.
+__global__ __launch_bounds__(kBlock) void k_validate(const int32_t *__restrict__ offsets, int64_t nbags, int64_t nnz,
+                                                      const int32_t *__restrict__ rows, const Ctrl *__restrict__ ctrl,
+                                                      unsigned long long *__restrict__ first_bad) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t total = nbags + 1 + (rows ? nnz : 0);
+  const long long n_rows = ctrl->n_rows;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+    bool bad;
+    if (i <= nbags) {
+      const int32_t o = offsets[i];
+      bad = (i == 0 && o != 0) || (i == nbags && (int64_t)o != nnz) || (i > 0 && o < offsets[i - 1]) || o < 0 ||
+            (int64_t)o > nnz;
+    } else {
+      const int32_t r = rows[i - nbags - 1];
+      bad = r < -1 || (long long)r >= n_rows;
+    }
+    if (bad) atomicMin(first_bad, (unsigned long long)i);
+  }
+}
+
 bool overlap(const void *a, size_t na, const void *b, size_t nb) {
   if (!a || !b) return false;
   const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
@@ -179,6 +200,27 @@ des_status_t des_table_migrate(des_table_t *src, const uint8_t *keep, des_table_
   if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return DES_ERR_DEVICE;
   if (n_rows_out) *n_rows_out = kept;
   return (des_status_t)des_table_status(dst);
+}
+
+des_status_t des_batch_validate(des_table_t *t, const des_batch_t *batch, const int32_t *rows, int64_t *first_bad,
+                                void *stream) {
+  if (!t || !batch || batch->B < 0 || batch->F < 1 || batch->nnz < 0 || batch->nnz >= 2147483647ll ||
+      batch->B * (int64_t)batch->F >= 2147483647ll || !batch->offsets || ((uintptr_t)batch->offsets & 3u) ||
+      ((uintptr_t)rows & 3u))
+    return DES_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  unsigned long long *word = &t->ctrl->first_bad;
+  const unsigned long long none = ~0ull;
+  unsigned long long got = none;
+  const int64_t nbags = batch->B * (int64_t)batch->F, total = nbags + 1 + (rows ? batch->nnz : 0);
+  if (hipMemcpyAsync(word, &none, sizeof(none), hipMemcpyHostToDevice, s) != hipSuccess) return DES_ERR_DEVICE;
+  hipLaunchKernelGGL(k_validate, dim3(blocks_for(total, 1 << 16)), dim3(kBlock), 0, s, batch->offsets, nbags, batch->nnz,
+                     rows, t->ctrl, word);
+  if (hipMemcpyAsync(&got, word, sizeof(got), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess || hipGetLastError() != hipSuccess)
+    return DES_ERR_DEVICE;
+  if (first_bad) *first_bad = got == none ? -1 : (int64_t)got;
+  return got == none ? DES_OK : DES_ERR_INVALID_ARG;
 }
 
 des_status_t des_table_mark_seen(const int32_t *rows, int64_t n, uint32_t stamp, uint32_t *last_seen, void *stream) {

@@ -28,7 +28,7 @@ EXPORTS = [
     "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_fm_finalize",
     "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge", "des_backward_prepare",
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
-    "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
+    "des_batch_validate", "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
     "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
     "des_profile_enable", "des_profile_read", "des_status_string",
 ]
@@ -93,6 +93,7 @@ _sig = {
     "des_bias_act_backward": [vp, vp, i64, i32, i32, vp, vp, vp, C.c_size_t, vp],
     "des_head": [vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp],
     "des_dense_update": [vp, vp, vp, vp, i64, C.POINTER(Optimizer), vp],
+    "des_batch_validate": [vp, C.POINTER(BatchDesc), vp, C.POINTER(i64), vp],
     "des_table_migrate_bytes": [i64, C.POINTER(C.c_size_t)],
     "des_table_migrate": [vp, vp, vp, vp, vp, C.POINTER(i64), vp],
     "des_table_mark_seen": [vp, i64, C.c_uint32, vp, vp],
@@ -225,6 +226,15 @@ class Table:
         _check(_lib.des_table_migrate(self._h, _ptr(keep), dst._h, _ptr(src_aux), _ptr(dst_aux), C.byref(n), _stream()),
                "des_table_migrate")
         return int(n.value)
+
+    def validate(self, batch: "Batch", rows: Optional[torch.Tensor] = None) -> int:
+        """-1 if the batch (and rows) keep the contract the kernels rely on, else the index of the first
+        offending offset, or B*F+1+e for rows[e] (des_batch_validate; synchronises)."""
+        bad = i64(-1)
+        code = _lib.des_batch_validate(self._h, C.byref(batch.desc), _ptr(rows), C.byref(bad), _stream())
+        if code not in (OK, ERR_INVALID_ARG) or (code == ERR_INVALID_ARG and bad.value < 0):
+            raise DesError(code, "des_batch_validate")
+        return int(bad.value)
 
     def size(self) -> int:
         n = i64(0)

@@ -376,3 +376,34 @@ def test_backward_prepare_on_a_second_stream(oracle, des):
         p.check_weights("after a stale prepare")
     finally:
         p.close()
+
+
+def test_batch_validate(des):
+    """des_batch_validate reports the first broken offset or row index and accepts a sound batch."""
+    import torch
+    w = synth.workload(0)
+    t = des.Table(w.D, w.capacity, num_shards=w.K, opt=des.OPT_SGD, init_seed=w.seed, init_scale=w.init_std)
+    try:
+        t.insert(dev(synth.preinsert_keys(w), torch))
+        batch = synth.gen_batch(w, 0)
+        gb = des.Batch.from_numpy(batch)
+        rows = t.find(gb.keys)
+        assert t.validate(gb) == -1 and t.validate(gb, rows) == -1
+        nb = batch.B * batch.F
+
+        def with_offsets(off):
+            b = synth.Batch(batch.B, batch.F, batch.keys, off.astype(np.int32))
+            return des.Batch.from_numpy(b)
+
+        off = batch.offsets.copy(); off[0] = 1
+        assert t.validate(with_offsets(off)) == 0
+        off = batch.offsets.copy(); off[100] = off[101] + 3                      # decreasing at 101
+        assert t.validate(with_offsets(off)) == 101
+        off = batch.offsets.copy(); off[nb] += 1                                  # last offset != nnz
+        assert t.validate(with_offsets(off)) == nb
+        bad_rows = rows.clone(); bad_rows[17] = t.size(); bad_rows[500] = -2      # one past the last row; below -1
+        assert t.validate(gb, bad_rows) == nb + 1 + 17
+        bad_rows[17] = -1                                                         # -1 marks an absent key: fine
+        assert t.validate(gb, bad_rows) == nb + 1 + 500
+    finally:
+        t.close()
