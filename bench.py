@@ -142,6 +142,8 @@ def main():
     ap.add_argument("--policy", type=str, default="key", choices=["key", "field"],
                     help="shard rule of the K logical shards: hash of the ID (default) or field index mod K "
                          "(the placement of the paper's Section 5)")
+    ap.add_argument("--step-series", action="store_true",
+                    help="also report every timed step's duration (events on the main stream) under \"series_ms\"")
     ap.add_argument("--no-overlap", action="store_true",
                     help="run the whole step on one stream (default: the backward pass's sort runs on a second "
                          "stream beside the forward pass)")
@@ -248,7 +250,11 @@ def run_workload(args, index, cpu):
     if streaming:
         gen = synth.StreamingGenerator(w)
         first_keys = gen.initial_keys()
-        host_batches = [gen.next_batch() for _ in range(n_batches)]
+        host_batches = []
+        for i in range(n_batches):
+            host_batches.append(gen.next_batch())
+            if i % 10 == 9:                       # long set-ups stay visibly alive
+                print(f"bench.py: generated {i + 1} of {n_batches} streaming batches", file=sys.stderr, flush=True)
     else:
         host_batches = [synth.gen_batch(w, i) for i in range(n_batches)]
     max_nnz = max(b.nnz for b in host_batches)
@@ -329,12 +335,18 @@ def run_workload(args, index, cpu):
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)] if args.step_series else None
     t0 = time.perf_counter()
     lookups = 0
     for i in range(args.warmup, total_steps):
+        if marks:
+            marks[i - args.warmup].record(main)
         lookups += step(i)
+    if marks:
+        marks[-1].record(main)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    series = [round(marks[i].elapsed_time(marks[i + 1]), 4) for i in range(args.steps)] if marks else None
     assert table.status() == 0, "device-side error during the timed steps"
     assert bool(torch.isfinite(fm2).all()) and bool(torch.isfinite(pool).all())
     ms_per_step = 1e3 * dt / args.steps
@@ -406,6 +418,8 @@ def run_workload(args, index, cpu):
                    "streams": 1 if args.no_overlap else 2, "shard_policy": args.policy},
         "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
+    if series is not None:
+        out["series_ms"] = series
     if model_res is not None:
         out["model_step"] = model_res
     if migrate_res is not None:
