@@ -46,6 +46,16 @@ __device__ inline float4 ld4g(const float *p) { return *reinterpret_cast<const f
 template <bool kKContig>
 __device__ inline void load_tile(const float *__restrict__ P, long long rs, long long cs, int mn0, int MN,
                                  long long k0, long long kend, float4 (&r)[2]) {
+  // whole tile inside the operand (the same answer for every thread): plain 16-byte loads, no per-element guards
+  if (mn0 + BM <= MN && k0 + BK <= kend) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int idx = threadIdx.x + i * kBlock;
+      r[i] = kKContig ? ld4g(P + (long long)(mn0 + idx / 4) * rs + k0 + (idx % 4) * 4)
+                      : ld4g(P + (k0 + idx / 32) * cs + mn0 + (idx % 32) * 4);
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int idx = threadIdx.x + i * kBlock;
@@ -126,17 +136,28 @@ __global__ __launch_bounds__(kBlock) void k_gemm(const GemmArgs g) {
         load_tile<kAKContig>(g.A, g.a_rs, g.a_cs, m0, g.M, k0 + BK, kend, ra);
         load_tile<kBKContig>(g.B, g.b_cs, g.b_rs, n0, g.N, k0 + BK, kend, rb);
       }
+      // operands of step kk+2 are read from LDS before the MFMAs of step kk are issued
+      float a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = As[lk * LDA + wm * 64 + i * 32 + lrow];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = Bs[lk * LDB + wn * 64 + j * 32 + lrow];
 #pragma unroll
       for (int kk = 0; kk < BK; kk += 2) {
-        float a[2], b[2];
+        float an[2] = {0.f, 0.f}, bn[2] = {0.f, 0.f};
+        if (kk + 2 < BK) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = As[(kk + lk) * LDA + wm * 64 + i * 32 + lrow];
+          for (int i = 0; i < 2; ++i) an[i] = As[(kk + 2 + lk) * LDA + wm * 64 + i * 32 + lrow];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = Bs[(kk + lk) * LDB + wn * 64 + j * 32 + lrow];
+          for (int j = 0; j < 2; ++j) bn[j] = Bs[(kk + 2 + lk) * LDB + wn * 64 + j * 32 + lrow];
+        }
+        __builtin_amdgcn_sched_barrier(0);       // keep the reads above the MFMAs: the scheduler would sink them to their use
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
           for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) { a[i] = an[i]; b[i] = bn[i]; }
       }
       if (kTwoLevel && ++run == kFlushTiles) {
         run = 0;
