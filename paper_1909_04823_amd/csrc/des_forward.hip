@@ -62,7 +62,10 @@ __device__ inline double group_sum(double q) {
   return q;
 }
 
-template <int D>
+// kByKey: shard of an entry = hash of its ID (entries of a bag scatter over the shards: one LDS update per
+// entry).  Otherwise the field partition of Section 5: a bag belongs to shard f mod K as a whole, so its sums
+// are formed in registers and the shard's accumulators take one update per bag.
+template <int D, bool kByKey>
 __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   extern __shared__ __align__(16) double lds[];
   constexpr int G = D / 4;                 // lanes per row = entries per chunk
@@ -82,7 +85,7 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   const bool active = b < a.B;
   const bool need_fm = a.P_sum != nullptr, need_lr = a.P_lr != nullptr, need_pool = a.pool != nullptr;
   const bool need_v = need_fm || need_pool;
-  const bool by_key = a.policy == DES_SHARD_KEY_HASH;
+  constexpr bool by_key = kByKey;
   const int tis = wis * kWave + lane, nts = wps * kWave;  // thread in sample, threads per sample
 
   for (int i = tis; i < a.acc_doubles; i += nts) sum[i] = 0.0;
@@ -96,7 +99,29 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
     const int e0 = offs[f0], e1 = offs[f1];
     int cur = f0;                                         // bag whose sum is being accumulated
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    double bag_sq = 0.0, bag_lr = 0.0;                    // field partition: this lane's share of the bag's scalars
+    bool bag_dirty = false;
     float *pool_row = need_pool ? a.pool + (b * F) * (int64_t)D + sub * 4 : nullptr;
+    // closes bag `cur`: pooled sum out; under the field partition also the bag's contribution to its shard
+    auto close_bag = [&]() {
+      if (need_pool)
+        st4(pool_row + (int64_t)cur * D, make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
+      if (!kByKey && bag_dirty) {
+        const int s = cur % K;
+        if (need_fm) {
+          double *dst = sum + s * P + sub;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) atomicAdd(dst + k * G, acc[k]);
+          const double q = group_sum<G>(bag_sq);
+          if (sub == 0) atomicAdd(sum + s * P + D, q);
+        }
+        if (need_lr && sub == kLrLane) atomicAdd(sum + s * P + D + 1, bag_lr);
+        bag_sq = 0.0;
+        bag_lr = 0.0;
+        bag_dirty = false;
+      }
+      acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
+    };
 
     // metadata of entry e0 + sub of the first chunk; later chunks are fetched one chunk ahead
     int r_n = -1;
@@ -169,10 +194,7 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
             if (j0 + i < cnt) {
               const int bag = md[i].y, s = md[i].z;
               while (cur < bag) {                          // close finished (possibly empty) bags
-                if (need_pool)
-                  st4(pool_row + (int64_t)cur * D,
-                      make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
-                acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
+                close_bag();
                 ++cur;
               }
               if (md[i].x >= 0) {
@@ -181,6 +203,12 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
                                       xd * (double)v[i].w};
 #pragma unroll
                 for (int k = 0; k < 4; ++k) acc[k] += xv[k];
+                if (!kByKey) {
+                  bag_sq += xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
+                  bag_lr += xd * (double)wv[i];
+                  bag_dirty = true;
+                  continue;
+                }
                 double q = 0.0;
                 if (need_fm) {
                   double *dst = sum + s * P + sub;
@@ -203,9 +231,7 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
       }
     }
     while (cur < f1) {                                    // last bag of the range and empty ones after it
-      if (need_pool)
-        st4(pool_row + (int64_t)cur * D, make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
-      acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
+      close_bag();
       ++cur;
     }
   }
@@ -289,15 +315,16 @@ des_status_t forward_launch(des_table *t, const des_batch_t *b, const int32_t *r
   const int spb = kBlock / kWave / wps;
   const dim3 grid((unsigned)((b->B + spb - 1) / spb)), block(kBlock);
   const size_t shmem = 16 * (size_t)kBlock + (size_t)per_sample * 8 * spb;
+  const bool by_key = a.policy == DES_SHARD_KEY_HASH;
   ProfScope ps(KID_FORWARD, s);
   switch (D) {
-    case 4: hipLaunchKernelGGL(k_forward<4>, grid, block, shmem, s, a); break;
-    case 8: hipLaunchKernelGGL(k_forward<8>, grid, block, shmem, s, a); break;
-    case 16: hipLaunchKernelGGL(k_forward<16>, grid, block, shmem, s, a); break;
-    case 32: hipLaunchKernelGGL(k_forward<32>, grid, block, shmem, s, a); break;
-    case 64: hipLaunchKernelGGL(k_forward<64>, grid, block, shmem, s, a); break;
-    case 128: hipLaunchKernelGGL(k_forward<128>, grid, block, shmem, s, a); break;
-    case 256: hipLaunchKernelGGL(k_forward<256>, grid, block, shmem, s, a); break;
+    case 4: if (by_key) hipLaunchKernelGGL((k_forward<4, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<4, false>), grid, block, shmem, s, a); break;
+    case 8: if (by_key) hipLaunchKernelGGL((k_forward<8, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<8, false>), grid, block, shmem, s, a); break;
+    case 16: if (by_key) hipLaunchKernelGGL((k_forward<16, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<16, false>), grid, block, shmem, s, a); break;
+    case 32: if (by_key) hipLaunchKernelGGL((k_forward<32, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<32, false>), grid, block, shmem, s, a); break;
+    case 64: if (by_key) hipLaunchKernelGGL((k_forward<64, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<64, false>), grid, block, shmem, s, a); break;
+    case 128: if (by_key) hipLaunchKernelGGL((k_forward<128, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<128, false>), grid, block, shmem, s, a); break;
+    case 256: if (by_key) hipLaunchKernelGGL((k_forward<256, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<256, false>), grid, block, shmem, s, a); break;
     default: return DES_ERR_INVALID_ARG;
   }
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
