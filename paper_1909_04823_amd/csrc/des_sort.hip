@@ -144,8 +144,8 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict
   __shared__ uint32_t dig_base[kMaxRadix];              // first sorted index of the digit inside the tile
   __shared__ uint32_t gofs[kMaxRadix];                  // where the tile's run of the digit starts in the output
   __shared__ uint32_t scan_lds[kWavesPerBlock];
-  __shared__ KeyT skey[kSortTile];
-  __shared__ uint32_t spay[kHasPayload ? kSortTile : 1];
+  __shared__ KeyT skey[kSortTile];                      // the sorted keys; afterwards reused for the payloads
+  static_assert(sizeof(KeyT) >= sizeof(uint32_t), "payloads are staged in the key buffer");
   const int64_t n_eff = n_dev ? (int64_t)min((long long)n, *n_dev) : n;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t tile = (int64_t)blockIdx.x * kSortTile;
@@ -213,23 +213,44 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict
   if (threadIdx.x * 2 < radix) dig_base[threadIdx.x * 2] = ex;
   if (threadIdx.x * 2 + 1 < radix) dig_base[threadIdx.x * 2 + 1] = ex + tot[0];
   __syncthreads();
+  uint32_t li[kSortItems];
 #pragma unroll
   for (int r = 0; r < kSortItems; ++r) {
     const int64_t idx = wbase + r * kWave + lane;
+    li[r] = 0;
     if (idx < n_eff) {
       const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
-      const uint32_t li = dig_base[d] + cnt[wave][d] + rank[r];
-      skey[li] = key[r];
-      if (kHasPayload) spay[li] = pay[r];
+      li[r] = dig_base[d] + cnt[wave][d] + rank[r];
+      skey[li[r]] = key[r];
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < tile_n; i += kBlock) {
-    const KeyT k = skey[i];
-    const uint32_t d = (uint32_t)(k >> shift) & mask;
-    const uint32_t pos = gofs[d] + ((uint32_t)i - dig_base[d]);
-    keys_out[pos] = k;
-    if (kHasPayload) pay_out[pos] = spay[i];
+  // keys out; every thread remembers where its sorted items went, for the payloads that follow
+  constexpr int kOut = kSortTile / kBlock;
+  uint32_t pos[kOut];
+#pragma unroll
+  for (int j = 0; j < kOut; ++j) {
+    const int i = threadIdx.x + j * kBlock;
+    pos[j] = 0;
+    if (i < tile_n) {
+      const KeyT k = skey[i];
+      const uint32_t d = (uint32_t)(k >> shift) & mask;
+      pos[j] = gofs[d] + ((uint32_t)i - dig_base[d]);
+      keys_out[pos[j]] = k;
+    }
+  }
+  if (kHasPayload) {
+    uint32_t *spay = reinterpret_cast<uint32_t *>(skey);
+    __syncthreads();                                   // all keys read before the buffer is overwritten
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r)
+      if (wbase + r * kWave + lane < n_eff) spay[li[r]] = pay[r];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kOut; ++j) {
+      const int i = threadIdx.x + j * kBlock;
+      if (i < tile_n) pay_out[pos[j]] = spay[i];
+    }
   }
 }
 
