@@ -5,10 +5,12 @@
 // gradient of a weight is applied locally and the table row is updated.
 //
 // Steps: (1) expand the CSR batch to (row, bag) pairs, (2) stable radix sort by row, (3) mark
-// segment heads and compact them (ascending row order), (4) one lane group per short segment
-// reduces its entries in registers and updates the row in the same kernel; segments longer
-// than kChunk entries are cut into chunks that are reduced in parallel and combined by one
-// workgroup per segment, which then updates the row.
+// segment heads and compact them (ascending row order), (4) one lane group per segment of up to
+// kShortMax entries reduces its entries in registers and updates the row in the same kernel; longer
+// segments are cut into chunks of kChunk entries, one wave each: a segment that is a single chunk
+// is updated by that wave, the others are combined and updated by one workgroup per segment.
+// Steps (1)-(3) need the batch and its rows only and can be issued ahead of the gradients
+// (des_backward_prepare).
 //
 // Per entry e of bag (b,f) with value x:  d/dw += x*g_lr[b],
 //   d/dv += x*(g_fm[b]*A_sum[b,:] + g_pool[b,f,:]) - v * (x*x*g_fm[b])
