@@ -472,19 +472,19 @@ def run_model_step(args, w, table, batches, opt, eps):
     insert = w.preinsert < w.key_space
     reps = max(3, min(args.steps, 5))
     for i in range(2):
-        m.train_step(batches[i % len(batches)], labels, insert=insert)
+        m.train_step(batches[i % len(batches)], labels, insert=insert, overlap=not args.no_overlap)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     lookups = 0
     for i in range(reps):
         b = batches[i % len(batches)]
-        m.train_step(b, labels, insert=insert)
+        m.train_step(b, labels, insert=insert, overlap=not args.no_overlap)
         lookups += b.nnz
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     des.profile_enable(True)
     for i in range(reps):
-        m.train_step(batches[i % len(batches)], labels, insert=insert)
+        m.train_step(batches[i % len(batches)], labels, insert=insert, overlap=False)    # per-kernel times: one stream
     prof = des.profile_read()
     des.profile_enable(False)
     assert table.status() == 0 and bool(torch.isfinite(m.loss).all())

@@ -31,6 +31,7 @@ class Model:
         self.parts = COMPONENTS[kind]
         self.opt_sparse, self.opt_dense = dict(opt_sparse), dict(opt_dense)
         self.step_no = 0
+        self._aux = None
         dev = table.emb.device
         f = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
         z = lambda *shape: torch.zeros(shape, dtype=torch.float32, device=dev)
@@ -122,11 +123,27 @@ class Model:
         for k in self.params:
             des.dense_update(self.params[k], g[k], dn, self.s1[k], self.s2[k])
 
-    def train_step(self, batch: des.Batch, labels: torch.Tensor, insert: bool = True):
+    def train_step(self, batch: des.Batch, labels: torch.Tensor, insert: bool = True, overlap: bool = True):
+        """find -> forward -> backward -> updates.  With `overlap` the row-sorting half of the sparse backward
+        pass (des_backward_prepare, which needs only the rows) is issued on a second stream of default
+        priority right after the lookup, so it runs beside the forward pass and the tower's matrix products."""
         rows = self.rows[:batch.nnz]
         self.t.find(batch.keys, des.MISS_INSERT if insert else des.MISS_ZERO, rows)
+        if overlap:
+            if self._aux is None:
+                self._aux = torch.cuda.Stream()
+                self._found, self._sorted = torch.cuda.Event(), torch.cuda.Event()
+            main = torch.cuda.current_stream()
+            self._found.record(main)
+            self._aux.wait_event(self._found)
+            with torch.cuda.stream(self._aux):
+                self.t.backward_prepare(batch, rows)
+                self._sorted.record(self._aux)
         self.forward(batch, rows, labels)
-        self.backward(batch, rows)
+        self.backward_tower(batch)
+        if overlap:
+            torch.cuda.current_stream().wait_event(self._sorted)
+        self.update(batch, rows)
         return self.loss
 
 
