@@ -208,7 +208,8 @@ def test_deepfm_learns_planted_labels(des):
             loss = m.train_step(des.Batch.from_numpy(batch), dev(labels, torch), insert=False)   # unseen IDs are skipped
             losses.append(float(loss.item()))
             aucs.append(auc(labels, m.p.cpu().numpy()))
-        print("loss", np.round(losses[::10], 4), "auc", np.round(aucs[::10], 3), flush=True)
+        print("loss", np.round(losses[::10], 4), "auc", np.round(aucs[::10], 3), "last ten: loss",
+              round(float(np.mean(losses[-10:])), 4), "auc", round(float(np.mean(aucs[-10:])), 4), flush=True)
         assert gt.status() == 0 and all(np.isfinite(losses))
         assert np.mean(aucs[-10:]) > 0.6, aucs
         assert np.mean(losses[-10:]) < 0.60, losses
