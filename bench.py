@@ -147,6 +147,8 @@ def main():
     ap.add_argument("--no-overlap", action="store_true",
                     help="run the whole step on one stream (default: the backward pass's sort runs on a second "
                          "stream beside the forward pass)")
+    ap.add_argument("--tower", type=str, default=None,
+                    help="comma-separated hidden widths of the model step's tower (default: dnn-hidden, dnn-hidden/2)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -462,7 +464,8 @@ def run_model_step(args, w, table, batches, opt, eps):
     from paper_1909_04823_amd import des, synth
     from paper_1909_04823_amd.model import Model
     H = args.dnn_hidden
-    tower = synth.tower_init(w.seed, w.F, w.D, hidden=(H, max(4, H // 2 // 4 * 4)))
+    hidden = tuple(int(x) for x in args.tower.split(",")) if args.tower else (H, max(4, H // 2 // 4 * 4))
+    tower = synth.tower_init(w.seed, w.F, w.D, hidden=hidden)
     # throughput only: the table has just been through the sparse steps above, whose upstream gradients
     # are random, so the loss value of these steps means nothing (it is only checked to be finite)
     m = Model(table, w.F, args.model, tower, w.B, dict(opt_emb=opt, opt_w=opt, lr=1e-5, eps=eps),
@@ -488,12 +491,12 @@ def run_model_step(args, w, table, batches, opt, eps):
     prof = des.profile_read()
     des.profile_enable(False)
     assert table.status() == 0 and bool(torch.isfinite(m.loss).all())
-    flops = 2.0 * w.B * w.F * w.D * H
+    flops = 2.0 * w.B * w.F * w.D * hidden[0]
     kernels = {}
     for name, (launches, total_ms) in prof.items():
         e = {"launches_per_step": launches / reps, "ms_per_step": round(total_ms / reps, 4)}
         kernels[name] = e
-    return {"model": args.model, "hidden": [H, max(4, H // 2 // 4 * 4)], "steps": reps,
+    return {"model": args.model, "hidden": list(hidden), "steps": reps,
             "ms_per_step": round(1e3 * dt / reps, 4), "lookups_per_s": lookups / dt, "samples_per_s": reps * w.B / dt,
             "first_layer_flops_per_product": flops,
             "kernel_ms_sum_per_step": round(sum(v["ms_per_step"] for v in kernels.values()), 4), "kernels": kernels}

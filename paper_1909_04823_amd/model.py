@@ -25,8 +25,9 @@ COMPONENTS = {"lr": ("lr",), "fm": ("lr", "fm"), "wd": ("lr", "dnn"), "deepfm": 
 class Model:
     def __init__(self, table: des.Table, F: int, kind: str, tower: Optional[Dict[str, np.ndarray]], B_max: int,
                  opt_sparse: dict, opt_dense: dict):
-        """`table`: a des.Table whose state arrays fit `opt_sparse`; `tower`: initial dense parameters
-        (W1[F*D,H1], b1, W2[H1,H2], b2, w_out[H2], b0[1]) as numpy arrays; opt_*: des_optimizer_t fields."""
+        """`table`: a des.Table whose state arrays fit `opt_sparse`; `tower`: initial dense parameters as numpy
+        arrays -- W1[F*D,H1], b1[H1] (the layer under DES), W2[H1,H2], b2, ... Wn, bn (n >= 1 hidden layers),
+        w_out[Hn], b0[1]; opt_*: des_optimizer_t fields."""
         self.t, self.F, self.D, self.K = table, int(F), table.dim, table.K
         self.parts = COMPONENTS[kind]
         self.opt_sparse, self.opt_dense = dict(opt_sparse), dict(opt_dense)
@@ -46,14 +47,18 @@ class Model:
         H_max = 4
         if self.dnn:
             self.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(dev) for k, v in tower.items()}
-            H1, H2 = self.params["W1"].shape[1], self.params["W2"].shape[1]
-            self.H1, self.H2 = H1, H2
-            H_max = max(H1, H2)
+            self.n_layers = sum(1 for k in self.params if k[0] == "W")
+            self.H = [self.params[f"W{i + 1}"].shape[1] for i in range(self.n_layers)]       # widths H1..Hn
+            H_max = max(self.H)
             self.pool, self.g_pool = f(B, F, D), f(B, F, D)
-            self.Y1p, self.a1, self.da1 = f(K, B, H1), f(B, H1), f(B, H1)
-            self.Y2p, self.a2, self.da2 = f(1, B, H2), f(B, H2), f(B, H2)
-            self.dnn_ws = torch.empty(max(des.dnn_backward_bytes(B, F, D, H1), des.dnn_backward_bytes(B, 1, H1, H2)),
-                                      dtype=torch.uint8, device=dev)
+            # per layer i: partials Y (K shards for the first layer, one otherwise), activations a, their gradient da
+            self.Yp = [f(K if i == 0 else 1, B, h) for i, h in enumerate(self.H)]
+            self.a = [f(B, h) for h in self.H]
+            self.da = [f(B, h) for h in self.H]
+            ws_bytes = des.dnn_backward_bytes(B, F, D, self.H[0])
+            for i in range(1, self.n_layers):
+                ws_bytes = max(ws_bytes, des.dnn_backward_bytes(B, 1, self.H[i - 1], self.H[i]))
+            self.dnn_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         else:
             self.params = {"b0": torch.from_numpy(np.ascontiguousarray(tower["b0"] if tower else np.zeros(1), dtype=np.float32)).to(dev)}
         self.grads = {k: torch.empty_like(v) for k, v in self.params.items()}
@@ -77,16 +82,17 @@ class Model:
             des.aggregate_partials(self.P_sq, self.A_sq)
             des.fm_finalize(self.A_sum, self.A_sq, self.fm2)
         if self.dnn:
-            des.dnn_partial_forward(self.pool, p["W1"], self.K, out=self.Y1p)
-            des.aggregate_bias_act(self.Y1p, p["b1"], True, self.a1)
-            des.dnn_partial_forward(self.a1.view(B, 1, self.H1), p["W2"], 1, out=self.Y2p)
-            des.aggregate_bias_act(self.Y2p, p["b2"], True, self.a2)
+            x = self.pool                                   # [B, F, D]: the first layer is cut over the fields
+            for i in range(self.n_layers):
+                des.dnn_partial_forward(x, p[f"W{i + 1}"], self.K if i == 0 else 1, out=self.Yp[i])
+                des.aggregate_bias_act(self.Yp[i], p[f"b{i + 1}"], True, self.a[i])
+                x = self.a[i].view(B, 1, self.H[i])
         des.head(labels, self.g_logit, self.ws,
                  A_lr=self.A_lr if "lr" in self.parts else None,
                  fm2=self.fm2 if "fm" in self.parts else None,
-                 a=self.a2 if self.dnn else None, w_out=p["w_out"] if self.dnn else None, b0=p["b0"],
+                 a=self.a[-1] if self.dnn else None, w_out=p["w_out"] if self.dnn else None, b0=p["b0"],
                  logit=self.logit, p=self.p, loss=self.loss,
-                 da=self.da2 if (self.dnn and backward_head) else None,
+                 da=self.da[-1] if (self.dnn and backward_head) else None,
                  dw_out=self.grads["w_out"] if (self.dnn and backward_head) else None,
                  db0=self.grads["b0"])
         return self.loss
@@ -101,11 +107,14 @@ class Model:
         p, g = self.params, self.grads
         B = batch.B
         if self.dnn:
-            des.bias_act_backward(self.a2, self.da2, True, self.da2, g["b2"], self.ws)               # da2 becomes dZ2
-            des.dnn_backward(self.a1.view(B, 1, self.H1), p["W2"], self.da2, self.da1.view(B, 1, self.H1), g["W2"],
-                             self.dnn_ws)
-            des.bias_act_backward(self.a1, self.da1, True, self.da1, g["b1"], self.ws)               # da1 becomes dZ1
-            des.dnn_backward(self.pool, p["W1"], self.da1, self.g_pool, g["W1"], self.dnn_ws)
+            for i in range(self.n_layers - 1, -1, -1):
+                # da[i] becomes dZ[i] in place; then the layer's input gradient and weight gradient
+                des.bias_act_backward(self.a[i], self.da[i], True, self.da[i], g[f"b{i + 1}"], self.ws)
+                if i > 0:
+                    des.dnn_backward(self.a[i - 1].view(B, 1, self.H[i - 1]), p[f"W{i + 1}"], self.da[i],
+                                     self.da[i - 1].view(B, 1, self.H[i - 1]), g[f"W{i + 1}"], self.dnn_ws)
+                else:
+                    des.dnn_backward(self.pool, p["W1"], self.da[0], self.g_pool, g["W1"], self.dnn_ws)
 
     def update(self, batch: des.Batch, rows: torch.Tensor, dbg: Optional[dict] = None):
         """Sparse backward with merge and row update, then the dense optimizer step."""

@@ -304,16 +304,19 @@ def dnn_layer_inputs(seed: int, B: int, F: int, D: int, H: int):
 
 
 def tower_init(seed: int, F: int, D: int, hidden=(256, 128)):
-    """Initial dense parameters of the tower after the pooled embeddings: W1[F*D,H1], b1[H1],
-    W2[H1,H2], b2[H2], w_out[H2], b0[1].  Weights N(0, 2/fan_in) (the usual scaling before a ReLU),
-    hidden biases 0.01, output bias 0."""
+    """Initial dense parameters of the tower after the pooled embeddings, for hidden widths H1..Hn:
+    W1[F*D,H1], b1[H1], W2[H1,H2], b2[H2], ..., w_out[Hn], b0[1].  Weights N(0, 2/fan_in) (the usual
+    scaling before a ReLU), hidden biases 0.01, output bias 0."""
     rng = np.random.default_rng((int(seed), 0x70E))
-    H1, H2 = hidden
     n = lambda rows, cols: (rng.standard_normal((rows, cols), dtype=np.float32) * np.float32(np.sqrt(2.0 / rows)))
-    return {"W1": n(F * D, H1), "b1": np.full(H1, 0.01, np.float32),
-            "W2": n(H1, H2), "b2": np.full(H2, 0.01, np.float32),
-            "w_out": (rng.standard_normal(H2, dtype=np.float32) * np.float32(np.sqrt(1.0 / H2))),
-            "b0": np.zeros(1, np.float32)}
+    out, fan_in = {}, F * D
+    for i, h in enumerate(hidden):
+        out[f"W{i + 1}"] = n(fan_in, h)
+        out[f"b{i + 1}"] = np.full(h, 0.01, np.float32)
+        fan_in = h
+    out["w_out"] = rng.standard_normal(fan_in, dtype=np.float32) * np.float32(np.sqrt(1.0 / fan_in))
+    out["b0"] = np.zeros(1, np.float32)
+    return out
 
 
 def planted_labels(batch: Batch, seed: int, base_rate_logit: float = -1.4, strength: float = 1.5) -> np.ndarray:

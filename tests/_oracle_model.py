@@ -33,10 +33,14 @@ class OracleModel:
             pool = t.partial_forward(B, F, batch.keys, batch.offsets, rows, 1, self.policy, batch.vals,
                                      lr=False, fm=False, pool=True)["P_pool"][0]
             c["pool"] = f32(pool)
-            c["a1"] = f32(o.bias_act(o.aggregate(o.dnn_partial_forward(c["pool"], p["W1"], K)), p["b1"], True))
-            c["a2"] = f32(o.bias_act(o.dnn_partial_forward(c["a1"][:, None, :], p["W2"], 1)[0], p["b2"], True))
-        c["head"] = o.head(labels, c["A_lr"], c["fm2"], c.get("a2"), p["w_out"] if "dnn" in self.parts else None,
-                           float(p["b0"][0]))
+            n_layers = sum(1 for k in p if k[0] == "W")
+            x, c["a"] = c["pool"], []
+            for i in range(n_layers):
+                Y = o.aggregate(o.dnn_partial_forward(x, p[f"W{i + 1}"], K if i == 0 else 1))
+                c["a"].append(f32(o.bias_act(Y, p[f"b{i + 1}"], True)))
+                x = c["a"][i][:, None, :]
+        c["head"] = o.head(labels, c["A_lr"], c["fm2"], c["a"][-1] if "dnn" in self.parts else None,
+                           p["w_out"] if "dnn" in self.parts else None, float(p["b0"][0]))
         return c
 
     def loss(self, batch, rows, labels):
@@ -52,11 +56,14 @@ class OracleModel:
         c["g_pool"] = None
         if "dnn" in self.parts:
             g["w_out"] = h["dw_out"]
-            dZ2, g["b2"] = o.bias_act_backward(c["a2"], f32(h["da"]), True)
-            da1, g["W2"] = o.dnn_backward(c["a1"][:, None, :], p["W2"], f32(dZ2))
-            dZ1, g["b1"] = o.bias_act_backward(c["a1"], f32(da1[:, 0, :]), True)
-            g_pool, g["W1"] = o.dnn_backward(c["pool"], p["W1"], f32(dZ1))
-            c["g_pool"] = f32(g_pool)
+            da = f32(h["da"])
+            for i in range(len(c["a"]) - 1, -1, -1):
+                dZ, g[f"b{i + 1}"] = o.bias_act_backward(c["a"][i], da, True)
+                x = c["a"][i - 1][:, None, :] if i > 0 else c["pool"]
+                dx, g[f"W{i + 1}"] = o.dnn_backward(x, p[f"W{i + 1}"], f32(dZ))
+                da = f32(dx[:, 0, :]) if i > 0 else None
+                if i == 0:
+                    c["g_pool"] = f32(dx)
         c["dense_grads"] = g
         return c
 

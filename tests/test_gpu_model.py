@@ -112,9 +112,10 @@ SETTINGS = {
 }
 
 
-@pytest.mark.parametrize("kind,setting", [("lr", "sgd"), ("fm", "sgd"), ("wd", "sgd"), ("deepfm", "sgd"),
-                                          ("deepfm", "paper")])
-def test_training_steps_match_oracle_chain(oracle, des, kind, setting):
+@pytest.mark.parametrize("kind,setting,hidden", [("lr", "sgd", (64, 32)), ("fm", "sgd", (64, 32)), ("wd", "sgd", (64, 32)),
+                                                 ("deepfm", "sgd", (64, 32)), ("deepfm", "paper", (64, 32)),
+                                                 ("deepfm", "sgd", (48,)), ("wd", "paper", (64, 32, 16))])
+def test_training_steps_match_oracle_chain(oracle, des, kind, setting, hidden):
     """Three training steps of the whole model on a shrunken Criteo-shaped workload, library calls
     against the oracle's functions chained in the same order.  Each step is compared from a common
     state: after the comparison the library's weights are overwritten with the oracle's, so the
@@ -127,7 +128,7 @@ def test_training_steps_match_oracle_chain(oracle, des, kind, setting):
     from paper_1909_04823_amd.model import Model
     w = synth.workload(1, scale=1 / 16)
     opt_sparse, opt_dense, state_arrays = SETTINGS[setting]
-    tower = synth.tower_init(w.seed, w.F, w.D, hidden=(64, 32))
+    tower = synth.tower_init(w.seed, w.F, w.D, hidden=hidden)
     keys0 = synth.preinsert_keys(w)
     vals0 = synth.host_values(w, keys0.shape[0])
     ot = oracle.Table(w.D, w.capacity, seed=w.seed, init_scale=w.init_std)

@@ -620,8 +620,9 @@ def test_dense_update_closed_forms(oracle):
     assert m.tolist() == (0.5 * g).tolist() and v.tolist() == (0.25 * g * g).tolist()
 
 
-@pytest.mark.parametrize("kind", ["lr", "fm", "wd", "deepfm"])
-def test_whole_model_gradients_match_finite_differences(oracle, kind):
+@pytest.mark.parametrize("kind,hidden", [("lr", (8, 4)), ("fm", (8, 4)), ("wd", (8, 4)), ("deepfm", (8, 4)),
+                                         ("deepfm", (8,)), ("wd", (8, 4, 4))])
+def test_whole_model_gradients_match_finite_differences(oracle, kind, hidden):
     """The chained step (sparse operators -> first layer under DES -> tower -> output unit -> loss and
     all the way back) against central differences of its own loss: every dense parameter class and the
     merged sparse gradient, i.e. the glue between the stages (g_lr = g_fm = dL/dlogit, g_pool = dZ1 W1^T, ...)."""
@@ -631,8 +632,8 @@ def test_whole_model_gradients_match_finite_differences(oracle, kind):
     vocab, keys, offsets, vals = random_batch(rng, B, F, 3, 12, with_vals=True, min_len=1)
     t = make_table(oracle, rng, vocab, D, scale=0.5)
     batch = synth.Batch(B, F, keys, offsets, vals)
-    tower = synth.tower_init(5, F, D, hidden=(8, 4))
-    for k in ("b1", "b2"):
+    tower = synth.tower_init(5, F, D, hidden=hidden)
+    for k in [k for k in tower if k[0] == "b" and k != "b0"]:
         tower[k] = (0.3 * rng.standard_normal(tower[k].shape)).astype(np.float32)     # units on both sides of 0
     labels = (rng.random(B) < 0.5).astype(np.float32)
     m = OracleModel(oracle, t, F, K, kind, tower, dict(opt_emb=0, opt_w=0), dict(opt_emb=0))
