@@ -144,6 +144,9 @@ def main():
                          "(the placement of the paper's Section 5)")
     ap.add_argument("--step-series", action="store_true",
                     help="also report every timed step's duration (events on the main stream) under \"series_ms\"")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the step of every distinct batch into a HIP graph and time replays (not for the "
+                         "streaming workload, whose every step has a new batch)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="run the whole step on one stream (default: the backward pass's sort runs on a second "
                          "stream beside the forward pass)")
@@ -298,12 +301,13 @@ def run_workload(args, index, cpu):
     # the row-sorting half of the backward pass needs only the rows, so it runs on a second stream
     # (default priority) beside the forward pass; events order find -> sort -> update
     main, aux = torch.cuda.current_stream(), torch.cuda.Stream()
-    ev_found, ev_sorted = torch.cuda.Event(), torch.cuda.Event()
     overlap = [not args.no_overlap]      # the per-kernel pass below switches it off: concurrent kernels stretch each other
 
     def step(i):
         b = batches[i % len(batches)]
         r = rows[:b.nnz]
+        main = torch.cuda.current_stream()               # the capture stream while a graph is being recorded
+        ev_found, ev_sorted = torch.cuda.Event(), torch.cuda.Event()
         table.find(b.keys, miss, r)
         if overlap[0]:
             ev_found.record(main)
@@ -337,13 +341,31 @@ def run_workload(args, index, cpu):
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    graphs = None
+    if args.graph and not streaming:
+        # one HIP graph per distinct batch: the whole step (both streams) is recorded once and replayed, which
+        # takes the ~30 launches and the Python calls off the critical path of the small workloads
+        graphs = []
+        for bi in range(len(batches)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(bi)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+    def run(i):
+        if graphs is None:
+            return step(i)
+        graphs[i % len(batches)].replay()
+        return batches[i % len(batches)].nnz
+
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)] if args.step_series else None
     t0 = time.perf_counter()
     lookups = 0
     for i in range(args.warmup, total_steps):
         if marks:
             marks[i - args.warmup].record(main)
-        lookups += step(i)
+        lookups += run(i)
     if marks:
         marks[-1].record(main)
     torch.cuda.synchronize()
@@ -417,7 +439,8 @@ def run_workload(args, index, cpu):
                    "B": B, "F": F, "D": D, "K": K, "optimizer": w.opt, "nnz_per_step": lookups / args.steps,
                    "table_rows": rows_before, "table_rows_after": table.size(), "distinct_batches": len(batches),
                    "find_policy": "insert" if miss == des.MISS_INSERT else "lookup", "setup_s": round(setup_s, 1),
-                   "streams": 1 if args.no_overlap else 2, "shard_policy": args.policy},
+                   "streams": 1 if args.no_overlap else 2, "shard_policy": args.policy,
+                   "hip_graph": bool(graphs)},
         "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
     if series is not None:

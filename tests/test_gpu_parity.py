@@ -407,3 +407,74 @@ def test_batch_validate(des):
         assert t.validate(gb, bad_rows) == nb + 1 + 500
     finally:
         t.close()
+
+
+def test_step_captured_in_a_hip_graph_replays_like_eager(oracle, des):
+    """One whole step (find with insertion, fused forward, aggregation, the backward's sort on a second
+    stream, the update) captured once into a HIP graph and replayed: after every replay, with eager work
+    and synchronisation between the replays, the table equals that of the same steps run eagerly."""
+    import torch
+    w = synth.workload(1, scale=1 / 16)
+    batch = synth.gen_batch(w, 0)
+    keys0 = synth.preinsert_keys(w)
+    vals0 = synth.host_values(w, keys0.shape[0])
+    g_lr, g_fm, g_pool = (dev(a, torch) for a in synth.upstream_gradients(w, 0))
+    B, F, D, K = w.B, w.F, w.D, w.K
+
+    def make():
+        t = des.Table(D, w.capacity, num_shards=K, opt=des.OPT_ADAGRAD, init_seed=w.seed, init_scale=w.init_std,
+                      max_n=1 << 17)
+        t.insert(dev(keys0, torch), dev(vals0, torch))
+        f = lambda *s: torch.zeros(s, dtype=torch.float32, device="cuda")
+        buf = dict(rows=torch.empty(batch.nnz, dtype=torch.int32, device="cuda"), P_lr=f(K, B), P_sum=f(K, B, D),
+                   P_sq=f(K, B), pool=f(B, F, D), A_lr=f(B), A_sum=f(B, D), A_sq=f(B), fm2=f(B))
+        return t, buf
+
+    gb = des.Batch.from_numpy(batch)
+    aux = torch.cuda.Stream()
+
+    def step(t, b):
+        main = torch.cuda.current_stream()
+        found, sorted_ = torch.cuda.Event(), torch.cuda.Event()
+        t.find(gb.keys, des.MISS_INSERT, b["rows"])
+        found.record(main)
+        aux.wait_event(found)
+        with torch.cuda.stream(aux):
+            t.backward_prepare(gb, b["rows"])
+            sorted_.record(aux)
+        t.partial_forward(gb, b["rows"], b["P_lr"], b["P_sum"], b["P_sq"], b["pool"])
+        des.aggregate_partials(b["P_lr"], b["A_lr"])
+        des.aggregate_partials(b["P_sum"], b["A_sum"])
+        des.aggregate_partials(b["P_sq"], b["A_sq"])
+        des.fm_finalize(b["A_sum"], b["A_sq"], b["fm2"])
+        main.wait_event(sorted_)
+        t.backward_update_adagrad(gb, b["rows"], w.lr, 1e-8, g_lr, g_fm, b["A_sum"], g_pool)
+
+    te, be = make()
+    tg, bg = make()
+    try:
+        step(tg, bg)                                      # warm-up outside the capture (lazy initialisation)
+        step(te, be)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(tg, bg)
+        torch.cuda.synchronize()
+        step(te, be)                                      # the capture itself does not execute: eager does step 2 ...
+        graph.replay()                                    # ... and the first replay is the graph side's step 2
+        for it in range(4):
+            torch.cuda.synchronize()
+            n = te.size()
+            assert tg.size() == n and tg.status() == 0 and te.status() == 0
+            assert torch.equal(bg["rows"], be["rows"])
+            assert torch.equal(tg.row_keys[:n], te.row_keys[:n])
+            for name in ("emb", "w", "acc_emb", "acc_w"):
+                assert_close(getattr(tg, name)[:n].cpu().numpy(), getattr(te, name)[:n].cpu().numpy(), f"replay {it} {name}")
+            assert_close(bg["fm2"].cpu().numpy(), be["fm2"].cpu().numpy(), f"replay {it} fm2")
+            assert_close(bg["pool"].cpu().numpy(), be["pool"].cpu().numpy(), f"replay {it} pool")
+            # eager work between the replays
+            _ = (bg["pool"] * 2).sum().item()
+            step(te, be)
+            graph.replay()
+    finally:
+        tg.close(); te.close()
