@@ -3,7 +3,7 @@
 
 A step is one pass of the whole hot path over one synthetic batch that is already resident in
 HBM: des_table_find (inserting unseen IDs where the workload grows) -> des_partial_forward
-(LR, FM, pooled partials of all K shards) -> des_aggregate_partials x3 + des_fm_finalize ->
+(LR, FM, pooled partials of all K shards) -> des_aggregate_forward (the three aggregations + fm2) ->
 des_backward_update_{adagrad,sgd} (sort by row, duplicate merge, fused row update).  Upstream
 gradients are seeded random tensors of the real shapes (the loss head is outside the path).
 
@@ -316,10 +316,7 @@ def run_workload(args, index, cpu):
                 table.backward_prepare(b, r)
                 ev_sorted.record(aux)
         table.partial_forward(b, r, P_lr, P_sum, P_sq, pool)
-        des.aggregate_partials(P_lr, A_lr)
-        des.aggregate_partials(P_sum, A_sum)
-        des.aggregate_partials(P_sq, A_sq)
-        des.fm_finalize(A_sum, A_sq, fm2)
+        des.aggregate_forward(P_lr, P_sum, P_sq, A_lr, A_sum, A_sq, fm2)     # the three aggregations and F in one launch
         dbg = {"n_uniq": n_uniq}
         if overlap[0]:
             main.wait_event(ev_sorted)

@@ -178,6 +178,14 @@ des_status_t des_partial_forward(des_table_t *t, const des_batch_t *batch, const
  * P device [K,n], out device [n]. */
 des_status_t des_aggregate_partials(const float *P, int32_t K, int64_t n, float *out, void *stream);
 
+/* The aggregations of one forward pass and the FM substitution operator in a single launch:
+ * A_lr[B], A_sum[B,D], A_sq[B] = sums over the K shards of P_lr[K,B], P_sum[K,B,D], P_sq[K,B] (Eq. (1)) and
+ * fm2[B] as below, formed from the double sums before they are rounded.  The LR group (P_lr, A_lr) or the
+ * FM group (P_sum, P_sq, A_sum, A_sq, optional fm2) may be null, not both.  Same results as the separate
+ * calls up to the last bit of fm2.  D a multiple of 4; P_sum and A_sum 16-byte aligned. */
+des_status_t des_aggregate_forward(const float *P_lr, const float *P_sum, const float *P_sq, int32_t K, int64_t B,
+                                   int32_t D, float *A_lr, float *A_sum, float *A_sq, float *fm2, void *stream);
+
 /* Substitution operator of FM order 2, Eq. (des_fm2): fm2[b] = (<A_sum[b],A_sum[b]> - A_sq[b])/2. */
 des_status_t des_fm_finalize(const float *A_sum, const float *A_sq, int64_t B, int32_t D,
                              float *fm2, void *stream);

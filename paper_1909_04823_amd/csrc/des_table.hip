@@ -329,6 +329,46 @@ __global__ __launch_bounds__(kBlock) void k_fm_finalize(const float *__restrict_
   if (b < B && sub == 0) fm2[b] = (float)(0.5 * (q - (double)A_sq[b]));
 }
 
+// The three aggregations of one forward pass and the FM substitution operator in one launch: eight lanes
+// per sample sum the K shards' partials of their columns in double, square the sums for fm2 before they
+// are rounded, and lane 0 adds the two scalars.  Any of the LR and FM groups may be absent.
+__global__ __launch_bounds__(kBlock) void k_aggregate_forward(const float *__restrict__ P_lr,
+                                                               const float *__restrict__ P_sum,
+                                                               const float *__restrict__ P_sq, int K, int64_t B, int D,
+                                                               float *__restrict__ A_lr, float *__restrict__ A_sum,
+                                                               float *__restrict__ A_sq, float *__restrict__ fm2) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t b = gid / 8;
+  const int sub = (int)(gid % 8);
+  double q = 0.0;
+  if (b < B && P_sum)
+    for (int d4 = sub; d4 < D / 4; d4 += 8) {
+      double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+      for (int s = 0; s < K; ++s) {
+        const float4 p = *reinterpret_cast<const float4 *>(P_sum + ((int64_t)s * B + b) * D + d4 * 4);
+        a0 += (double)p.x; a1 += (double)p.y; a2 += (double)p.z; a3 += (double)p.w;
+      }
+      *reinterpret_cast<float4 *>(A_sum + b * D + d4 * 4) = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
+      q += a0 * a0 + a1 * a1 + a2 * a2 + a3 * a3;
+    }
+  q += __shfl_xor(q, 1, 8);
+  q += __shfl_xor(q, 2, 8);
+  q += __shfl_xor(q, 4, 8);
+  if (b < B && sub == 0) {
+    if (P_sum) {
+      double sq = 0.0;
+      for (int s = 0; s < K; ++s) sq += (double)P_sq[(int64_t)s * B + b];
+      A_sq[b] = (float)sq;
+      if (fm2) fm2[b] = (float)(0.5 * (q - sq));
+    }
+    if (P_lr) {
+      double l = 0.0;
+      for (int s = 0; s < K; ++s) l += (double)P_lr[(int64_t)s * B + b];
+      A_lr[b] = (float)l;
+    }
+  }
+}
+
 inline unsigned grid_for(int64_t n, int per_block = kBlock, int64_t cap = 1 << 20) {
   int64_t g = (n + per_block - 1) / per_block;
   if (g < 1) g = 1;
@@ -599,6 +639,20 @@ des_status_t des_aggregate_partials(const float *P, int32_t K, int64_t n, float 
     hipLaunchKernelGGL(k_aggregate<true>, dim3(grid_for(n / 4)), dim3(kBlock), 0, s, P, K, n, out);
   else
     hipLaunchKernelGGL(k_aggregate<false>, dim3(grid_for(n)), dim3(kBlock), 0, s, P, K, n, out);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+des_status_t des_aggregate_forward(const float *P_lr, const float *P_sum, const float *P_sq, int32_t K, int64_t B,
+                                   int32_t D, float *A_lr, float *A_sum, float *A_sq, float *fm2, void *stream) {
+  if (K < 1 || B < 0 || D < 4 || (D & 3)) return DES_ERR_INVALID_ARG;
+  if ((P_sum == nullptr) != (P_sq == nullptr) || (!P_lr && !P_sum)) return DES_ERR_INVALID_ARG;
+  if (B == 0) return DES_OK;
+  if ((P_lr && !A_lr) || (P_sum && (!A_sum || !A_sq))) return DES_ERR_INVALID_ARG;
+  if (P_sum && (!aligned16(P_sum) || !aligned16(A_sum))) return DES_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope ps(KID_AGGREGATE, s);
+  hipLaunchKernelGGL(k_aggregate_forward, dim3(grid_for(B * 8, kBlock, 1ll << 30)), dim3(kBlock), 0, s, P_lr, P_sum, P_sq,
+                     K, B, D, A_lr, A_sum, A_sq, fm2);
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
 }
 

@@ -25,7 +25,7 @@ MISS_ZERO, MISS_INSERT = 0, 1
 EXPORTS = [
     "des_table_query_bytes", "des_table_create", "des_table_destroy", "des_table_insert", "des_table_find",
     "des_table_size", "des_table_status", "des_partial_forward_lr", "des_partial_forward_fm",
-    "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_fm_finalize",
+    "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_aggregate_forward", "des_fm_finalize",
     "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge", "des_backward_prepare",
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
     "des_batch_validate", "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
@@ -80,6 +80,7 @@ _sig = {
     "des_partial_forward": [vp, C.POINTER(BatchDesc), vp, vp, vp, vp, vp, vp],
     "des_aggregate_partials": [vp, i32, i64, vp, vp],
     "des_fm_finalize": [vp, vp, i64, i32, vp, vp],
+    "des_aggregate_forward": [vp, vp, vp, i32, i64, i32, vp, vp, vp, vp, vp],
     "des_backward_update_sgd": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), f32, vp],
     "des_backward_update_adagrad": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), f32, f32, vp],
     "des_backward_update": [vp, C.POINTER(BatchDesc), vp, C.POINTER(BackwardIO), C.POINTER(Optimizer), vp],
@@ -328,6 +329,15 @@ def aggregate_partials(P: torch.Tensor, out: Optional[torch.Tensor] = None) -> t
         out = torch.empty(P.shape[1:], dtype=torch.float32, device=P.device)
     _check(_lib.des_aggregate_partials(_ptr(P), K, n, _ptr(out), _stream()), "des_aggregate_partials")
     return out
+
+
+def aggregate_forward(P_lr, P_sum, P_sq, A_lr=None, A_sum=None, A_sq=None, fm2=None):
+    """All aggregations of one forward pass and fm2 in one launch (des_aggregate_forward)."""
+    ref = P_sum if P_sum is not None else P_lr
+    K, B = ref.shape[0], ref.shape[1]
+    D = P_sum.shape[2] if P_sum is not None else 4
+    _check(_lib.des_aggregate_forward(_ptr(P_lr), _ptr(P_sum), _ptr(P_sq), K, B, D, _ptr(A_lr), _ptr(A_sum), _ptr(A_sq),
+                                      _ptr(fm2), _stream()), "des_aggregate_forward")
 
 
 def fm_finalize(A_sum: torch.Tensor, A_sq: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

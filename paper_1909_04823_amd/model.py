@@ -76,11 +76,10 @@ class Model:
         fm = "fm" in self.parts
         self.t.partial_forward(batch, rows, self.P_lr, self.P_sum if fm else None, self.P_sq if fm else None,
                                self.pool if self.dnn else None)
-        des.aggregate_partials(self.P_lr, self.A_lr)
         if fm:
-            des.aggregate_partials(self.P_sum, self.A_sum)
-            des.aggregate_partials(self.P_sq, self.A_sq)
-            des.fm_finalize(self.A_sum, self.A_sq, self.fm2)
+            des.aggregate_forward(self.P_lr, self.P_sum, self.P_sq, self.A_lr, self.A_sum, self.A_sq, self.fm2)
+        else:
+            des.aggregate_forward(self.P_lr, None, None, self.A_lr)
         if self.dnn:
             x = self.pool                                   # [B, F, D]: the first layer is cut over the fields
             for i in range(self.n_layers):

@@ -132,6 +132,12 @@ class Pair:
         assert_close(gA_sum.cpu().numpy(), A_sum, "A_sum")
         assert_close(gA_sq.cpu().numpy(), A_sq, "A_sq")
         assert_close(g_fm2.cpu().numpy(), fm2, "fm2")
+        # the same four results from the single fused launch
+        fA_lr, fA_sum, fA_sq, f_fm2 = z(B), z(B, D), z(B), z(B)
+        d.aggregate_forward(P_lr, P_sum, P_sq, fA_lr, fA_sum, fA_sq, f_fm2)
+        torch.cuda.synchronize()
+        assert torch.equal(fA_lr, gA_lr) and torch.equal(fA_sum, gA_sum) and torch.equal(fA_sq, gA_sq)
+        assert_close(f_fm2.cpu().numpy(), fm2, "fm2 (fused aggregation)")
         if dense_pool:
             Pp = z(K, B, F, D)
             self.gt.partial_forward_pool(self.gb, self.rows_g, Pp, dense_k=True)
