@@ -65,3 +65,16 @@ def test_host_side_validation_needs_no_device(lib):
     lib.des_table_create.argtypes = [C.POINTER(TableConfig), C.POINTER(C.c_void_p)]
     assert lib.des_table_create(C.byref(cfg), C.byref(out)) == ERR_INVALID_ARG   # null buffers
     assert not out.value
+
+
+def test_header_is_plain_c_and_cxx(tmp_path):
+    """include/des.h compiles on its own as C99 and as C++17 (no torch, no HIP types in the signatures)."""
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    c = tmp_path / "use.c"
+    c.write_text('#include "des.h"\nint main(void) { des_table_config_t c; des_optimizer_t o; (void)c; (void)o; '
+                 'return (int)sizeof(des_batch_t) == 0; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(c)])
+    cpp = tmp_path / "use.cpp"
+    cpp.write_text(c.read_text())
+    subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)])
