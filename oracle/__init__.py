@@ -70,6 +70,11 @@ def lib():
         L.oracle_dnn_partial_forward.argtypes = [vp, vp, i64, i32, C.c_int, C.c_int, C.c_int, vp]
         L.oracle_dnn_backward.restype = None
         L.oracle_dnn_backward.argtypes = [vp, vp, vp, i64, i32, C.c_int, C.c_int, vp, vp]
+        L.oracle_cross_partial.restype = None
+        L.oracle_cross_partial.argtypes = [vp, vp, i64, i32, C.c_int, C.c_int, vp]
+        L.oracle_cross_apply.restype = None; L.oracle_cross_apply.argtypes = [vp, vp, vp, vp, i64, i64, vp]
+        L.oracle_cross_backward.restype = None
+        L.oracle_cross_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp]
         L.oracle_bias_act.restype = None; L.oracle_bias_act.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp]
         L.oracle_bias_act_backward.restype = None
         L.oracle_bias_act_backward.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, vp]
@@ -274,6 +279,45 @@ def dnn_backward(pool: np.ndarray, W: np.ndarray, dY: np.ndarray, want_g_pool: b
     dW = np.empty((F * D, H), np.float64) if want_dW else None
     lib().oracle_dnn_backward(_p(pool), _p(W), _p(dY), B, F, D, H, _p(g_pool), _p(dW))
     return g_pool, dW
+
+
+def cross_partial(xl: np.ndarray, w: np.ndarray, K: int) -> np.ndarray:
+    """Per-shard scalars P[K,B] (float64) of a DCN cross layer: xl is [B,F,D] fp32, w is [F*D] fp32, the
+    columns of field f belong to shard f mod K."""
+    xl, w = _c(xl, np.float32), _c(w, np.float32)
+    B, F, D = xl.shape
+    if w.shape != (F * D,):
+        raise ValueError("w must be [F*D]")
+    out = np.empty((K, B), np.float64)
+    lib().oracle_cross_partial(_p(xl), _p(w), B, F, D, K, _p(out))
+    return out
+
+
+def cross_apply(x0: np.ndarray, xl: np.ndarray, s: np.ndarray, bias: np.ndarray) -> np.ndarray:
+    """y[B,d] = x0 * s[:,None] + bias + xl in float64; s is the aggregated scalar per sample (fp32)."""
+    x0, xl, s, bias = _c(x0, np.float32), _c(xl, np.float32), _c(s, np.float32), _c(bias, np.float32)
+    B = x0.shape[0]
+    d = x0.size // max(B, 1)
+    if xl.shape != x0.shape or s.shape != (B,) or bias.shape != (d,):
+        raise ValueError("shape mismatch")
+    y = np.empty(x0.shape, np.float64)
+    lib().oracle_cross_apply(_p(x0), _p(xl), _p(s), _p(bias), B, d, _p(y))
+    return y
+
+
+def cross_backward(x0: np.ndarray, xl: np.ndarray, w: np.ndarray, s: np.ndarray, g_y: np.ndarray):
+    """(g_s[B], g_xl, g_x0, dw[d], db[d]) in float64 for the upstream gradient g_y of the layer's output;
+    g_x0 is this layer's share of the gradient of x0."""
+    x0, xl, w, s, g_y = (_c(a, np.float32) for a in (x0, xl, w, s, g_y))
+    B = x0.shape[0]
+    d = w.shape[0]
+    if xl.shape != x0.shape or g_y.shape != x0.shape or x0.size != B * d or s.shape != (B,):
+        raise ValueError("shape mismatch")
+    g_s = np.empty(B, np.float64)
+    g_xl, g_x0 = np.empty(x0.shape, np.float64), np.empty(x0.shape, np.float64)
+    dw, db = np.empty(d, np.float64), np.empty(d, np.float64)
+    lib().oracle_cross_backward(_p(x0), _p(xl), _p(w), _p(s), _p(g_y), B, d, _p(g_s), _p(g_xl), _p(g_x0), _p(dw), _p(db))
+    return g_s, g_xl, g_x0, dw, db
 
 
 def bias_act(Z: np.ndarray, bias: Optional[np.ndarray], relu: bool) -> np.ndarray:

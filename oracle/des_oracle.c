@@ -428,6 +428,56 @@ void oracle_dnn_backward(const float *pool, const float *W, const float *dY, int
       }
 }
 
+/* ------------------------------------------------------------------ DCN cross layer ------ */
+
+/* Section 4, "DCN" paragraph (with the cross layer of the DCN paper it cites, its Section 2.2):
+ *   x_{l+1} = x_0 (x_l^T w_l) + b_l + x_l,
+ * all vectors of length d = F*D, x_0 the concatenated embedding output.  Under DES w_l is cut along d and
+ * every process forms the dot product over its own part first, a scalar per sample; the aggregation sums
+ * the scalars and the rest follows:  y = x_0 * (+)(x_local^T w_local) + b + x.
+ * Columns are placed like the fields they belong to (f mod K, Section 5): column j = f*D + c goes with f.
+ * P[s][b] = sum over the columns j of shard s of xl[b][j] * w[j]. */
+void oracle_cross_partial(const float *xl, const float *w, int64_t B, int32_t F, int D, int K, double *P) {
+  memset(P, 0, sizeof(double) * (size_t)K * (size_t)B);
+  for (int64_t b = 0; b < B; ++b)
+    for (int32_t f = 0; f < F; ++f)
+      for (int c = 0; c < D; ++c) {
+        const int64_t j = (int64_t)f * D + c;
+        P[(int64_t)(f % K) * B + b] += (double)xl[b * (int64_t)F * D + j] * (double)w[j];
+      }
+}
+
+/* y[b][j] = x0[b][j] * s[b] + bias[j] + xl[b][j], s the aggregated scalar. */
+void oracle_cross_apply(const float *x0, const float *xl, const float *s, const float *bias, int64_t B, int64_t d,
+                        double *y) {
+  for (int64_t b = 0; b < B; ++b)
+    for (int64_t j = 0; j < d; ++j)
+      y[b * d + j] = (double)x0[b * d + j] * (double)s[b] + (double)bias[j] + (double)xl[b * d + j];
+}
+
+/* Backward of one cross layer for the upstream gradient g_y[B][d] (Section 3.2.2: the gradient of the
+ * aggregate reaches every sub-operator unchanged).  With s[b] = xl[b]^T w:
+ *   g_s[b]     = sum_j g_y[b][j] x0[b][j]            (gradient of the aggregated scalar)
+ *   g_xl[b][j] = g_y[b][j] + g_s[b] w[j]             (identity path + the sub-operators)
+ *   g_x0[b][j] = g_y[b][j] s[b]                      (this layer's share; x_0 feeds every layer)
+ *   dw[j] = sum_b g_s[b] xl[b][j],   db[j] = sum_b g_y[b][j]. */
+void oracle_cross_backward(const float *x0, const float *xl, const float *w, const float *s, const float *g_y,
+                           int64_t B, int64_t d, double *g_s, double *g_xl, double *g_x0, double *dw, double *db) {
+  for (int64_t j = 0; j < d; ++j) { dw[j] = 0.0; db[j] = 0.0; }
+  for (int64_t b = 0; b < B; ++b) {
+    double gs = 0.0;
+    for (int64_t j = 0; j < d; ++j) gs += (double)g_y[b * d + j] * (double)x0[b * d + j];
+    g_s[b] = gs;
+    for (int64_t j = 0; j < d; ++j) {
+      const double g = (double)g_y[b * d + j];
+      g_xl[b * d + j] = g + gs * (double)w[j];
+      g_x0[b * d + j] = g * (double)s[b];
+      dw[j] += gs * (double)xl[b * d + j];
+      db[j] += g;
+    }
+  }
+}
+
 /* ------------------------------------------------------------------ dense tower and output unit ----
  * What follows the aggregated weights-rich operators (Section 3.2.1: the layers after them see the
  * same aggregated result on every process; Section 4, Table "common components": LR = first order,

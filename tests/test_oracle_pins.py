@@ -292,6 +292,108 @@ def test_dnn_partial_size_reproduces_printed_comm_saving_column(oracle):
         assert abs(got - float(r)) < 1.5e-3, (B, got, r)
 
 
+# --------------------------------------------------------------------------- DCN cross layer ---
+def test_cross_layer_is_the_outer_product_form_regrouped(oracle):
+    """The cross layer is defined as x0 (xl^T w) + b + xl = (x0 xl^T) w + b + xl.  DES regroups it so that the
+    dot product comes first and is split over the shards; the pin builds the d x d matrix x0 xl^T explicitly
+    and multiplies it by w (numpy float64), which the oracle's shard-wise route never forms."""
+    x = np.array([[[1.0, 2.0], [3.0, 4.0]]], np.float32)            # B=1, F=2, D=2
+    w = np.array([1.0, 10.0, 100.0, 1000.0], np.float32)
+    assert oracle.cross_partial(x, w, 2).tolist() == [[21.0], [4300.0]]      # field 0 -> shard 0, field 1 -> shard 1
+    assert oracle.cross_partial(x, w, 1).tolist() == [[4321.0]]
+    assert oracle.cross_partial(x, w, 3).tolist() == [[21.0], [4300.0], [0.0]]
+    rng = np.random.default_rng(21)
+    B, F, D = 4, 5, 4
+    d = F * D
+    x0 = rng.standard_normal((B, F, D)).astype(np.float32)
+    xl = rng.standard_normal((B, F, D)).astype(np.float32)
+    w = rng.standard_normal(d).astype(np.float32)
+    bias = rng.standard_normal(d).astype(np.float32)
+    for K in (1, 2, 3, 7):
+        P = oracle.cross_partial(xl, w, K)
+        for s in range(K):
+            cols = np.concatenate([np.arange(f * D, (f + 1) * D) for f in range(F) if f % K == s] or [np.arange(0)]).astype(int)
+            np.testing.assert_allclose(P[s], xl.reshape(B, d)[:, cols].astype(np.float64) @ w[cols].astype(np.float64),
+                                       rtol=1e-13, atol=1e-13)
+        s32 = oracle.aggregate(P).astype(np.float32)
+        y = oracle.cross_apply(x0, xl, s32, bias).reshape(B, d)
+        for b in range(B):
+            outer = np.outer(x0[b].ravel().astype(np.float64), xl[b].ravel().astype(np.float64))     # [d, d]
+            ref = outer @ w.astype(np.float64) + bias + xl[b].ravel()
+            np.testing.assert_allclose(y[b], ref, rtol=2e-6, atol=2e-6)       # s was rounded to fp32 once
+
+
+def test_cross_backward_matches_exact_differences(oracle):
+    """With L = <c, y> and small-integer inputs every sum is exact.  L is linear in b, in x0 and in w, so a unit
+    step in one element changes L by exactly its gradient; in xl it is linear too (s is linear in xl)."""
+    rng = np.random.default_rng(22)
+    B, F, D, K = 3, 3, 4, 2
+    d = F * D
+    ints = lambda *shape: rng.integers(-3, 4, shape).astype(np.float32)
+    x0, xl, w, bias, c = ints(B, F, D), ints(B, F, D), ints(d), ints(d), ints(B, F, D)
+
+    def L(x0_, xl_, w_, b_):
+        s = oracle.aggregate(oracle.cross_partial(xl_, w_, K)).astype(np.float32)
+        return float((oracle.cross_apply(x0_, xl_, s, b_) * c).sum())
+
+    s = oracle.aggregate(oracle.cross_partial(xl, w, K)).astype(np.float32)
+    g_s, g_xl, g_x0, dw, db = oracle.cross_backward(x0, xl, w, s, c)
+    L0 = L(x0, xl, w, bias)
+    np.testing.assert_array_equal(g_s, (c.reshape(B, d).astype(np.float64) * x0.reshape(B, d)).sum(axis=1))
+    for idx in np.ndindex(B, F, D):
+        a = x0.copy(); a[idx] += 1
+        assert L(a, xl, w, bias) - L0 == g_x0[idx]
+        a = xl.copy(); a[idx] += 1
+        assert L(x0, a, w, bias) - L0 == g_xl[idx]
+    for j in range(d):
+        a = w.copy(); a[j] += 1
+        assert L(x0, xl, a, bias) - L0 == dw[j]
+        a = bias.copy(); a[j] += 1
+        assert L(x0, xl, w, a) - L0 == db[j]
+
+
+def test_stacked_cross_layers_backward_by_finite_differences(oracle):
+    """Three stacked layers share x0: the gradient of x0 is the sum of every layer's share plus what flows
+    back through the chain to layer 0's input.  Central differences of the oracle's own forward."""
+    rng = np.random.default_rng(23)
+    B, F, D, K, n_layers = 2, 3, 4, 2, 3
+    d = F * D
+    x0 = (0.5 * rng.standard_normal((B, F, D))).astype(np.float32)
+    ws = [(0.5 * rng.standard_normal(d)).astype(np.float32) for _ in range(n_layers)]
+    bs = [(0.1 * rng.standard_normal(d)).astype(np.float32) for _ in range(n_layers)]
+    c = rng.standard_normal((B, F, D))
+
+    def forward(x0_):
+        xs, ss = [x0_], []
+        for l in range(n_layers):
+            s = oracle.aggregate(oracle.cross_partial(xs[-1], ws[l], K)).astype(np.float32)
+            ss.append(s)
+            xs.append(oracle.cross_apply(x0_, xs[-1], s, bs[l]).astype(np.float32).reshape(B, F, D))
+        return xs, ss
+
+    def L64(x0_):       # the same chain kept in float64 between layers, for clean differences
+        x0d = x0_.astype(np.float64).reshape(B, d)
+        x = x0d
+        for l in range(n_layers):
+            x = x0d * (x @ ws[l].astype(np.float64))[:, None] + bs[l] + x
+        return float((x * c.reshape(B, d)).sum())
+
+    xs, ss = forward(x0)
+    g = c.astype(np.float32)
+    g_x0_total = np.zeros((B, F, D))
+    for l in range(n_layers - 1, -1, -1):
+        _, g_xl, g_x0, _, _ = oracle.cross_backward(x0, xs[l], ws[l], ss[l], g)
+        g_x0_total += g_x0
+        g = g_xl.astype(np.float32)
+    g_x0_total += g                                   # layer 0's input is x0 itself
+    eps = 2.0 ** -10
+    for idx in [(0, 0, 0), (1, 2, 3), (0, 1, 2), (1, 0, 1)]:
+        hi = x0.astype(np.float64).copy(); hi[idx] += eps
+        lo = x0.astype(np.float64).copy(); lo[idx] -= eps
+        fd = (L64(hi) - L64(lo)) / (2 * eps)
+        assert abs(fd - g_x0_total[idx]) <= 1e-4 * max(1.0, abs(fd)), (idx, fd, g_x0_total[idx])
+
+
 # --------------------------------------------------------------------------- backward ------
 def scalar_objective(oracle, t, B, F, keys, offsets, vals, rows, c_lr, c_fm, c_pool):
     P = t.partial_forward(B, F, keys, offsets, rows, 3, 0, vals)
