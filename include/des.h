@@ -282,6 +282,41 @@ des_status_t des_backward_update(des_table_t *t, const des_batch_t *batch, const
 des_status_t des_backward_merge(des_table_t *t, const des_batch_t *batch, const int32_t *rows,
                                 const des_backward_io_t *io, void *stream);
 
+/* ---- DCN cross layer under DES (Section 4, the paragraph on DCN; the layer is the cited DCN paper's
+ *     x_{l+1} = x_0 (x_l^T w_l) + b_l + x_l,      all vectors of length d = F*D,
+ * x_0 the concatenated embedding output [B,F,D] of des_partial_forward_pool).  The paper cuts w_l along
+ * d, lets every process form the dot product over its own part first, a scalar per sample, and sums
+ * the scalars:  y = x_0 * (+)(x_local^T w_local) + b + x.  Columns go with the field they belong to:
+ * column j = f*D + c is held by shard f mod K (Section 5).
+ *
+ * des_cross_partial: the sub-operator.  P[s,b] = sum over the columns j of shard s of xl[b,j] * w[j]
+ * (double sum in a fixed order, rounded once).  xl [B,F,D], w [F*D], P [K,B] fully overwritten.  The K
+ * scalars of a sample are summed with des_aggregate_partials(P, K, B, s).  K = 1 gives the plain row
+ * dot product xl w.
+ * des_cross_apply: the remaining operator, the same on every process: y[b,j] = x0[b,j] * s[b] + bias[j]
+ * + xl[b,j].  y may alias xl.
+ * All pointers: device, 16-byte aligned, row-major, owned by the caller.  D and d multiples of 4,
+ * F*D <= 2^30, K >= 1, else DES_ERR_INVALID_ARG.  B == 0 is a no-op. */
+des_status_t des_cross_partial(const float *xl, const float *w, int64_t B, int32_t F, int32_t D, int32_t K, float *P,
+                               void *stream);
+des_status_t des_cross_apply(const float *x0, const float *xl, const float *s, const float *bias, int64_t B,
+                             int64_t d, float *y, void *stream);
+
+/* Backward of one cross layer for the gradient g_y[B,d] of its output (Section 3.2.2: the gradient of
+ * the aggregated scalar reaches every sub-operator unchanged).  With s the aggregated scalar of the
+ * forward pass and g_s[b] = <g_y[b,:], x0[b,:]>:
+ *     g_xl[b,j] = g_y[b,j] + g_s[b] w[j]           dw[j] = sum_b g_s[b] xl[b,j]
+ *     g_x0[b,j] (+)= g_y[b,j] s[b]                 db[j] = sum_b g_y[b,j]
+ * x_0 feeds every layer, so the layers' shares of its gradient add up: accumulate_g_x0 != 0 adds to
+ * what g_x0 holds, 0 overwrites it.  (The first layer's input is x_0 itself: its g_xl is one more
+ * share, to be added by the caller.)  Sums in double, the batch sums as per-slice partials added in
+ * slice order.  g_xl may alias g_y.  workspace: device, 256-byte aligned, des_cross_backward_bytes(B, d)
+ * bytes, else DES_ERR_WORKSPACE.  B == 0 writes dw = db = 0 and touches nothing else. */
+des_status_t des_cross_backward_bytes(int64_t B, int64_t d, size_t *workspace_bytes);
+des_status_t des_cross_backward(const float *x0, const float *xl, const float *w, const float *s, const float *g_y,
+                                int64_t B, int64_t d, float *g_xl, float *g_x0, int32_t accumulate_g_x0, float *dw,
+                                float *db, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- The dense remainder of a model step --------------------------------------------------------
  * After the aggregated weights-rich operators every process computes the same thing (Section 3.2.1);
  * Section 4's models differ in which components feed the output (LR: first order; FM: + second

@@ -423,7 +423,8 @@ const char *kKernelNames[KID_COUNT] = {
     "backward_segment_heads", "backward_classify", "backward_short_update", "backward_long_partial",
     "backward_long_final", "backward_export", "fill",
     "dnn_forward", "dnn_grad_pool", "dnn_grad_weights",
-    "aggregate_bias_act", "column_partials", "column_final", "output_unit", "dense_update", "table_migrate"};
+    "aggregate_bias_act", "column_partials", "column_final", "output_unit", "dense_update", "table_migrate",
+    "cross_partial", "cross_apply", "cross_backward"};
 }  // namespace
 
 void prof_begin(int kid, hipStream_t s) {

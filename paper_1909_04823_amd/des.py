@@ -30,6 +30,7 @@ EXPORTS = [
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
     "des_batch_validate", "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
     "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
+    "des_cross_partial", "des_cross_apply", "des_cross_backward_bytes", "des_cross_backward",
     "des_profile_enable", "des_profile_read", "des_status_string",
 ]
 
@@ -99,6 +100,10 @@ _sig = {
     "des_table_migrate": [vp, vp, vp, vp, vp, C.POINTER(i64), vp],
     "des_table_mark_seen": [vp, i64, C.c_uint32, vp, vp],
     "des_table_select_recent": [vp, i64, C.c_uint32, vp, vp],
+    "des_cross_partial": [vp, vp, i64, i32, i32, i32, vp, vp],
+    "des_cross_apply": [vp, vp, vp, vp, i64, i64, vp, vp],
+    "des_cross_backward_bytes": [i64, i64, C.POINTER(C.c_size_t)],
+    "des_cross_backward": [vp, vp, vp, vp, vp, i64, i64, vp, vp, i32, vp, vp, vp, C.c_size_t, vp],
     "des_profile_enable": [i32],
     "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
 }
@@ -382,6 +387,55 @@ def dnn_backward(pool: torch.Tensor, W: torch.Tensor, dY: torch.Tensor, g_pool: 
     _check(_lib.des_dnn_backward(_ptr(pool), _ptr(W), _ptr(dY), B, F, D, H, _ptr(g_pool), _ptr(dW),
                                  _ptr(workspace), nbytes, _stream()), "des_dnn_backward")
     return g_pool, dW
+
+
+def cross_partial(xl: torch.Tensor, w: torch.Tensor, K: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Per-shard scalars P[K,B] of a DCN cross layer: xl [B,F,D], w [F*D]; shard of field f is f mod K."""
+    B, F, D = xl.shape
+    if tuple(w.shape) != (F * D,) or not (xl.is_contiguous() and w.is_contiguous()):
+        raise ValueError("xl must be contiguous [B,F,D] and w [F*D]")
+    if out is None:
+        out = torch.empty((K, B), dtype=torch.float32, device=xl.device)
+    _check(_lib.des_cross_partial(_ptr(xl), _ptr(w), B, F, D, K, _ptr(out), _stream()), "des_cross_partial")
+    return out
+
+
+def cross_apply(x0: torch.Tensor, xl: torch.Tensor, s: torch.Tensor, bias: torch.Tensor,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """y = x0 * s[:,None] + bias + xl over rows of length d = x0.numel() / B."""
+    B = x0.shape[0]
+    d = bias.numel()
+    if x0.numel() != B * d or xl.shape != x0.shape or s.numel() != B:
+        raise ValueError("shape mismatch")
+    if out is None:
+        out = torch.empty_like(x0)
+    for t in (x0, xl, s, bias, out):
+        if not t.is_contiguous():
+            raise ValueError("operands must be contiguous")
+    _check(_lib.des_cross_apply(_ptr(x0), _ptr(xl), _ptr(s), _ptr(bias), B, d, _ptr(out), _stream()), "des_cross_apply")
+    return out
+
+
+def cross_backward_bytes(B: int, d: int) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.des_cross_backward_bytes(B, d, C.byref(n)), "des_cross_backward_bytes")
+    return int(n.value)
+
+
+def cross_backward(x0: torch.Tensor, xl: torch.Tensor, w: torch.Tensor, s: torch.Tensor, g_y: torch.Tensor,
+                   g_xl: torch.Tensor, g_x0: torch.Tensor, accumulate_g_x0: bool, dw: torch.Tensor, db: torch.Tensor,
+                   workspace: torch.Tensor):
+    """Gradients of one cross layer into g_xl, g_x0 (added to when `accumulate_g_x0`), dw, db."""
+    B = x0.shape[0]
+    d = w.numel()
+    for t in (x0, xl, g_y, g_xl, g_x0):
+        if t.numel() != B * d or not t.is_contiguous():
+            raise ValueError("row arrays must be contiguous with B*d elements")
+    if s.numel() != B or dw.numel() != d or db.numel() != d:
+        raise ValueError("shape mismatch")
+    _check(_lib.des_cross_backward(_ptr(x0), _ptr(xl), _ptr(w), _ptr(s), _ptr(g_y), B, d, _ptr(g_xl), _ptr(g_x0),
+                                   int(accumulate_g_x0), _ptr(dw), _ptr(db), _ptr(workspace), _nbytes(workspace),
+                                   _stream()), "des_cross_backward")
 
 
 def aggregate_bias_act(P: torch.Tensor, bias: Optional[torch.Tensor], relu: bool,
