@@ -73,6 +73,8 @@ def lib():
         L.oracle_cross_partial.restype = None
         L.oracle_cross_partial.argtypes = [vp, vp, i64, i32, C.c_int, C.c_int, vp]
         L.oracle_cross_apply.restype = None; L.oracle_cross_apply.argtypes = [vp, vp, vp, vp, i64, i64, vp]
+        L.oracle_cross_partial_backward.restype = None
+        L.oracle_cross_partial_backward.argtypes = [vp, vp, vp, i64, i64, vp, vp]
         L.oracle_cross_backward.restype = None
         L.oracle_cross_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp]
         L.oracle_bias_act.restype = None; L.oracle_bias_act.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp]
@@ -291,6 +293,17 @@ def cross_partial(xl: np.ndarray, w: np.ndarray, K: int) -> np.ndarray:
     out = np.empty((K, B), np.float64)
     lib().oracle_cross_partial(_p(xl), _p(w), B, F, D, K, _p(out))
     return out
+
+
+def cross_partial_backward(xl: np.ndarray, w: np.ndarray, g_s: np.ndarray):
+    """(g_xl, dw[d]) in float64 for a gradient g_s[B] of the aggregated scalar xl w."""
+    xl, w, g_s = _c(xl, np.float32), _c(w, np.float32), _c(g_s, np.float32)
+    B, d = xl.shape[0], w.shape[0]
+    if xl.size != B * d or g_s.shape != (B,):
+        raise ValueError("shape mismatch")
+    g_xl, dw = np.empty(xl.shape, np.float64), np.empty(d, np.float64)
+    lib().oracle_cross_partial_backward(_p(xl), _p(w), _p(g_s), B, d, _p(g_xl), _p(dw))
+    return g_xl, dw
 
 
 def cross_apply(x0: np.ndarray, xl: np.ndarray, s: np.ndarray, bias: np.ndarray) -> np.ndarray:

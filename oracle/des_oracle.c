@@ -447,6 +447,18 @@ void oracle_cross_partial(const float *xl, const float *w, int64_t B, int32_t F,
       }
 }
 
+/* Backward of that sub-operator for a gradient g_s[b] of its aggregated scalar (Section 3.2.2: every shard
+ * receives it unchanged, so over all shards): g_xl[b][j] = g_s[b] w[j], dw[j] = sum_b g_s[b] xl[b][j]. */
+void oracle_cross_partial_backward(const float *xl, const float *w, const float *g_s, int64_t B, int64_t d,
+                                   double *g_xl, double *dw) {
+  for (int64_t j = 0; j < d; ++j) dw[j] = 0.0;
+  for (int64_t b = 0; b < B; ++b)
+    for (int64_t j = 0; j < d; ++j) {
+      g_xl[b * d + j] = (double)g_s[b] * (double)w[j];
+      dw[j] += (double)g_s[b] * (double)xl[b * d + j];
+    }
+}
+
 /* y[b][j] = x0[b][j] * s[b] + bias[j] + xl[b][j], s the aggregated scalar. */
 void oracle_cross_apply(const float *x0, const float *xl, const float *s, const float *bias, int64_t B, int64_t d,
                         double *y) {

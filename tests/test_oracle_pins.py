@@ -352,6 +352,26 @@ def test_cross_backward_matches_exact_differences(oracle):
         assert L(x0, xl, w, a) - L0 == db[j]
 
 
+def test_cross_partial_backward_is_the_adjoint_of_the_sub_operator(oracle):
+    """s = xl w is bilinear: with L = <g_s, s> a unit step in one element of xl or w changes L by exactly that
+    element's gradient (small integers, every sum exact), through the oracle's own sharded forward."""
+    rng = np.random.default_rng(24)
+    B, F, D, K = 4, 3, 4, 2
+    d = F * D
+    xl = rng.integers(-4, 5, (B, F, D)).astype(np.float32)
+    w = rng.integers(-4, 5, d).astype(np.float32)
+    g_s = rng.integers(-4, 5, B).astype(np.float32)
+    L = lambda x_, w_: float(oracle.aggregate(oracle.cross_partial(x_, w_, K)) @ g_s)
+    g_xl, dw = oracle.cross_partial_backward(xl, w, g_s)
+    L0 = L(xl, w)
+    for idx in np.ndindex(B, F, D):
+        a = xl.copy(); a[idx] += 1
+        assert L(a, w) - L0 == g_xl[idx]
+    for j in range(d):
+        a = w.copy(); a[j] += 1
+        assert L(xl, a) - L0 == dw[j]
+
+
 def test_stacked_cross_layers_backward_by_finite_differences(oracle):
     """Three stacked layers share x0: the gradient of x0 is the sum of every layer's share plus what flows
     back through the chain to layer 0's input.  Central differences of the oracle's own forward."""
