@@ -152,6 +152,8 @@ def main():
                          "stream beside the forward pass)")
     ap.add_argument("--tower", type=str, default=None,
                     help="comma-separated hidden widths of the model step's tower (default: dnn-hidden, dnn-hidden/2)")
+    ap.add_argument("--no-cross", action="store_true",
+                    help="skip the DCN cross layer timed at the main workload's shape (reported under \"cross_layer\")")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -177,6 +179,9 @@ def main():
     if args.dnn_hidden > 0:
         torch.cuda.empty_cache()
         out["dnn_layer"] = run_dnn_layer(args, args.config)
+    if not args.no_cross:
+        torch.cuda.empty_cache()
+        out["cross_layer"] = run_cross_layer(args, args.config)
     print(json.dumps(out))
 
 
@@ -232,6 +237,63 @@ def run_dnn_layer(args, index):
     return {"workload": f"configs[{w.index}] {w.name}", "B": B, "F": F, "D": D, "H": H, "K": K, "dtype": "f32",
             "ms_per_pass": round(ms, 4), "flops_per_product": flops, "peak_TFLOPs": FP32_MFMA_PEAK_TFLOPS,
             "kernels": kernels}
+
+
+def run_cross_layer(args, index):
+    """One DCN cross layer under DES at the workload's shape (outside `value`): per-shard dot products, their
+    aggregation, y = x0*s + b + xl, and the backward pass with accumulation into the gradient of x0.
+    Streaming work: algorithmic bytes = every [B,d] array once per kernel that needs it, against the HBM peak."""
+    import torch
+    from paper_1909_04823_amd import des, synth
+    w = synth.workload(index, scale=args.scale)
+    B, F, D, K = w.B, w.F, w.D, w.K
+    d = F * D
+    gen = torch.Generator(device="cuda"); gen.manual_seed(9)
+    x0 = torch.randn((B, F, D), device="cuda", generator=gen) * 0.3
+    xl = torch.randn((B, F, D), device="cuda", generator=gen) * 0.3
+    g_y = torch.randn((B, F, D), device="cuda", generator=gen) * 0.01
+    wl = torch.randn(d, device="cuda", generator=gen) / float(np.sqrt(d))
+    bias = torch.randn(d, device="cuda", generator=gen) * 0.1
+    P, s = torch.empty((K, B), device="cuda"), torch.empty(B, device="cuda")
+    y, g_xl, g_x0 = torch.empty_like(x0), torch.empty_like(x0), torch.zeros_like(x0)
+    dw, db = torch.empty(d, device="cuda"), torch.empty(d, device="cuda")
+    ws = torch.empty(des.cross_backward_bytes(B, d), dtype=torch.uint8, device="cuda")
+
+    def layer():
+        des.cross_partial(xl, wl, K, out=P)
+        des.aggregate_partials(P, s)
+        des.cross_apply(x0, xl, s, bias, out=y)
+        des.cross_backward(x0, xl, wl, s, g_y, g_xl, g_x0, True, dw, db, ws)
+
+    reps = max(3, min(args.steps, 10))
+    for _ in range(2):
+        layer()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        layer()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / reps
+    des.profile_enable(True)
+    for _ in range(reps):
+        layer()
+    prof = des.profile_read()
+    des.profile_enable(False)
+    arr = 4.0 * B * d
+    algo = {"cross_partial": arr + 4.0 * d + 4.0 * K * B, "cross_apply": 3 * arr + 4.0 * d + 4.0 * B,
+            "cross_backward": 7 * arr + 12.0 * d + 12.0 * B}
+    kernels = {}
+    for name, (launches, total_ms) in prof.items():
+        per = total_ms / reps
+        e = {"launches_per_pass": launches / reps, "ms_per_pass": round(per, 4)}
+        if name in algo and per > 0:
+            e["algorithmic_GB"] = round(algo[name] / 1e9, 3)
+            e["GBps"] = round(algo[name] / (per * 1e-3) / 1e9, 1)
+            e["frac_of_hbm_peak"] = round(e["GBps"] / HBM_PEAK_GBS, 4)
+        kernels[name] = e
+    assert bool(torch.isfinite(y).all()) and bool(torch.isfinite(dw).all())
+    return {"workload": f"configs[{w.index}] {w.name}", "B": B, "F": F, "D": D, "d": d, "K": K, "dtype": "f32",
+            "ms_per_pass": round(ms, 4), "peak_GBps": HBM_PEAK_GBS, "kernels": kernels}
 
 
 def run_workload(args, index, cpu):

@@ -309,13 +309,20 @@ des_status_t des_cross_apply(const float *x0, const float *xl, const float *s, c
  *     g_x0[b,j] (+)= g_y[b,j] s[b]                 db[j] = sum_b g_y[b,j]
  * x_0 feeds every layer, so the layers' shares of its gradient add up: accumulate_g_x0 != 0 adds to
  * what g_x0 holds, 0 overwrites it.  (The first layer's input is x_0 itself: its g_xl is one more
- * share, to be added by the caller.)  Sums in double, the batch sums as per-slice partials added in
- * slice order.  g_xl may alias g_y.  workspace: device, 256-byte aligned, des_cross_backward_bytes(B, d)
+ * share: pass g_xl == NULL for that layer and it is added into g_x0 as well.)  Sums in double, the batch
+ * sums as per-slice partials added in slice order.  g_xl may alias g_y.  workspace: device, 256-byte aligned, des_cross_backward_bytes(B, d)
  * bytes, else DES_ERR_WORKSPACE.  B == 0 writes dw = db = 0 and touches nothing else. */
 des_status_t des_cross_backward_bytes(int64_t B, int64_t d, size_t *workspace_bytes);
 des_status_t des_cross_backward(const float *x0, const float *xl, const float *w, const float *s, const float *g_y,
                                 int64_t B, int64_t d, float *g_xl, float *g_x0, int32_t accumulate_g_x0, float *dw,
                                 float *db, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward of the sub-operator alone, for a gradient g_s[B] of its aggregated scalar (e.g. when the
+ * scalar is a term of the logit: the output unit's weights on the cross network's result):
+ *     g_xl[b,j] = g_s[b] w[j]      dw[j] = sum_b g_s[b] xl[b,j].
+ * g_xl may be null (only dw wanted).  Same workspace as des_cross_backward. */
+des_status_t des_cross_partial_backward(const float *xl, const float *w, const float *g_s, int64_t B, int64_t d,
+                                        float *g_xl, float *dw, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- The dense remainder of a model step --------------------------------------------------------
  * After the aggregated weights-rich operators every process computes the same thing (Section 3.2.1);

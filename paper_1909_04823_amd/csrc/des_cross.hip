@@ -33,6 +33,7 @@ __global__ __launch_bounds__(kBlock) void k_cross_partial(const float *__restric
     const int nf = s < F ? (F - s + K - 1) / K : 0;           // fields of this shard
     const int m_end = nf * D4;
     double acc = 0.0;
+#pragma unroll 4
     for (int m = t; m < m_end; m += G) {
       const int f = s + K * (m / D4);
       const int64_t q = (int64_t)f * D4 + (m % D4);
@@ -53,6 +54,7 @@ __global__ __launch_bounds__(kBlock) void k_cross_apply(const float *__restrict_
                                                          int64_t B, int64_t d4, float *__restrict__ y) {
   const int64_t n4 = B * d4;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+#pragma unroll 2
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
     const int64_t b = i / d4, q = i % d4;
     const float4 a = reinterpret_cast<const float4 *>(x0)[i];
@@ -75,6 +77,7 @@ __global__ __launch_bounds__(kBlock) void k_cross_gs(const float *__restrict__ g
   const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
   for (int64_t b = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave; b < B; b += wstride) {
     double acc = 0.0;
+#pragma unroll 4
     for (int64_t q = lane; q < d4; q += kWave) {
       const float4 g = reinterpret_cast<const float4 *>(g_y)[b * d4 + q];
       const float4 a = reinterpret_cast<const float4 *>(x0)[b * d4 + q];
@@ -90,7 +93,9 @@ __global__ __launch_bounds__(kBlock) void k_cross_gs(const float *__restrict__ g
 // slices); a thread owns four columns, walks the slice's rows and keeps its eight sums in double:
 //   g_xl = g_y + g_s[b] * w,   g_x0 (+)= g_y * s[b],   dw += g_s[b] * xl,   db += g_y.
 // partial[slice][0][:] = dw sums, partial[slice][1][:] = db sums.
-template <bool kAccumulate>
+// kFold: the layer's input is x0 itself, so g_xl is one more share of x0's gradient and is added into g_x0
+// instead of being written.
+template <bool kAccumulate, bool kFold>
 __global__ __launch_bounds__(kBlock) void k_cross_grad(const float *__restrict__ xl, const float *__restrict__ w,
                                                         const float *__restrict__ s, const float *__restrict__ g_s,
                                                         const float *g_y, int64_t B, int64_t d4,
@@ -126,11 +131,12 @@ __global__ __launch_bounds__(kBlock) void k_cross_grad(const float *__restrict__
       o.y = (float)((double)g[k].y + gd * (double)wv.y);
       o.z = (float)((double)g[k].z + gd * (double)wv.z);
       o.w = (float)((double)g[k].w + gd * (double)wv.w);
-      z.x = (float)((kAccumulate ? (double)old[k].x : 0.0) + (double)g[k].x * sd);
-      z.y = (float)((kAccumulate ? (double)old[k].y : 0.0) + (double)g[k].y * sd);
-      z.z = (float)((kAccumulate ? (double)old[k].z : 0.0) + (double)g[k].z * sd);
-      z.w = (float)((kAccumulate ? (double)old[k].w : 0.0) + (double)g[k].w * sd);
-      reinterpret_cast<float4 *>(g_xl)[i] = o;
+      const double f = kFold ? sd + 1.0 : sd;            // g*s + g when the input gradient is folded in
+      z.x = (float)((kAccumulate ? (double)old[k].x : 0.0) + (double)g[k].x * f + (kFold ? gd * (double)wv.x : 0.0));
+      z.y = (float)((kAccumulate ? (double)old[k].y : 0.0) + (double)g[k].y * f + (kFold ? gd * (double)wv.y : 0.0));
+      z.z = (float)((kAccumulate ? (double)old[k].z : 0.0) + (double)g[k].z * f + (kFold ? gd * (double)wv.z : 0.0));
+      z.w = (float)((kAccumulate ? (double)old[k].w : 0.0) + (double)g[k].w * f + (kFold ? gd * (double)wv.w : 0.0));
+      if (!kFold) reinterpret_cast<float4 *>(g_xl)[i] = o;
       reinterpret_cast<float4 *>(g_x0)[i] = z;
       dw[0] += gd * (double)x[k].x; dw[1] += gd * (double)x[k].y; dw[2] += gd * (double)x[k].z; dw[3] += gd * (double)x[k].w;
       db[0] += (double)g[k].x; db[1] += (double)g[k].y; db[2] += (double)g[k].z; db[3] += (double)g[k].w;
@@ -142,11 +148,49 @@ __global__ __launch_bounds__(kBlock) void k_cross_grad(const float *__restrict__
   for (int k = 0; k < 4; ++k) { p[k] = dw[k]; p[d + k] = db[k]; }
 }
 
-// dw[j], db[j] = sums over the slices, in slice order.
+// Backward of the sub-operator alone, for the gradient g_s[b] of the aggregated scalar:
+//   g_xl[b,j] = g_s[b] * w[j],   dw[j] = sum_b g_s[b] * xl[b,j]   (partial[slice][0][:]; the db half stays unused).
+__global__ __launch_bounds__(kBlock) void k_cross_subop_grad(const float *__restrict__ xl, const float *__restrict__ w,
+                                                              const float *__restrict__ g_s, int64_t B, int64_t d4,
+                                                              int64_t rows_per_slice, float *__restrict__ g_xl,
+                                                              double *__restrict__ partial) {
+  const int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (q >= d4) return;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_slice;
+  const int64_t r1 = min(B, r0 + rows_per_slice);
+  const float4 wv = reinterpret_cast<const float4 *>(w)[q];
+  double dw[4] = {0.0, 0.0, 0.0, 0.0};
+  constexpr int U = 4;
+  for (int64_t r = r0; r < r1; r += U) {
+    float4 x[U];
+    float gs[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const int64_t rr = r + k < r1 ? r + k : r;
+      x[k] = reinterpret_cast<const float4 *>(xl)[rr * d4 + q];
+      gs[k] = g_s[rr];
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      if (r + k >= r1) break;
+      const double gd = (double)gs[k];
+      if (g_xl)
+        reinterpret_cast<float4 *>(g_xl)[(r + k) * d4 + q] =
+            make_float4((float)(gd * (double)wv.x), (float)(gd * (double)wv.y), (float)(gd * (double)wv.z),
+                        (float)(gd * (double)wv.w));
+      dw[0] += gd * (double)x[k].x; dw[1] += gd * (double)x[k].y; dw[2] += gd * (double)x[k].z; dw[3] += gd * (double)x[k].w;
+    }
+  }
+  double *p = partial + (int64_t)blockIdx.y * 2 * (d4 * 4) + q * 4;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) p[k] = dw[k];
+}
+
+// dw[j], db[j] = sums over the slices, in slice order (db null: only the dw half is summed).
 __global__ __launch_bounds__(kBlock) void k_cross_final(const double *__restrict__ partial, int slices, int64_t d,
                                                          float *__restrict__ dw, float *__restrict__ db) {
   const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= 2 * d) return;
+  if (j >= (db ? 2 * d : d)) return;
   double a = 0.0;
   for (int sl = 0; sl < slices; ++sl) a += partial[(int64_t)sl * 2 * d + j];
   if (j < d) dw[j] = (float)a; else db[j - d] = (float)a;
@@ -203,7 +247,7 @@ des_status_t des_cross_apply(const float *x0, const float *xl, const float *s_in
     return DES_ERR_INVALID_ARG;
   hipStream_t s = (hipStream_t)stream;
   ProfScope ps(KID_CROSS_APPLY, s);
-  hipLaunchKernelGGL(k_cross_apply, dim3(blocks_for(B * (d / 4), 1 << 16)), dim3(kBlock), 0, s, x0, xl, s_in, bias, B,
+  hipLaunchKernelGGL(k_cross_apply, dim3(blocks_for(B * (d / 4), 1 << 18)), dim3(kBlock), 0, s, x0, xl, s_in, bias, B,
                      d / 4, y);
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
 }
@@ -231,7 +275,7 @@ des_status_t des_cross_backward(const float *x0, const float *xl, const float *w
     hipLaunchKernelGGL(k_cross_final, dim3(blocks_for(2 * d, 1 << 20)), dim3(kBlock), 0, s, partial, 0, d, dw, db);
     return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
   }
-  if (!x0 || !xl || !w || !s_in || !g_y || !g_xl || !g_x0) return DES_ERR_INVALID_ARG;
+  if (!x0 || !xl || !w || !s_in || !g_y || !g_x0) return DES_ERR_INVALID_ARG;
   if (!aligned16(x0) || !aligned16(xl) || !aligned16(w) || !aligned16(g_y) || !aligned16(g_xl) || !aligned16(g_x0))
     return DES_ERR_INVALID_ARG;
   const int64_t d4 = d / 4;
@@ -240,13 +284,36 @@ des_status_t des_cross_backward(const float *x0, const float *xl, const float *w
   ProfScope ps(KID_CROSS_GRAD, s);
   hipLaunchKernelGGL(k_cross_gs, dim3(blocks_for(B * kWave, 1 << 16)), dim3(kBlock), 0, s, g_y, x0, B, d4, g_s);
   const dim3 grid((unsigned)((d4 + kBlock - 1) / kBlock), (unsigned)slices);
-  if (accumulate_g_x0)
-    hipLaunchKernelGGL(k_cross_grad<true>, grid, dim3(kBlock), 0, s, xl, w, s_in, g_s, g_y, B, d4, rows_per_slice, g_xl,
-                       g_x0, partial);
-  else
-    hipLaunchKernelGGL(k_cross_grad<false>, grid, dim3(kBlock), 0, s, xl, w, s_in, g_s, g_y, B, d4, rows_per_slice, g_xl,
-                       g_x0, partial);
+#define DES_CROSS_GRAD(ACC, FOLD)                                                                                    \
+  hipLaunchKernelGGL((k_cross_grad<ACC, FOLD>), grid, dim3(kBlock), 0, s, xl, w, s_in, g_s, g_y, B, d4, rows_per_slice, \
+                     g_xl, g_x0, partial)
+  if (g_xl) { if (accumulate_g_x0) DES_CROSS_GRAD(true, false); else DES_CROSS_GRAD(false, false); }
+  else      { if (accumulate_g_x0) DES_CROSS_GRAD(true, true);  else DES_CROSS_GRAD(false, true); }
+#undef DES_CROSS_GRAD
   hipLaunchKernelGGL(k_cross_final, dim3(blocks_for(2 * d, 1 << 20)), dim3(kBlock), 0, s, partial, slices, d, dw, db);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+des_status_t des_cross_partial_backward(const float *xl, const float *w, const float *g_s, int64_t B, int64_t d,
+                                        float *g_xl, float *dw, void *workspace, size_t workspace_bytes, void *stream) {
+  if (B < 0 || d < 4 || (d & 3) || !dw) return DES_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  size_t need = 0;
+  des_cross_backward_bytes(B, d, &need);
+  if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return DES_ERR_WORKSPACE;
+  double *partial = (double *)((char *)workspace + align_up((size_t)(B > 0 ? B : 1) * sizeof(float), 256));
+  ProfScope ps(KID_CROSS_GRAD, s);
+  if (B == 0) {
+    hipLaunchKernelGGL(k_cross_final, dim3(blocks_for(d, 1 << 20)), dim3(kBlock), 0, s, partial, 0, d, dw, (float *)nullptr);
+    return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+  }
+  if (!xl || !w || !g_s || !aligned16(xl) || !aligned16(w) || !aligned16(g_xl)) return DES_ERR_INVALID_ARG;
+  const int64_t d4 = d / 4;
+  const int slices = cross_slices(B, d);
+  const int64_t rows_per_slice = (B + slices - 1) / slices;
+  const dim3 grid((unsigned)((d4 + kBlock - 1) / kBlock), (unsigned)slices);
+  hipLaunchKernelGGL(k_cross_subop_grad, grid, dim3(kBlock), 0, s, xl, w, g_s, B, d4, rows_per_slice, g_xl, partial);
+  hipLaunchKernelGGL(k_cross_final, dim3(blocks_for(d, 1 << 20)), dim3(kBlock), 0, s, partial, slices, d, dw, (float *)nullptr);
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
 }
 

@@ -30,7 +30,7 @@ EXPORTS = [
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
     "des_batch_validate", "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
     "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
-    "des_cross_partial", "des_cross_apply", "des_cross_backward_bytes", "des_cross_backward",
+    "des_cross_partial", "des_cross_apply", "des_cross_backward_bytes", "des_cross_backward", "des_cross_partial_backward",
     "des_profile_enable", "des_profile_read", "des_status_string",
 ]
 
@@ -104,6 +104,7 @@ _sig = {
     "des_cross_apply": [vp, vp, vp, vp, i64, i64, vp, vp],
     "des_cross_backward_bytes": [i64, i64, C.POINTER(C.c_size_t)],
     "des_cross_backward": [vp, vp, vp, vp, vp, i64, i64, vp, vp, i32, vp, vp, vp, C.c_size_t, vp],
+    "des_cross_partial_backward": [vp, vp, vp, i64, i64, vp, vp, vp, C.c_size_t, vp],
     "des_profile_enable": [i32],
     "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
 }
@@ -422,13 +423,27 @@ def cross_backward_bytes(B: int, d: int) -> int:
     return int(n.value)
 
 
+def cross_partial_backward(xl: torch.Tensor, w: torch.Tensor, g_s: torch.Tensor, g_xl: Optional[torch.Tensor],
+                           dw: torch.Tensor, workspace: torch.Tensor):
+    """g_xl = g_s[:,None] * w and dw = sum_b g_s[b] xl[b] for a gradient g_s of the aggregated scalar."""
+    B = xl.shape[0]
+    d = w.numel()
+    if xl.numel() != B * d or g_s.numel() != B or dw.numel() != d or (g_xl is not None and g_xl.numel() != B * d):
+        raise ValueError("shape mismatch")
+    _check(_lib.des_cross_partial_backward(_ptr(xl), _ptr(w), _ptr(g_s), B, d, _ptr(g_xl), _ptr(dw), _ptr(workspace),
+                                           _nbytes(workspace), _stream()), "des_cross_partial_backward")
+
+
 def cross_backward(x0: torch.Tensor, xl: torch.Tensor, w: torch.Tensor, s: torch.Tensor, g_y: torch.Tensor,
-                   g_xl: torch.Tensor, g_x0: torch.Tensor, accumulate_g_x0: bool, dw: torch.Tensor, db: torch.Tensor,
-                   workspace: torch.Tensor):
-    """Gradients of one cross layer into g_xl, g_x0 (added to when `accumulate_g_x0`), dw, db."""
+                   g_xl: Optional[torch.Tensor], g_x0: torch.Tensor, accumulate_g_x0: bool, dw: torch.Tensor,
+                   db: torch.Tensor, workspace: torch.Tensor):
+    """Gradients of one cross layer into g_xl, g_x0 (added to when `accumulate_g_x0`), dw, db.  g_xl None: the
+    layer's input is x0 itself and its gradient is added into g_x0 too."""
     B = x0.shape[0]
     d = w.numel()
     for t in (x0, xl, g_y, g_xl, g_x0):
+        if t is None:
+            continue
         if t.numel() != B * d or not t.is_contiguous():
             raise ValueError("row arrays must be contiguous with B*d elements")
     if s.numel() != B or dw.numel() != d or db.numel() != d:
