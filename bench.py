@@ -136,7 +136,7 @@ def main():
     ap.add_argument("--dnn-hidden", type=int, default=256,
                     help="width H of the first fully-connected layer measured after the sparse step and reported "
                          "under \"dnn_layer\" (0 to skip)")
-    ap.add_argument("--model", type=str, default="deepfm", choices=["none", "lr", "fm", "wd", "deepfm"],
+    ap.add_argument("--model", type=str, default="deepfm", choices=["none", "lr", "fm", "wd", "deepfm", "dcn"],
                     help="after the sparse steps, also time whole training steps of this model (tower widths "
                          "--dnn-hidden and half of it) on the main workload; reported under \"model_step\"")
     ap.add_argument("--policy", type=str, default="key", choices=["key", "field"],
@@ -152,6 +152,7 @@ def main():
                          "stream beside the forward pass)")
     ap.add_argument("--tower", type=str, default=None,
                     help="comma-separated hidden widths of the model step's tower (default: dnn-hidden, dnn-hidden/2)")
+    ap.add_argument("--cross-layers", type=int, default=2, help="cross layers of --model dcn")
     ap.add_argument("--no-cross", action="store_true",
                     help="skip the DCN cross layer timed at the main workload's shape (reported under \"cross_layer\")")
     ap.add_argument("--no-cpu", action="store_true")
@@ -548,6 +549,8 @@ def run_model_step(args, w, table, batches, opt, eps):
     H = args.dnn_hidden
     hidden = tuple(int(x) for x in args.tower.split(",")) if args.tower else (H, max(4, H // 2 // 4 * 4))
     tower = synth.tower_init(w.seed, w.F, w.D, hidden=hidden)
+    if args.model == "dcn":
+        tower.update(synth.cross_init(w.seed, w.F, w.D, n_cross=args.cross_layers))
     # throughput only: the table has just been through the sparse steps above, whose upstream gradients
     # are random, so the loss value of these steps means nothing (it is only checked to be finite)
     m = Model(table, w.F, args.model, tower, w.B, dict(opt_emb=opt, opt_w=opt, lr=1e-5, eps=eps),

@@ -1,4 +1,4 @@
-"""One training step of LR / FM / W&D / DeepFM under DES on one MI355X, as a sequence of library calls.
+"""One training step of LR / FM / W&D / DeepFM / DCN under DES on one MI355X, as a sequence of library calls.
 
 Nothing is computed here: every tensor operation is a call into libdes (``des.py``); this module only
 owns the device buffers and fixes the order of the calls --
@@ -8,7 +8,12 @@ owns the device buffers and fixes the order of the calls --
          -> head backward -> tower backward -> dnn_backward -> backward_update -> dense_update
 
 Model kinds follow the paper's table of shared components (Section 4): "lr" first order; "fm" first and
-second order; "wd" first and high order; "deepfm" all three.
+second order; "wd" first and high order; "deepfm" all three.  "dcn" (Section 4, the paragraph on DCN) puts a
+cross network x_{l+1} = x_0 (x_l^T w_l) + b_l + x_l beside the tower, both on the pooled embeddings x_0; every
+dot product over the d = F*D columns, the output unit's on the network's result included, is a DES
+sub-operator (per-shard scalars, summed):
+
+    pool -> [cross_partial -> aggregate -> cross_apply] x n -> cross_partial -> aggregate  (one logit term)
 """
 from __future__ import annotations
 
@@ -19,7 +24,8 @@ import torch
 
 from . import des
 
-COMPONENTS = {"lr": ("lr",), "fm": ("lr", "fm"), "wd": ("lr", "dnn"), "deepfm": ("lr", "fm", "dnn")}
+COMPONENTS = {"lr": ("lr",), "fm": ("lr", "fm"), "wd": ("lr", "dnn"), "deepfm": ("lr", "fm", "dnn"),
+              "dcn": ("cross", "dnn")}
 
 
 class Model:
@@ -27,7 +33,8 @@ class Model:
                  opt_sparse: dict, opt_dense: dict):
         """`table`: a des.Table whose state arrays fit `opt_sparse`; `tower`: initial dense parameters as numpy
         arrays -- W1[F*D,H1], b1[H1] (the layer under DES), W2[H1,H2], b2, ... Wn, bn (n >= 1 hidden layers),
-        w_out[Hn], b0[1]; opt_*: des_optimizer_t fields."""
+        w_out[Hn], b0[1]; for "dcn" also cw1[d], cb1[d], ... (cross layers) and w_cross[d]; opt_*:
+        des_optimizer_t fields."""
         self.t, self.F, self.D, self.K = table, int(F), table.dim, table.K
         self.parts = COMPONENTS[kind]
         self.opt_sparse, self.opt_dense = dict(opt_sparse), dict(opt_dense)
@@ -59,7 +66,17 @@ class Model:
             for i in range(1, self.n_layers):
                 ws_bytes = max(ws_bytes, des.dnn_backward_bytes(B, 1, self.H[i - 1], self.H[i]))
             self.dnn_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+            self.cross = "cross" in self.parts
+            if self.cross:
+                d = F * D
+                self.n_cross = sum(1 for k in self.params if k.startswith("cw"))
+                self.xs = [self.pool] + [f(B, F, D) for _ in range(self.n_cross)]      # inputs of the cross layers, result
+                self.cs = [f(B) for _ in range(self.n_cross + 1)]                       # aggregated scalars; last: logit term
+                self.cP = f(K, B)
+                self.g_x = f(B, F, D)
+                self.cross_ws = torch.empty(des.cross_backward_bytes(B, d), dtype=torch.uint8, device=dev)
         else:
+            self.cross = False
             self.params = {"b0": torch.from_numpy(np.ascontiguousarray(tower["b0"] if tower else np.zeros(1), dtype=np.float32)).to(dev)}
         self.grads = {k: torch.empty_like(v) for k, v in self.params.items()}
         self.s1 = {k: torch.zeros_like(v) for k, v in self.params.items()}
@@ -86,8 +103,15 @@ class Model:
                 des.dnn_partial_forward(x, p[f"W{i + 1}"], self.K if i == 0 else 1, out=self.Yp[i])
                 des.aggregate_bias_act(self.Yp[i], p[f"b{i + 1}"], True, self.a[i])
                 x = self.a[i].view(B, 1, self.H[i])
+        if self.cross:
+            for l in range(self.n_cross):
+                des.cross_partial(self.xs[l], p[f"cw{l + 1}"], self.K, out=self.cP)
+                des.aggregate_partials(self.cP, self.cs[l])
+                des.cross_apply(self.pool, self.xs[l], self.cs[l], p[f"cb{l + 1}"], out=self.xs[l + 1])
+            des.cross_partial(self.xs[-1], p["w_cross"], self.K, out=self.cP)
+            des.aggregate_partials(self.cP, self.cs[-1])
         des.head(labels, self.g_logit, self.ws,
-                 A_lr=self.A_lr if "lr" in self.parts else None,
+                 A_lr=self.A_lr if "lr" in self.parts else (self.cs[-1] if self.cross else None),
                  fm2=self.fm2 if "fm" in self.parts else None,
                  a=self.a[-1] if self.dnn else None, w_out=p["w_out"] if self.dnn else None, b0=p["b0"],
                  logit=self.logit, p=self.p, loss=self.loss,
@@ -114,6 +138,14 @@ class Model:
                                      self.da[i - 1].view(B, 1, self.H[i - 1]), g[f"W{i + 1}"], self.dnn_ws)
                 else:
                     des.dnn_backward(self.pool, p["W1"], self.da[0], self.g_pool, g["W1"], self.dnn_ws)
+        if self.cross:
+            # the cross network's result is a term of the logit; then layer by layer, every layer adding its share of
+            # the gradient of x0 = pool to what the tower left in g_pool (the first layer's input gradient too)
+            des.cross_partial_backward(self.xs[-1], p["w_cross"], self.g_logit, self.g_x, g["w_cross"], self.cross_ws)
+            for l in range(self.n_cross - 1, -1, -1):
+                des.cross_backward(self.pool, self.xs[l], p[f"cw{l + 1}"], self.cs[l], self.g_x,
+                                   self.g_x if l > 0 else None, self.g_pool, True, g[f"cw{l + 1}"], g[f"cb{l + 1}"],
+                                   self.cross_ws)
 
     def update(self, batch: des.Batch, rows: torch.Tensor, dbg: Optional[dict] = None):
         """Sparse backward with merge and row update, then the dense optimizer step."""

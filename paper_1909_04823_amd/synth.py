@@ -319,6 +319,19 @@ def tower_init(seed: int, F: int, D: int, hidden=(256, 128)):
     return out
 
 
+def cross_init(seed: int, F: int, D: int, n_cross: int = 2):
+    """Initial parameters of a DCN cross network over d = F*D columns: cw{l}[d] ~ N(0, 1/d) and cb{l}[d] = 0 for
+    l = 1..n_cross, and w_cross[d] ~ N(0, 1/d), the output unit's weights on the network's result."""
+    rng = np.random.default_rng((int(seed), 0xC705))
+    d = F * D
+    out = {}
+    for l in range(1, n_cross + 1):
+        out[f"cw{l}"] = rng.standard_normal(d, dtype=np.float32) * np.float32(np.sqrt(1.0 / d))
+        out[f"cb{l}"] = np.zeros(d, np.float32)
+    out["w_cross"] = rng.standard_normal(d, dtype=np.float32) * np.float32(np.sqrt(1.0 / d))
+    return out
+
+
 def planted_labels(batch: Batch, seed: int, base_rate_logit: float = -1.4, strength: float = 1.5) -> np.ndarray:
     """Click labels a model can learn from the IDs: every ID carries a hidden weight in [-1,1)
     (a scramble of the ID, centred on the batch's entry mean so that hot IDs do not shift every

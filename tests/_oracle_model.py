@@ -7,7 +7,8 @@ import numpy as np
 
 f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
 
-COMPONENTS = {"lr": ("lr",), "fm": ("lr", "fm"), "wd": ("lr", "dnn"), "deepfm": ("lr", "fm", "dnn")}
+COMPONENTS = {"lr": ("lr",), "fm": ("lr", "fm"), "wd": ("lr", "dnn"), "deepfm": ("lr", "fm", "dnn"),
+              "dcn": ("cross", "dnn")}
 
 
 class OracleModel:
@@ -39,6 +40,16 @@ class OracleModel:
                 Y = o.aggregate(o.dnn_partial_forward(x, p[f"W{i + 1}"], K if i == 0 else 1))
                 c["a"].append(f32(o.bias_act(Y, p[f"b{i + 1}"], True)))
                 x = c["a"][i][:, None, :]
+        if "cross" in self.parts:
+            # cross network on x0 = pool; its result enters the logit through one more sharded dot product
+            n_cross = sum(1 for k in p if k.startswith("cw"))
+            c["xs"], c["cs"] = [c["pool"]], []
+            for l in range(n_cross):
+                s = f32(o.aggregate(o.cross_partial(c["xs"][l], p[f"cw{l + 1}"], K)))
+                c["cs"].append(s)
+                c["xs"].append(f32(o.cross_apply(c["pool"], c["xs"][l], s, p[f"cb{l + 1}"])))
+            c["cs"].append(f32(o.aggregate(o.cross_partial(c["xs"][-1], p["w_cross"], K))))
+            c["A_lr"] = c["cs"][-1]                      # an additive term of the logit, like the first-order sum
         c["head"] = o.head(labels, c["A_lr"], c["fm2"], c["a"][-1] if "dnn" in self.parts else None,
                            p["w_out"] if "dnn" in self.parts else None, float(p["b0"][0]))
         return c
@@ -64,6 +75,18 @@ class OracleModel:
                 da = f32(dx[:, 0, :]) if i > 0 else None
                 if i == 0:
                     c["g_pool"] = f32(dx)
+        if "cross" in self.parts:
+            n_cross = len(c["xs"]) - 1
+            gx, g["w_cross"] = o.cross_partial_backward(c["xs"][-1], p["w_cross"], c["g_logit"])
+            gx = f32(gx)
+            g_pool = c["g_pool"]                          # fp32: what the tower's backward left
+            for l in range(n_cross - 1, -1, -1):
+                _, g_xl, g_x0, g[f"cw{l + 1}"], g[f"cb{l + 1}"] = o.cross_backward(c["pool"], c["xs"][l], p[f"cw{l + 1}"],
+                                                                                 c["cs"][l], gx)
+                share = g_x0 + (g_xl if l == 0 else 0.0)  # the first layer's input is x0 itself
+                g_pool = f32(g_pool.astype(np.float64) + share)
+                gx = f32(g_xl)
+            c["g_pool"] = g_pool
         c["dense_grads"] = g
         return c
 

@@ -70,6 +70,42 @@ def test_cross_layer_forward_and_backward(oracle, des, B, F, D, K):
     assert_close(dw.cpu().numpy(), dw_ref, "dw (second call)")
 
 
+@pytest.mark.parametrize("B,F,D", [(3, 2, 4), (700, 9, 16), (130, 4, 64)])
+def test_sub_operator_backward_and_first_layer_fold(oracle, des, B, F, D):
+    """des_cross_partial_backward (gradient of the scalar only), and des_cross_backward without g_xl: the layer's
+    input is x0 itself, so its input gradient lands in g_x0 together with the layer's own share."""
+    import torch
+    d = F * D
+    x0, xl, w, bias, g_y = cross_inputs(11 * B, B, F, D)
+    rng = np.random.default_rng(B)
+    g_s = (0.1 * rng.standard_normal(B)).astype(np.float32)
+    s32 = oracle.aggregate(oracle.cross_partial(x0, w, 3)).astype(np.float32)
+    t = lambda a: torch.from_numpy(a).cuda()
+    ws = torch.empty(des.cross_backward_bytes(B, d), dtype=torch.uint8, device="cuda")
+    nan = lambda *shape: torch.full(shape, float("nan"), device="cuda")
+    g_xl, dw, db = nan(B, F, D), nan(d), nan(d)
+    des.cross_partial_backward(t(xl), t(w), t(g_s), g_xl, dw, ws)
+    torch.cuda.synchronize()
+    g_ref, dw_ref = oracle.cross_partial_backward(xl, w, g_s)
+    assert_close(g_xl.cpu().numpy(), g_ref, "g_xl of the sub-operator")
+    assert_close(dw.cpu().numpy(), dw_ref, "dw of the sub-operator")
+    dw2 = nan(d)
+    des.cross_partial_backward(t(xl), t(w), t(g_s), None, dw2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dw, dw2)
+    # first layer: xl is x0
+    _, g_xl_ref, g_x0_ref, dw_ref, db_ref = oracle.cross_backward(x0, x0, w, s32, g_y)
+    for accumulate in (False, True):
+        before = (0.01 * rng.standard_normal((B, F, D))).astype(np.float32)
+        g_x0 = t(before.copy())
+        des.cross_backward(t(x0), t(x0), t(w), t(s32), t(g_y), None, g_x0, accumulate, dw, db, ws)
+        torch.cuda.synchronize()
+        assert_close(g_x0.cpu().numpy(), (before.astype(np.float64) if accumulate else 0.0) + g_x0_ref + g_xl_ref,
+                     f"g_x0 with the input gradient folded in (accumulate={accumulate})")
+        assert_close(dw.cpu().numpy(), dw_ref, "dw")
+        assert_close(db.cpu().numpy(), db_ref, "db")
+
+
 def test_stacked_cross_layers_chain(oracle, des):
     """Three layers forward and backward, each stage fed with the previous stage's fp32 output on both sides."""
     import torch

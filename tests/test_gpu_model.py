@@ -114,7 +114,8 @@ SETTINGS = {
 
 @pytest.mark.parametrize("kind,setting,hidden", [("lr", "sgd", (64, 32)), ("fm", "sgd", (64, 32)), ("wd", "sgd", (64, 32)),
                                                  ("deepfm", "sgd", (64, 32)), ("deepfm", "paper", (64, 32)),
-                                                 ("deepfm", "sgd", (48,)), ("wd", "paper", (64, 32, 16))])
+                                                 ("deepfm", "sgd", (48,)), ("wd", "paper", (64, 32, 16)),
+                                                 ("dcn", "sgd", (64, 32)), ("dcn", "paper", (48,))])
 def test_training_steps_match_oracle_chain(oracle, des, kind, setting, hidden):
     """Three training steps of the whole model on a shrunken Criteo-shaped workload, library calls
     against the oracle's functions chained in the same order.  Each step is compared from a common
@@ -129,6 +130,8 @@ def test_training_steps_match_oracle_chain(oracle, des, kind, setting, hidden):
     w = synth.workload(1, scale=1 / 16)
     opt_sparse, opt_dense, state_arrays = SETTINGS[setting]
     tower = synth.tower_init(w.seed, w.F, w.D, hidden=hidden)
+    if kind == "dcn":
+        tower.update(synth.cross_init(w.seed, w.F, w.D, n_cross=3))
     keys0 = synth.preinsert_keys(w)
     vals0 = synth.host_values(w, keys0.shape[0])
     ot = oracle.Table(w.D, w.capacity, seed=w.seed, init_scale=w.init_std)

@@ -743,7 +743,7 @@ def test_dense_update_closed_forms(oracle):
 
 
 @pytest.mark.parametrize("kind,hidden", [("lr", (8, 4)), ("fm", (8, 4)), ("wd", (8, 4)), ("deepfm", (8, 4)),
-                                         ("deepfm", (8,)), ("wd", (8, 4, 4))])
+                                         ("deepfm", (8,)), ("wd", (8, 4, 4)), ("dcn", (8, 4))])
 def test_whole_model_gradients_match_finite_differences(oracle, kind, hidden):
     """The chained step (sparse operators -> first layer under DES -> tower -> output unit -> loss and
     all the way back) against central differences of its own loss: every dense parameter class and the
@@ -757,6 +757,10 @@ def test_whole_model_gradients_match_finite_differences(oracle, kind, hidden):
     tower = synth.tower_init(5, F, D, hidden=hidden)
     for k in [k for k in tower if k[0] == "b" and k != "b0"]:
         tower[k] = (0.3 * rng.standard_normal(tower[k].shape)).astype(np.float32)     # units on both sides of 0
+    if kind == "dcn":
+        tower.update(synth.cross_init(5, F, D, n_cross=2))
+        for k in [k for k in tower if k.startswith("cb")]:
+            tower[k] = (0.3 * rng.standard_normal(tower[k].shape)).astype(np.float32)
     labels = (rng.random(B) < 0.5).astype(np.float32)
     m = OracleModel(oracle, t, F, K, kind, tower, dict(opt_emb=0, opt_w=0), dict(opt_emb=0))
     rows = t.find(keys)
