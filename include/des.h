@@ -324,6 +324,36 @@ des_status_t des_cross_backward(const float *x0, const float *xl, const float *w
 des_status_t des_cross_partial_backward(const float *xl, const float *w, const float *g_s, int64_t B, int64_t d,
                                         float *g_xl, float *dw, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The whole cross network in two passes over x_0.  Every layer adds a multiple of x_0 and a bias to its
+ * input, so x_l[b,:] = gamma_l[b] x_0[b,:] + c_l with gamma_0 = 1, gamma_{l+1} = gamma_l + s_l,
+ * c_l = b_0 + ... + b_{l-1}, and s_l[b] = gamma_l[b] t_l[b] + <c_l, w_l> where t_k[b] = <x_0[b,:], u_k>.
+ * U [m,d] holds the n layers' weights w_0 .. w_{n-1} and, as its last row, the weights u_n of the output
+ * unit on the network's result x_n (m = n + 1 <= 8); bias is [n,d].  The dot products t_k are the
+ * sub-operators (cut along d, one scalar per sample, shard and row of U; under DES one exchange of m
+ * scalars per sample serves the whole network); the rest is arithmetic on scalars.  Results equal the
+ * layer-by-layer calls above up to the rounding of the intermediate x_l, which are never formed.
+ *
+ * des_cross_net_partial: P[s,b,k] = sum over the columns j of shard s of x0[b,j] U[k,j]; P [K,B,m].  Sum the
+ *   shards with des_aggregate_partials(P, K, B*m, t) to get t [B,m].
+ * des_cross_net_forward: gamma [B,m] (gamma_0 .. gamma_n) and c[b] = <x_n[b,:], u_n>, the network's term of
+ *   the logit.
+ * des_cross_net_backward, for the gradient g[B] of that term: g_x0[b,:] (+)= sum_k beta_k[b] U[k,:] with
+ *   beta_l = g_s_l gamma_l, beta_n = g gamma_n, g_s_l = g t_n + sum_{l'>l} g_s_l' t_l' (accumulate_g_x0 as above);
+ *   dU[k,:] = sum_b beta_k[b] x0[b,:] + c_k sum_b g_s_k (k = n: sum_b g);  dbias[l,:] = the batch sum of the
+ *   gradient of x_{l+1}.  Batch sums in double, per-slice partials added in slice order.
+ * workspace: device, 256-byte aligned, des_cross_net_bytes(B, d, n) bytes, the same buffer for forward and
+ * backward is fine.  Pointer, alignment and size rules as for the layer-by-layer calls. */
+des_status_t des_cross_net_bytes(int64_t B, int64_t d, int32_t n_layers, size_t *workspace_bytes);
+des_status_t des_cross_net_partial(const float *x0, const float *U, int64_t B, int32_t F, int32_t D, int32_t m,
+                                   int32_t K, float *P, void *stream);
+des_status_t des_cross_net_forward(const float *t, const float *U, const float *bias, int64_t B, int64_t d,
+                                   int32_t n_layers, float *gamma, float *c, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+des_status_t des_cross_net_backward(const float *x0, const float *U, const float *bias, const float *t,
+                                    const float *gamma, const float *g, int64_t B, int64_t d, int32_t n_layers,
+                                    float *g_x0, int32_t accumulate_g_x0, float *dU, float *dbias, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
 /* ---- The dense remainder of a model step --------------------------------------------------------
  * After the aggregated weights-rich operators every process computes the same thing (Section 3.2.1);
  * Section 4's models differ in which components feed the output (LR: first order; FM: + second

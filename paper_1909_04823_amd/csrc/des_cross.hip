@@ -196,6 +196,223 @@ __global__ __launch_bounds__(kBlock) void k_cross_final(const double *__restrict
   if (j < d) dw[j] = (float)a; else db[j - d] = (float)a;
 }
 
+// ---- the whole cross network at once -----------------------------------------------------------
+// Every cross layer adds a multiple of x_0 and a bias to its input, so by induction
+//   x_l[b,:] = gamma_l[b] * x_0[b,:] + c_l[:],   gamma_0 = 1, gamma_{l+1} = gamma_l + s_l,   c_l = b_0 + ... + b_{l-1},
+//   s_l[b]   = <x_l[b], w_l> = gamma_l[b] * t_l[b] + <c_l, w_l>,          t_k[b] = <x_0[b], u_k>,
+// with u_0..u_{n-1} the layers' weights and u_n the output unit's weights on x_n.  The only contact with the
+// [B,d] data is the m = n+1 dot products t_k, all of them sub-operators on x_0 (cut along d, one scalar per
+// sample, shard and vector, summed by the aggregation): one pass over x_0 instead of four per layer, and under
+// DES one exchange of m scalars per sample for the whole network.  The rest of the forward pass is a
+// recurrence on scalars.  Backward, for the gradient g[b] of the logit term <x_n, u_n>:
+//   g_s_l = g t_n + sum_{l'>l} g_s_l' t_l'                    (gradient of s_l; every g_{x_l} is a combination of the u_k)
+//   beta_l = g_s_l gamma_l (l < n),  beta_n = g gamma_n
+//   g_x0[b,:] = sum_k beta_k[b] u_k                           (rank m)
+//   du_k = sum_b beta_k[b] x_0[b,:] + c_k G_k,   G_l = sum_b g_s_l,  G_n = sum_b g
+//   db_l = u_n G_n + sum_{l'>l} u_l' G_l'
+// which is a second pass over x_0 fused with the update of x_0's gradient.
+constexpr int kCrossNetMax = 8;        // most vectors u_k (seven layers and the output unit's)
+
+// P[s,b,k] = sum over the columns j of shard s of x0[b,j] * U[k,j]; a group of G lanes per (sample, shard).
+template <int M>
+__global__ __launch_bounds__(kBlock) void k_cross_net_partial(const float *__restrict__ x0, const float *__restrict__ U,
+                                                               int64_t B, int F, int D4, int K, int G,
+                                                               float *__restrict__ P) {
+  const int64_t gid = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / G;
+  const int t = threadIdx.x % G;
+  const int64_t stride = (int64_t)gridDim.x * kBlock / G;
+  const int64_t row4 = (int64_t)F * D4;
+  for (int64_t item = gid; item < B * K; item += stride) {
+    const int64_t b = item / K;
+    const int s = (int)(item % K);
+    const int nf = s < F ? (F - s + K - 1) / K : 0;
+    const int m_end = nf * D4;
+    double acc[M];
+#pragma unroll
+    for (int k = 0; k < M; ++k) acc[k] = 0.0;
+#pragma unroll 2
+    for (int i = t; i < m_end; i += G) {
+      const int f = s + K * (i / D4);
+      const int64_t q = (int64_t)f * D4 + (i % D4);
+      const float4 xv = reinterpret_cast<const float4 *>(x0)[b * row4 + q];
+#pragma unroll
+      for (int k = 0; k < M; ++k) {
+        const float4 uv = reinterpret_cast<const float4 *>(U)[k * row4 + q];
+        acc[k] += ((double)xv.x * (double)uv.x + (double)xv.y * (double)uv.y) +
+                  ((double)xv.z * (double)uv.z + (double)xv.w * (double)uv.w);
+      }
+    }
+    for (int o = G / 2; o > 0; o >>= 1) {
+#pragma unroll
+      for (int k = 0; k < M; ++k) acc[k] += __shfl_xor(acc[k], o, kWave);
+    }
+    if (t == 0) {
+#pragma unroll
+      for (int k = 0; k < M; ++k) P[((int64_t)s * B + b) * M + k] = (float)acc[k];
+    }
+  }
+}
+
+// c_k[j] = bias[0][j] + ... + bias[k-1][j]
+__device__ inline double bias_prefix(const float *__restrict__ bias, int64_t d, int k, int64_t j) {
+  double c = 0.0;
+  for (int l = 0; l < k; ++l) c += (double)bias[(int64_t)l * d + j];
+  return c;
+}
+
+// kappa[k] = <c_k, u_k>; one workgroup per k.
+__global__ __launch_bounds__(kBlock) void k_cross_net_kappa(const float *__restrict__ U, const float *__restrict__ bias,
+                                                             int64_t d, double *__restrict__ kappa) {
+  __shared__ double red[kBlock];
+  const int k = blockIdx.x;
+  double acc = 0.0;
+  for (int64_t j = threadIdx.x; j < d; j += kBlock) acc += bias_prefix(bias, d, k, j) * (double)U[(int64_t)k * d + j];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int h = kBlock / 2; h > 0; h >>= 1) {
+    if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) kappa[k] = red[0];
+}
+
+// gamma[b,0] = 1, gamma[b,l+1] = gamma[b,l] + s_l[b], c[b] = gamma[b,n] t[b,n] + kappa[n]; one thread per sample.
+__global__ __launch_bounds__(kBlock) void k_cross_net_scalars(const float *__restrict__ t, const double *__restrict__ kappa,
+                                                               int64_t B, int n, float *__restrict__ gamma,
+                                                               float *__restrict__ c) {
+  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  const int m = n + 1;
+  double gam = 1.0;
+  for (int l = 0; l < n; ++l) {
+    gamma[b * m + l] = (float)gam;
+    gam += gam * (double)t[b * m + l] + kappa[l];
+  }
+  gamma[b * m + n] = (float)gam;
+  c[b] = (float)(gam * (double)t[b * m + n] + kappa[n]);
+}
+
+// beta[b,k] and, per workgroup, the sums of g_s_l and g over its samples (Gpart[block][k], double).
+__global__ __launch_bounds__(kBlock) void k_cross_net_beta(const float *__restrict__ t, const float *__restrict__ gamma,
+                                                            const float *__restrict__ g, int64_t B, int n,
+                                                            float *__restrict__ beta, double *__restrict__ Gpart) {
+  __shared__ double red[kBlock];
+  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int m = n + 1;
+  double gs[kCrossNetMax];
+#pragma unroll
+  for (int k = 0; k < kCrossNetMax; ++k) gs[k] = 0.0;
+  if (b < B) {
+    const double gb = (double)g[b];
+#pragma unroll
+    for (int k = 0; k < kCrossNetMax; ++k)
+      if (k == n) gs[k] = gb;                               // slot n carries g itself
+#pragma unroll
+    for (int l = kCrossNetMax - 2; l >= 0; --l) {
+      if (l < n) {
+        double a = gb * (double)t[b * m + n];
+#pragma unroll
+        for (int lp = 1; lp < kCrossNetMax - 1; ++lp)
+          if (lp > l && lp < n) a += gs[lp] * (double)t[b * m + lp];
+        gs[l] = a;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kCrossNetMax; ++k)
+      if (k <= n) beta[b * m + k] = (float)(gs[k] * (double)gamma[b * m + k]);
+  }
+#pragma unroll
+  for (int k = 0; k < kCrossNetMax; ++k) {
+    if (k > n) break;                                       // uniform
+    red[threadIdx.x] = gs[k];
+    __syncthreads();
+    for (int h = kBlock / 2; h > 0; h >>= 1) {
+      if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) Gpart[(int64_t)blockIdx.x * m + k] = red[0];
+    __syncthreads();
+  }
+}
+
+// Gsum[k] = sum over the workgroups' partials, in order; one thread per k.
+__global__ void k_cross_net_gsum(const double *__restrict__ Gpart, int64_t nblk, int m, double *__restrict__ Gsum) {
+  const int k = threadIdx.x;
+  if (k >= m) return;
+  double a = 0.0;
+  for (int64_t i = 0; i < nblk; ++i) a += Gpart[i * m + k];
+  Gsum[k] = a;
+}
+
+// The pass over x0 of the backward: g_x0[b,j] (+)= sum_k beta[b,k] U[k,j] and the slice's part of
+// S[k,j] = sum_b beta[b,k] x0[b,j].  grid (blocks of 256 float4 columns, slices); partial[slice][k][:].
+template <int M, bool kAccumulate>
+__global__ __launch_bounds__(kBlock) void k_cross_net_grad(const float *__restrict__ x0, const float *__restrict__ U,
+                                                            const float *__restrict__ beta, int64_t B, int64_t d4,
+                                                            int64_t rows_per_slice, float *g_x0,
+                                                            double *__restrict__ partial) {
+  const int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (q >= d4) return;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_slice;
+  const int64_t r1 = min(B, r0 + rows_per_slice);
+  float4 u[M];
+  double S[M][4];
+#pragma unroll
+  for (int k = 0; k < M; ++k) {
+    u[k] = reinterpret_cast<const float4 *>(U)[k * d4 + q];
+    S[k][0] = S[k][1] = S[k][2] = S[k][3] = 0.0;
+  }
+  constexpr int UR = 2;
+  for (int64_t r = r0; r < r1; r += UR) {
+    float4 x[UR], old[UR];
+#pragma unroll
+    for (int i = 0; i < UR; ++i) {
+      const int64_t rr = r + i < r1 ? r + i : r;
+      x[i] = reinterpret_cast<const float4 *>(x0)[rr * d4 + q];
+      if (kAccumulate) old[i] = reinterpret_cast<const float4 *>(g_x0)[rr * d4 + q];
+    }
+#pragma unroll
+    for (int i = 0; i < UR; ++i) {
+      if (r + i >= r1) break;
+      double z[4] = {0.0, 0.0, 0.0, 0.0};
+      if (kAccumulate) { z[0] = old[i].x; z[1] = old[i].y; z[2] = old[i].z; z[3] = old[i].w; }
+#pragma unroll
+      for (int k = 0; k < M; ++k) {
+        const double bk = (double)beta[(r + i) * M + k];      // the same address for the whole workgroup
+        z[0] += bk * (double)u[k].x; z[1] += bk * (double)u[k].y; z[2] += bk * (double)u[k].z; z[3] += bk * (double)u[k].w;
+        S[k][0] += bk * (double)x[i].x; S[k][1] += bk * (double)x[i].y; S[k][2] += bk * (double)x[i].z; S[k][3] += bk * (double)x[i].w;
+      }
+      reinterpret_cast<float4 *>(g_x0)[(r + i) * d4 + q] = make_float4((float)z[0], (float)z[1], (float)z[2], (float)z[3]);
+    }
+  }
+  const int64_t d = d4 * 4;
+#pragma unroll
+  for (int k = 0; k < M; ++k) {
+    double *p = partial + ((int64_t)blockIdx.y * M + k) * d + q * 4;
+    p[0] = S[k][0]; p[1] = S[k][1]; p[2] = S[k][2]; p[3] = S[k][3];
+  }
+}
+
+// dU[k,j] = sum over the slices of S + c_k[j] G_k;  dbias[l,j] = U[n,j] G_n + sum_{l'>l} U[l',j] G_l'.
+__global__ __launch_bounds__(kBlock) void k_cross_net_final(const double *__restrict__ partial, int slices,
+                                                             const double *__restrict__ Gsum, const float *__restrict__ U,
+                                                             const float *__restrict__ bias, int64_t d, int n,
+                                                             float *__restrict__ dU, float *__restrict__ dbias) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= d) return;
+  const int m = n + 1;
+  for (int k = 0; k < m; ++k) {
+    double a = 0.0;
+    for (int sl = 0; sl < slices; ++sl) a += partial[((int64_t)sl * m + k) * d + j];
+    dU[(int64_t)k * d + j] = (float)(a + bias_prefix(bias, d, k, j) * Gsum[k]);
+  }
+  double tail = (double)U[(int64_t)n * d + j] * Gsum[n];      // u_n G_n + sum over the layers above l
+  for (int l = n - 1; l >= 0; --l) {
+    dbias[(int64_t)l * d + j] = (float)tail;
+    tail += (double)U[(int64_t)l * d + j] * Gsum[l];
+  }
+}
+
 inline unsigned blocks_for(int64_t threads, int64_t cap) {
   int64_t g = (threads + kBlock - 1) / kBlock;
   return (unsigned)(g < 1 ? 1 : (g > cap ? cap : g));
@@ -314,6 +531,114 @@ des_status_t des_cross_partial_backward(const float *xl, const float *w, const f
   const dim3 grid((unsigned)((d4 + kBlock - 1) / kBlock), (unsigned)slices);
   hipLaunchKernelGGL(k_cross_subop_grad, grid, dim3(kBlock), 0, s, xl, w, g_s, B, d4, rows_per_slice, g_xl, partial);
   hipLaunchKernelGGL(k_cross_final, dim3(blocks_for(d, 1 << 20)), dim3(kBlock), 0, s, partial, slices, d, dw, (float *)nullptr);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+// ---- whole cross network ----
+struct NetLayout { size_t kappa, gsum, beta, gpart, partial, total; int slices; int64_t nblk; };
+static NetLayout net_layout(int64_t B, int64_t d, int n) {
+  const int m = n + 1;
+  const int64_t rows = B > 0 ? B : 1;
+  NetLayout L;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
+  L.nblk = (rows + kBlock - 1) / kBlock;
+  L.slices = cross_slices(rows, d);
+  L.kappa = take(kCrossNetMax * sizeof(double));
+  L.gsum = take(kCrossNetMax * sizeof(double));
+  L.beta = take((size_t)rows * m * sizeof(float));
+  L.gpart = take((size_t)L.nblk * m * sizeof(double));
+  L.partial = take((size_t)L.slices * m * (size_t)d * sizeof(double));
+  L.total = o;
+  return L;
+}
+
+des_status_t des_cross_net_bytes(int64_t B, int64_t d, int32_t n_layers, size_t *bytes) {
+  if (!bytes || B < 0 || d < 4 || (d & 3) || n_layers < 0 || n_layers + 1 > kCrossNetMax) return DES_ERR_INVALID_ARG;
+  *bytes = net_layout(B, d, n_layers).total;
+  return DES_OK;
+}
+
+des_status_t des_cross_net_partial(const float *x0, const float *U, int64_t B, int32_t F, int32_t D, int32_t m,
+                                   int32_t K, float *P, void *stream) {
+  if (B < 0 || F < 1 || D < 4 || (D & 3) || K < 1 || m < 1 || m > kCrossNetMax || (int64_t)F * D > (1ll << 30))
+    return DES_ERR_INVALID_ARG;
+  if (B == 0) return DES_OK;
+  if (!x0 || !U || !P || !aligned16(x0) || !aligned16(U)) return DES_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const int D4 = D / 4;
+  int G = 1;
+  while (G < 16 && G * 2 <= D4) G *= 2;
+  const unsigned grid = blocks_for(B * K * G, 1 << 20);
+  ProfScope ps(KID_CROSS_PARTIAL, s);
+#define DES_NET_PARTIAL(M) \
+  case M: hipLaunchKernelGGL(k_cross_net_partial<M>, dim3(grid), dim3(kBlock), 0, s, x0, U, B, F, D4, K, G, P); break
+  switch (m) {
+    DES_NET_PARTIAL(1); DES_NET_PARTIAL(2); DES_NET_PARTIAL(3); DES_NET_PARTIAL(4);
+    DES_NET_PARTIAL(5); DES_NET_PARTIAL(6); DES_NET_PARTIAL(7); DES_NET_PARTIAL(8);
+  }
+#undef DES_NET_PARTIAL
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+des_status_t des_cross_net_forward(const float *t, const float *U, const float *bias, int64_t B, int64_t d,
+                                   int32_t n_layers, float *gamma, float *c, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+  if (B < 0 || d < 4 || (d & 3) || n_layers < 0 || n_layers + 1 > kCrossNetMax) return DES_ERR_INVALID_ARG;
+  if (B == 0) return DES_OK;
+  if (!t || !U || (n_layers > 0 && !bias) || !gamma || !c) return DES_ERR_INVALID_ARG;
+  const NetLayout L = net_layout(B, d, n_layers);
+  if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & 255u)) return DES_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  double *kappa = (double *)((char *)workspace + L.kappa);
+  ProfScope ps(KID_CROSS_APPLY, s);
+  hipLaunchKernelGGL(k_cross_net_kappa, dim3(n_layers + 1), dim3(kBlock), 0, s, U, bias, d, kappa);
+  hipLaunchKernelGGL(k_cross_net_scalars, dim3(blocks_for(B, 1 << 30)), dim3(kBlock), 0, s, t, kappa, B, n_layers, gamma, c);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+}
+
+des_status_t des_cross_net_backward(const float *x0, const float *U, const float *bias, const float *t,
+                                    const float *gamma, const float *g, int64_t B, int64_t d, int32_t n_layers,
+                                    float *g_x0, int32_t accumulate_g_x0, float *dU, float *dbias, void *workspace,
+                                    size_t workspace_bytes, void *stream) {
+  if (B < 0 || d < 4 || (d & 3) || n_layers < 0 || n_layers + 1 > kCrossNetMax) return DES_ERR_INVALID_ARG;
+  if (!dU || (n_layers > 0 && (!dbias || !bias)) || !U) return DES_ERR_INVALID_ARG;
+  const NetLayout L = net_layout(B, d, n_layers);
+  if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & 255u)) return DES_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char *ws = (char *)workspace;
+  float *beta = (float *)(ws + L.beta);
+  double *gpart = (double *)(ws + L.gpart), *gsum = (double *)(ws + L.gsum), *partial = (double *)(ws + L.partial);
+  const int m = n_layers + 1;
+  const int64_t d4 = d / 4;
+  ProfScope ps(KID_CROSS_GRAD, s);
+  if (B == 0) {                                          // empty batch: every sum is zero
+    hipLaunchKernelGGL(k_cross_net_gsum, dim3(1), dim3(kWave), 0, s, gpart, (int64_t)0, m, gsum);
+    hipLaunchKernelGGL(k_cross_net_final, dim3(blocks_for(d, 1 << 20)), dim3(kBlock), 0, s, partial, 0, gsum, U, bias, d,
+                       n_layers, dU, dbias);
+    return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
+  }
+  if (!x0 || !t || !gamma || !g || !g_x0 || !aligned16(x0) || !aligned16(U) || !aligned16(g_x0)) return DES_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(k_cross_net_beta, dim3((unsigned)L.nblk), dim3(kBlock), 0, s, t, gamma, g, B, n_layers, beta, gpart);
+  hipLaunchKernelGGL(k_cross_net_gsum, dim3(1), dim3(kWave), 0, s, gpart, L.nblk, m, gsum);
+  const int64_t rows_per_slice = (B + L.slices - 1) / L.slices;
+  const dim3 grid((unsigned)((d4 + kBlock - 1) / kBlock), (unsigned)L.slices);
+#define DES_NET_GRAD(M)                                                                                                  \
+  case M:                                                                                                                \
+    if (accumulate_g_x0)                                                                                                 \
+      hipLaunchKernelGGL((k_cross_net_grad<M, true>), grid, dim3(kBlock), 0, s, x0, U, beta, B, d4, rows_per_slice, g_x0, \
+                         partial);                                                                                       \
+    else                                                                                                                 \
+      hipLaunchKernelGGL((k_cross_net_grad<M, false>), grid, dim3(kBlock), 0, s, x0, U, beta, B, d4, rows_per_slice,      \
+                         g_x0, partial);                                                                                 \
+    break
+  switch (m) {
+    DES_NET_GRAD(1); DES_NET_GRAD(2); DES_NET_GRAD(3); DES_NET_GRAD(4);
+    DES_NET_GRAD(5); DES_NET_GRAD(6); DES_NET_GRAD(7); DES_NET_GRAD(8);
+  }
+#undef DES_NET_GRAD
+  hipLaunchKernelGGL(k_cross_net_final, dim3(blocks_for(d, 1 << 20)), dim3(kBlock), 0, s, partial, L.slices, gsum, U, bias,
+                     d, n_layers, dU, dbias);
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
 }
 

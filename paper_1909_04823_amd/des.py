@@ -31,6 +31,7 @@ EXPORTS = [
     "des_batch_validate", "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
     "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
     "des_cross_partial", "des_cross_apply", "des_cross_backward_bytes", "des_cross_backward", "des_cross_partial_backward",
+    "des_cross_net_bytes", "des_cross_net_partial", "des_cross_net_forward", "des_cross_net_backward",
     "des_profile_enable", "des_profile_read", "des_status_string",
 ]
 
@@ -105,6 +106,10 @@ _sig = {
     "des_cross_backward_bytes": [i64, i64, C.POINTER(C.c_size_t)],
     "des_cross_backward": [vp, vp, vp, vp, vp, i64, i64, vp, vp, i32, vp, vp, vp, C.c_size_t, vp],
     "des_cross_partial_backward": [vp, vp, vp, i64, i64, vp, vp, vp, C.c_size_t, vp],
+    "des_cross_net_bytes": [i64, i64, i32, C.POINTER(C.c_size_t)],
+    "des_cross_net_partial": [vp, vp, i64, i32, i32, i32, i32, vp, vp],
+    "des_cross_net_forward": [vp, vp, vp, i64, i64, i32, vp, vp, vp, C.c_size_t, vp],
+    "des_cross_net_backward": [vp, vp, vp, vp, vp, vp, i64, i64, i32, vp, i32, vp, vp, vp, C.c_size_t, vp],
     "des_profile_enable": [i32],
     "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
 }
@@ -451,6 +456,45 @@ def cross_backward(x0: torch.Tensor, xl: torch.Tensor, w: torch.Tensor, s: torch
     _check(_lib.des_cross_backward(_ptr(x0), _ptr(xl), _ptr(w), _ptr(s), _ptr(g_y), B, d, _ptr(g_xl), _ptr(g_x0),
                                    int(accumulate_g_x0), _ptr(dw), _ptr(db), _ptr(workspace), _nbytes(workspace),
                                    _stream()), "des_cross_backward")
+
+
+def cross_net_bytes(B: int, d: int, n_layers: int) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.des_cross_net_bytes(B, d, n_layers, C.byref(n)), "des_cross_net_bytes")
+    return int(n.value)
+
+
+def cross_net_partial(x0: torch.Tensor, U: torch.Tensor, K: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """P[K,B,m]: per-shard dot products of x0 [B,F,D] with the m rows of U [m, F*D]."""
+    B, F, D = x0.shape
+    m = U.shape[0]
+    if U.shape[1] != F * D or not (x0.is_contiguous() and U.is_contiguous()):
+        raise ValueError("x0 must be contiguous [B,F,D] and U contiguous [m,F*D]")
+    if out is None:
+        out = torch.empty((K, B, m), dtype=torch.float32, device=x0.device)
+    _check(_lib.des_cross_net_partial(_ptr(x0), _ptr(U), B, F, D, m, K, _ptr(out), _stream()), "des_cross_net_partial")
+    return out
+
+
+def cross_net_forward(t: torch.Tensor, U: torch.Tensor, bias: Optional[torch.Tensor], gamma: torch.Tensor,
+                      c: torch.Tensor, workspace: torch.Tensor):
+    """gamma[B,m] and the logit term c[B] of the whole cross network from the aggregated dot products t[B,m]."""
+    B, m = t.shape
+    _check(_lib.des_cross_net_forward(_ptr(t), _ptr(U), _ptr(bias), B, U.shape[1], m - 1, _ptr(gamma), _ptr(c),
+                                      _ptr(workspace), _nbytes(workspace), _stream()), "des_cross_net_forward")
+
+
+def cross_net_backward(x0: torch.Tensor, U: torch.Tensor, bias: Optional[torch.Tensor], t: torch.Tensor,
+                       gamma: torch.Tensor, g: torch.Tensor, g_x0: torch.Tensor, accumulate_g_x0: bool,
+                       dU: torch.Tensor, dbias: Optional[torch.Tensor], workspace: torch.Tensor):
+    """Backward of the whole cross network for the gradient g[B] of its logit term."""
+    B = x0.shape[0]
+    m, d = U.shape
+    if x0.numel() != B * d or g_x0.numel() != B * d or tuple(t.shape) != (B, m) or tuple(gamma.shape) != (B, m):
+        raise ValueError("shape mismatch")
+    _check(_lib.des_cross_net_backward(_ptr(x0), _ptr(U), _ptr(bias), _ptr(t), _ptr(gamma), _ptr(g), B, d, m - 1,
+                                       _ptr(g_x0), int(accumulate_g_x0), _ptr(dU), _ptr(dbias), _ptr(workspace),
+                                       _nbytes(workspace), _stream()), "des_cross_net_backward")
 
 
 def aggregate_bias_act(P: torch.Tensor, bias: Optional[torch.Tensor], relu: bool,

@@ -222,3 +222,64 @@ def test_cross_layer_full_size_sampled(oracle, des, index):
     gy_cols = h(g_y.reshape(B, d)[:, jt]).astype(np.float64)
     assert_close(h(dw[jt]), (gs_all[:, None] * xl_cols).sum(axis=0), "dw columns")
     assert_close(h(db[jt]), gy_cols.sum(axis=0), "db columns")
+
+
+def oracle_cross_network(oracle, x0, U, bias, g, K):
+    """The network layer by layer with the oracle's functions (fp32 between the stages, as the layer-by-layer
+    library calls hand tensors on): forward scalars, logit term, and every gradient for the gradient g of the term."""
+    n = U.shape[0] - 1
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    xs, ss = [x0], []
+    for l in range(n):
+        s = f32(oracle.aggregate(oracle.cross_partial(xs[l], U[l], K)))
+        ss.append(s)
+        xs.append(f32(oracle.cross_apply(x0, xs[l], s, bias[l])))
+    c = oracle.aggregate(oracle.cross_partial(xs[n], U[n], K))
+    gx, dwc = oracle.cross_partial_backward(xs[n], U[n], g)
+    dU, db = np.zeros(U.shape), np.zeros((n,) + U.shape[1:])
+    dU[n] = dwc
+    g_x0 = np.zeros(x0.shape)
+    gx = f32(gx)
+    for l in range(n - 1, -1, -1):
+        _, g_xl, share, dU[l], db[l] = oracle.cross_backward(x0, xs[l], U[l], ss[l], gx)
+        g_x0 += share
+        gx = f32(g_xl)
+    g_x0 += gx
+    B = x0.shape[0]
+    gamma = 1.0 + np.concatenate([np.zeros((1, B)), np.cumsum(np.array(ss, np.float64).reshape(n, B), axis=0)]).T
+    return dict(c=c, gamma=gamma, g_x0=g_x0, dU=dU, db=db)
+
+
+@pytest.mark.parametrize("B,F,D,K,n", [(5, 2, 4, 2, 1), (300, 26, 16, 8, 2), (129, 7, 64, 4, 3), (64, 5, 32, 9, 0),
+                                       (1000, 3, 8, 1, 7), (40, 2, 256, 2, 2)])
+def test_whole_cross_network_matches_the_layer_by_layer_oracle(oracle, des, B, F, D, K, n):
+    import torch
+    d, m = F * D, n + 1
+    rng = np.random.default_rng(100 * B + n)
+    x0 = (0.3 * rng.standard_normal((B, F, D))).astype(np.float32)
+    U = (rng.standard_normal((m, d)) / np.sqrt(d)).astype(np.float32)
+    bias = (0.1 * rng.standard_normal((n, d))).astype(np.float32)
+    g = (0.05 * rng.standard_normal(B)).astype(np.float32)
+    before = (0.01 * rng.standard_normal((B, F, D))).astype(np.float32)
+    ref = oracle_cross_network(oracle, x0, U, bias, g, K)
+    t_ = lambda a: torch.from_numpy(a).cuda()
+    tx0, tU, tb = t_(x0), t_(U), (t_(bias) if n else None)
+    P = des.cross_net_partial(tx0, tU, K)
+    tt = des.aggregate_partials(P.view(K, B * m)).view(B, m)
+    ws = torch.empty(des.cross_net_bytes(B, d, n), dtype=torch.uint8, device="cuda")
+    gamma, c = torch.empty((B, m), device="cuda"), torch.empty(B, device="cuda")
+    des.cross_net_forward(tt, tU, tb, gamma, c, ws)
+    torch.cuda.synchronize()
+    for k in range(m):                                   # every dot product is the layer sub-operator applied to x0
+        assert_close(P[:, :, k].cpu().numpy(), oracle.cross_partial(x0, U[k], K), f"P of vector {k}")
+    assert_close(gamma.cpu().numpy(), ref["gamma"], "gamma")
+    assert_close(c.cpu().numpy(), ref["c"], "logit term")
+    for accumulate in (False, True):
+        g_x0 = t_(before.copy())
+        dU, db = torch.full((m, d), float("nan"), device="cuda"), (torch.full((n, d), float("nan"), device="cuda") if n else None)
+        des.cross_net_backward(tx0, tU, tb, tt, gamma, t_(g), g_x0, accumulate, dU, db, ws)
+        torch.cuda.synchronize()
+        assert_close(g_x0.cpu().numpy(), (before.astype(np.float64) if accumulate else 0.0) + ref["g_x0"], "g_x0")
+        assert_close(dU.cpu().numpy(), ref["dU"], "dU")
+        if n:
+            assert_close(db.cpu().numpy(), ref["db"], "dbias")
