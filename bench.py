@@ -266,6 +266,23 @@ def run_cross_layer(args, index):
         des.cross_apply(x0, xl, s, bias, out=y)
         des.cross_backward(x0, xl, wl, s, g_y, g_xl, g_x0, True, dw, db, ws)
 
+    # the whole network (n layers and the output unit's dot product) in its two-pass form
+    n = args.cross_layers
+    m = n + 1
+    U = torch.randn((m, d), device="cuda", generator=gen) / float(np.sqrt(d))
+    nb = torch.randn((n, d), device="cuda", generator=gen) * 0.1 if n else None
+    g = torch.randn(B, device="cuda", generator=gen) * 0.01
+    nP, nt, ngam, nc = torch.empty((K, B, m), device="cuda"), torch.empty((B, m), device="cuda"), \
+        torch.empty((B, m), device="cuda"), torch.empty(B, device="cuda")
+    dU, dB = torch.empty_like(U), (torch.empty_like(nb) if n else None)
+    nws = torch.empty(des.cross_net_bytes(B, d, n), dtype=torch.uint8, device="cuda")
+
+    def network():
+        des.cross_net_partial(x0, U, K, out=nP)
+        des.aggregate_partials(nP.view(K, -1), nt.view(-1))
+        des.cross_net_forward(nt, U, nb, ngam, nc, nws)
+        des.cross_net_backward(x0, U, nb, nt, ngam, g, g_x0, True, dU, dB, nws)
+
     reps = max(3, min(args.steps, 10))
     for _ in range(2):
         layer()
@@ -293,8 +310,34 @@ def run_cross_layer(args, index):
             e["frac_of_hbm_peak"] = round(e["GBps"] / HBM_PEAK_GBS, 4)
         kernels[name] = e
     assert bool(torch.isfinite(y).all()) and bool(torch.isfinite(dw).all())
+    for _ in range(2):
+        network()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        network()
+    torch.cuda.synchronize()
+    net_ms = 1e3 * (time.perf_counter() - t0) / reps
+    des.profile_enable(True)
+    for _ in range(reps):
+        network()
+    prof = des.profile_read()
+    des.profile_enable(False)
+    net_algo = {"cross_partial": arr + 4.0 * m * d + 4.0 * K * B * m, "cross_backward": 3 * arr + 8.0 * m * d + 8.0 * B * m}
+    net_kernels = {}
+    for name, (launches, total_ms) in prof.items():
+        per = total_ms / reps
+        e = {"launches_per_pass": launches / reps, "ms_per_pass": round(per, 4)}
+        if name in net_algo and per > 0:
+            e["algorithmic_GB"] = round(net_algo[name] / 1e9, 3)
+            e["GBps"] = round(net_algo[name] / (per * 1e-3) / 1e9, 1)
+            e["frac_of_hbm_peak"] = round(e["GBps"] / HBM_PEAK_GBS, 4)
+        net_kernels[name] = e
+    assert bool(torch.isfinite(nc).all()) and bool(torch.isfinite(dU).all())
     return {"workload": f"configs[{w.index}] {w.name}", "B": B, "F": F, "D": D, "d": d, "K": K, "dtype": "f32",
-            "ms_per_pass": round(ms, 4), "peak_GBps": HBM_PEAK_GBS, "kernels": kernels}
+            "peak_GBps": HBM_PEAK_GBS,
+            "one_layer": {"ms_per_pass": round(ms, 4), "kernels": kernels},
+            "whole_network": {"layers": n, "ms_per_pass": round(net_ms, 4), "kernels": net_kernels}}
 
 
 def run_workload(args, index, cpu):

@@ -192,6 +192,7 @@ __global__ __launch_bounds__(kBlock) void k_cross_final(const double *__restrict
   const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= (db ? 2 * d : d)) return;
   double a = 0.0;
+#pragma unroll 8
   for (int sl = 0; sl < slices; ++sl) a += partial[(int64_t)sl * 2 * d + j];
   if (j < d) dw[j] = (float)a; else db[j - d] = (float)a;
 }
@@ -213,7 +214,9 @@ __global__ __launch_bounds__(kBlock) void k_cross_final(const double *__restrict
 // which is a second pass over x_0 fused with the update of x_0's gradient.
 constexpr int kCrossNetMax = 8;        // most vectors u_k (seven layers and the output unit's)
 
-// P[s,b,k] = sum over the columns j of shard s of x0[b,j] * U[k,j]; a group of G lanes per (sample, shard).
+// P[s,b,k] = sum over the columns j of shard s of x0[b,j] * U[k,j]; a group of G lanes per (kNetRows samples,
+// shard), so that every float4 of U fetched from the caches serves several samples.
+constexpr int kNetRows = 4;
 template <int M>
 __global__ __launch_bounds__(kBlock) void k_cross_net_partial(const float *__restrict__ x0, const float *__restrict__ U,
                                                                int64_t B, int F, int D4, int K, int G,
@@ -222,33 +225,45 @@ __global__ __launch_bounds__(kBlock) void k_cross_net_partial(const float *__res
   const int t = threadIdx.x % G;
   const int64_t stride = (int64_t)gridDim.x * kBlock / G;
   const int64_t row4 = (int64_t)F * D4;
-  for (int64_t item = gid; item < B * K; item += stride) {
-    const int64_t b = item / K;
+  const int64_t n_items = ((B + kNetRows - 1) / kNetRows) * K;
+  for (int64_t item = gid; item < n_items; item += stride) {
+    const int64_t b0 = (item / K) * kNetRows;
     const int s = (int)(item % K);
     const int nf = s < F ? (F - s + K - 1) / K : 0;
     const int m_end = nf * D4;
-    double acc[M];
+    double acc[kNetRows][M];
 #pragma unroll
-    for (int k = 0; k < M; ++k) acc[k] = 0.0;
-#pragma unroll 2
+    for (int r = 0; r < kNetRows; ++r)
+#pragma unroll
+      for (int k = 0; k < M; ++k) acc[r][k] = 0.0;
     for (int i = t; i < m_end; i += G) {
       const int f = s + K * (i / D4);
       const int64_t q = (int64_t)f * D4 + (i % D4);
-      const float4 xv = reinterpret_cast<const float4 *>(x0)[b * row4 + q];
+      float4 xv[kNetRows];
+#pragma unroll
+      for (int r = 0; r < kNetRows; ++r)
+        xv[r] = reinterpret_cast<const float4 *>(x0)[min(b0 + r, B - 1) * row4 + q];
 #pragma unroll
       for (int k = 0; k < M; ++k) {
         const float4 uv = reinterpret_cast<const float4 *>(U)[k * row4 + q];
-        acc[k] += ((double)xv.x * (double)uv.x + (double)xv.y * (double)uv.y) +
-                  ((double)xv.z * (double)uv.z + (double)xv.w * (double)uv.w);
+        const double ux = (double)uv.x, uy = (double)uv.y, uz = (double)uv.z, uw = (double)uv.w;
+#pragma unroll
+        for (int r = 0; r < kNetRows; ++r)
+          acc[r][k] += ((double)xv[r].x * ux + (double)xv[r].y * uy) + ((double)xv[r].z * uz + (double)xv[r].w * uw);
       }
     }
     for (int o = G / 2; o > 0; o >>= 1) {
 #pragma unroll
-      for (int k = 0; k < M; ++k) acc[k] += __shfl_xor(acc[k], o, kWave);
+      for (int r = 0; r < kNetRows; ++r)
+#pragma unroll
+        for (int k = 0; k < M; ++k) acc[r][k] += __shfl_xor(acc[r][k], o, kWave);
     }
     if (t == 0) {
 #pragma unroll
-      for (int k = 0; k < M; ++k) P[((int64_t)s * B + b) * M + k] = (float)acc[k];
+      for (int r = 0; r < kNetRows; ++r)
+        if (b0 + r < B)
+#pragma unroll
+          for (int k = 0; k < M; ++k) P[((int64_t)s * B + b0 + r) * M + k] = (float)acc[r][k];
     }
   }
 }
@@ -335,13 +350,17 @@ __global__ __launch_bounds__(kBlock) void k_cross_net_beta(const float *__restri
   }
 }
 
-// Gsum[k] = sum over the workgroups' partials, in order; one thread per k.
-__global__ void k_cross_net_gsum(const double *__restrict__ Gpart, int64_t nblk, int m, double *__restrict__ Gsum) {
-  const int k = threadIdx.x;
-  if (k >= m) return;
+// Gsum[k] = sum over the workgroups' partials: one wave per k, lane i adds the partials i, i+64, ... in order,
+// an xor tree adds the lanes.
+__global__ __launch_bounds__(kWave) void k_cross_net_gsum(const double *__restrict__ Gpart, int64_t nblk, int m,
+                                                           double *__restrict__ Gsum) {
+  const int k = blockIdx.x;
   double a = 0.0;
-  for (int64_t i = 0; i < nblk; ++i) a += Gpart[i * m + k];
-  Gsum[k] = a;
+#pragma unroll 4
+  for (int64_t i = threadIdx.x; i < nblk; i += kWave) a += Gpart[i * m + k];
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) a += __shfl_xor(a, o, kWave);
+  if (threadIdx.x == 0) Gsum[k] = a;
 }
 
 // The pass over x0 of the backward: g_x0[b,j] (+)= sum_k beta[b,k] U[k,j] and the slice's part of
@@ -362,7 +381,7 @@ __global__ __launch_bounds__(kBlock) void k_cross_net_grad(const float *__restri
     u[k] = reinterpret_cast<const float4 *>(U)[k * d4 + q];
     S[k][0] = S[k][1] = S[k][2] = S[k][3] = 0.0;
   }
-  constexpr int UR = 2;
+  constexpr int UR = 4;
   for (int64_t r = r0; r < r1; r += UR) {
     float4 x[UR], old[UR];
 #pragma unroll
@@ -403,6 +422,7 @@ __global__ __launch_bounds__(kBlock) void k_cross_net_final(const double *__rest
   const int m = n + 1;
   for (int k = 0; k < m; ++k) {
     double a = 0.0;
+#pragma unroll 8
     for (int sl = 0; sl < slices; ++sl) a += partial[((int64_t)sl * m + k) * d + j];
     dU[(int64_t)k * d + j] = (float)(a + bias_prefix(bias, d, k, j) * Gsum[k]);
   }
@@ -569,7 +589,7 @@ des_status_t des_cross_net_partial(const float *x0, const float *U, int64_t B, i
   const int D4 = D / 4;
   int G = 1;
   while (G < 16 && G * 2 <= D4) G *= 2;
-  const unsigned grid = blocks_for(B * K * G, 1 << 20);
+  const unsigned grid = blocks_for((B + kNetRows - 1) / kNetRows * K * G, 1 << 20);
   ProfScope ps(KID_CROSS_PARTIAL, s);
 #define DES_NET_PARTIAL(M) \
   case M: hipLaunchKernelGGL(k_cross_net_partial<M>, dim3(grid), dim3(kBlock), 0, s, x0, U, B, F, D4, K, G, P); break
@@ -613,14 +633,14 @@ des_status_t des_cross_net_backward(const float *x0, const float *U, const float
   const int64_t d4 = d / 4;
   ProfScope ps(KID_CROSS_GRAD, s);
   if (B == 0) {                                          // empty batch: every sum is zero
-    hipLaunchKernelGGL(k_cross_net_gsum, dim3(1), dim3(kWave), 0, s, gpart, (int64_t)0, m, gsum);
+    hipLaunchKernelGGL(k_cross_net_gsum, dim3(m), dim3(kWave), 0, s, gpart, (int64_t)0, m, gsum);
     hipLaunchKernelGGL(k_cross_net_final, dim3(blocks_for(d, 1 << 20)), dim3(kBlock), 0, s, partial, 0, gsum, U, bias, d,
                        n_layers, dU, dbias);
     return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
   }
   if (!x0 || !t || !gamma || !g || !g_x0 || !aligned16(x0) || !aligned16(U) || !aligned16(g_x0)) return DES_ERR_INVALID_ARG;
   hipLaunchKernelGGL(k_cross_net_beta, dim3((unsigned)L.nblk), dim3(kBlock), 0, s, t, gamma, g, B, n_layers, beta, gpart);
-  hipLaunchKernelGGL(k_cross_net_gsum, dim3(1), dim3(kWave), 0, s, gpart, L.nblk, m, gsum);
+  hipLaunchKernelGGL(k_cross_net_gsum, dim3(m), dim3(kWave), 0, s, gpart, L.nblk, m, gsum);
   const int64_t rows_per_slice = (B + L.slices - 1) / L.slices;
   const dim3 grid((unsigned)((d4 + kBlock - 1) / kBlock), (unsigned)L.slices);
 #define DES_NET_GRAD(M)                                                                                                  \

@@ -14,6 +14,9 @@ dot product over the d = F*D columns, the output unit's on the network's result 
 sub-operator (per-shard scalars, summed):
 
     pool -> [cross_partial -> aggregate -> cross_apply] x n -> cross_partial -> aggregate  (one logit term)
+
+or, by default, all of them at once (cross_net_partial -> aggregate -> cross_net_forward): the layers only ever
+add multiples of x_0 and biases, so the network needs one pass over x_0 for all its dot products.
 """
 from __future__ import annotations
 
@@ -30,7 +33,7 @@ COMPONENTS = {"lr": ("lr",), "fm": ("lr", "fm"), "wd": ("lr", "dnn"), "deepfm": 
 
 class Model:
     def __init__(self, table: des.Table, F: int, kind: str, tower: Optional[Dict[str, np.ndarray]], B_max: int,
-                 opt_sparse: dict, opt_dense: dict):
+                 opt_sparse: dict, opt_dense: dict, cross_fused: bool = True):
         """`table`: a des.Table whose state arrays fit `opt_sparse`; `tower`: initial dense parameters as numpy
         arrays -- W1[F*D,H1], b1[H1] (the layer under DES), W2[H1,H2], b2, ... Wn, bn (n >= 1 hidden layers),
         w_out[Hn], b0[1]; for "dcn" also cw1[d], cb1[d], ... (cross layers) and w_cross[d]; opt_*:
@@ -52,8 +55,22 @@ class Model:
         self.rows = torch.empty(table.max_n, dtype=torch.int32, device=dev)
         self.dnn = "dnn" in self.parts
         H_max = 4
+        self.grads = {}
         if self.dnn:
             self.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(dev) for k, v in tower.items()}
+            if "cross" in self.parts:
+                # the cross network's vectors side by side, U = [cw1 .. cwn, w_cross] and bias = [cb1 .. cbn]; the
+                # per-parameter tensors are rows of these blocks, and so are their gradients
+                n_cross = sum(1 for k in self.params if k.startswith("cw"))
+                names = [f"cw{l + 1}" for l in range(n_cross)] + ["w_cross"]
+                self.cU = torch.stack([self.params[k] for k in names]).contiguous()
+                self.cB = torch.stack([self.params[f"cb{l + 1}"] for l in range(n_cross)]).contiguous() if n_cross else None
+                self.dU = torch.empty_like(self.cU)
+                self.dB = torch.empty_like(self.cB) if n_cross else None
+                for i, k in enumerate(names):
+                    self.params[k], self.grads[k] = self.cU[i], self.dU[i]
+                for l in range(n_cross):
+                    self.params[f"cb{l + 1}"], self.grads[f"cb{l + 1}"] = self.cB[l], self.dB[l]
             self.n_layers = sum(1 for k in self.params if k[0] == "W")
             self.H = [self.params[f"W{i + 1}"].shape[1] for i in range(self.n_layers)]       # widths H1..Hn
             H_max = max(self.H)
@@ -70,15 +87,23 @@ class Model:
             if self.cross:
                 d = F * D
                 self.n_cross = sum(1 for k in self.params if k.startswith("cw"))
-                self.xs = [self.pool] + [f(B, F, D) for _ in range(self.n_cross)]      # inputs of the cross layers, result
+                self.cross_fused = bool(cross_fused)
                 self.cs = [f(B) for _ in range(self.n_cross + 1)]                       # aggregated scalars; last: logit term
-                self.cP = f(K, B)
-                self.g_x = f(B, F, D)
-                self.cross_ws = torch.empty(des.cross_backward_bytes(B, d), dtype=torch.uint8, device=dev)
+                if self.cross_fused:
+                    m = self.n_cross + 1
+                    self.cP, self.ct, self.cgamma = f(K, B, m), f(B, m), f(B, m)
+                    self.cross_ws = torch.empty(des.cross_net_bytes(B, d, self.n_cross), dtype=torch.uint8, device=dev)
+                else:
+                    self.xs = [self.pool] + [f(B, F, D) for _ in range(self.n_cross)]  # inputs of the cross layers, result
+                    self.cP = f(K, B)
+                    self.g_x = f(B, F, D)
+                    self.cross_ws = torch.empty(des.cross_backward_bytes(B, d), dtype=torch.uint8, device=dev)
         else:
             self.cross = False
             self.params = {"b0": torch.from_numpy(np.ascontiguousarray(tower["b0"] if tower else np.zeros(1), dtype=np.float32)).to(dev)}
-        self.grads = {k: torch.empty_like(v) for k, v in self.params.items()}
+        for k, v in self.params.items():
+            if k not in self.grads:
+                self.grads[k] = torch.empty_like(v)
         self.s1 = {k: torch.zeros_like(v) for k, v in self.params.items()}
         self.s2 = {k: torch.zeros_like(v) for k, v in self.params.items()}
         self.ws = torch.empty(des.dense_workspace_bytes(H_max), dtype=torch.uint8, device=dev)
@@ -103,7 +128,11 @@ class Model:
                 des.dnn_partial_forward(x, p[f"W{i + 1}"], self.K if i == 0 else 1, out=self.Yp[i])
                 des.aggregate_bias_act(self.Yp[i], p[f"b{i + 1}"], True, self.a[i])
                 x = self.a[i].view(B, 1, self.H[i])
-        if self.cross:
+        if self.cross and self.cross_fused:
+            des.cross_net_partial(self.pool, self.cU, self.K, out=self.cP)
+            des.aggregate_partials(self.cP.view(self.K, -1), self.ct.view(-1))
+            des.cross_net_forward(self.ct, self.cU, self.cB, self.cgamma, self.cs[-1], self.cross_ws)
+        elif self.cross:
             for l in range(self.n_cross):
                 des.cross_partial(self.xs[l], p[f"cw{l + 1}"], self.K, out=self.cP)
                 des.aggregate_partials(self.cP, self.cs[l])
@@ -138,7 +167,11 @@ class Model:
                                      self.da[i - 1].view(B, 1, self.H[i - 1]), g[f"W{i + 1}"], self.dnn_ws)
                 else:
                     des.dnn_backward(self.pool, p["W1"], self.da[0], self.g_pool, g["W1"], self.dnn_ws)
-        if self.cross:
+        if self.cross and self.cross_fused:
+            # added to what the tower left in g_pool
+            des.cross_net_backward(self.pool, self.cU, self.cB, self.ct, self.cgamma, self.g_logit, self.g_pool, True,
+                                   self.dU, self.dB, self.cross_ws)
+        elif self.cross:
             # the cross network's result is a term of the logit; then layer by layer, every layer adding its share of
             # the gradient of x0 = pool to what the tower left in g_pool (the first layer's input gradient too)
             des.cross_partial_backward(self.xs[-1], p["w_cross"], self.g_logit, self.g_x, g["w_cross"], self.cross_ws)

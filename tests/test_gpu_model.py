@@ -115,7 +115,8 @@ SETTINGS = {
 @pytest.mark.parametrize("kind,setting,hidden", [("lr", "sgd", (64, 32)), ("fm", "sgd", (64, 32)), ("wd", "sgd", (64, 32)),
                                                  ("deepfm", "sgd", (64, 32)), ("deepfm", "paper", (64, 32)),
                                                  ("deepfm", "sgd", (48,)), ("wd", "paper", (64, 32, 16)),
-                                                 ("dcn", "sgd", (64, 32)), ("dcn", "paper", (48,))])
+                                                 ("dcn", "sgd", (64, 32)), ("dcn", "paper", (48,)),
+                                                 ("dcn-layer-by-layer", "sgd", (48,))])
 def test_training_steps_match_oracle_chain(oracle, des, kind, setting, hidden):
     """Three training steps of the whole model on a shrunken Criteo-shaped workload, library calls
     against the oracle's functions chained in the same order.  Each step is compared from a common
@@ -127,6 +128,8 @@ def test_training_steps_match_oracle_chain(oracle, des, kind, setting, hidden):
     import torch
     from _oracle_model import OracleModel
     from paper_1909_04823_amd.model import Model
+    cross_fused = kind != "dcn-layer-by-layer"             # the cross network in one piece, or call by call
+    kind = kind.split("-")[0]
     w = synth.workload(1, scale=1 / 16)
     opt_sparse, opt_dense, state_arrays = SETTINGS[setting]
     tower = synth.tower_init(w.seed, w.F, w.D, hidden=hidden)
@@ -140,7 +143,7 @@ def test_training_steps_match_oracle_chain(oracle, des, kind, setting, hidden):
                    max_n=1 << 17, state_arrays=state_arrays)
     gt.insert(dev(keys0, torch), dev(vals0, torch))
     om = OracleModel(oracle, ot, w.F, w.K, kind, tower, opt_sparse, opt_dense)
-    gm = Model(gt, w.F, kind, tower, w.B, opt_sparse, opt_dense)
+    gm = Model(gt, w.F, kind, tower, w.B, opt_sparse, opt_dense, cross_fused=cross_fused)
     names = [("emb", "emb"), ("w", "w"), ("acc_emb", "acc_emb"), ("acc2_emb", "acc2_emb"), ("acc_w", "acc_w"),
              ("acc2_w", "acc2_w")]
     try:
