@@ -195,8 +195,9 @@ def test_training_steps_match_oracle_chain(oracle, des, kind, setting, hidden):
         gt.close(); ot.close()
 
 
-def test_deepfm_learns_planted_labels(des):
-    """Sixty steps of DeepFM (Adagrad) on fresh batches whose labels depend on the IDs: predictions are
+@pytest.mark.parametrize("kind", ["deepfm", "dcn"])
+def test_model_learns_planted_labels(des, kind):
+    """Sixty steps of DeepFM / DCN (Adagrad) on fresh batches whose labels depend on the IDs: predictions are
     made before each batch's update, so they are held-out; over the last ten batches their AUC is well
     above chance and the mean log-loss is below that of a constant predictor at the base rate (0.613)."""
     import torch
@@ -205,7 +206,10 @@ def test_deepfm_learns_planted_labels(des):
     gt = des.Table(w.D, w.capacity, num_shards=w.K, opt=des.OPT_ADAGRAD, init_seed=w.seed, init_scale=w.init_std,
                    max_n=1 << 18)
     gt.insert(dev(synth.preinsert_keys(w), torch))
-    m = Model(gt, w.F, "deepfm", synth.tower_init(1, w.F, w.D, hidden=(64, 32)), w.B,
+    tower = synth.tower_init(1, w.F, w.D, hidden=(64, 32))
+    if kind == "dcn":
+        tower.update(synth.cross_init(1, w.F, w.D, n_cross=2))
+    m = Model(gt, w.F, kind, tower, w.B,
               dict(opt_emb=2, opt_w=2, lr=0.01, eps=1e-8), dict(opt_emb=2, lr=0.005, eps=1e-8))
     losses, aucs = [], []
     try:
@@ -215,7 +219,7 @@ def test_deepfm_learns_planted_labels(des):
             loss = m.train_step(des.Batch.from_numpy(batch), dev(labels, torch), insert=False)   # unseen IDs are skipped
             losses.append(float(loss.item()))
             aucs.append(auc(labels, m.p.cpu().numpy()))
-        print("loss", np.round(losses[::10], 4), "auc", np.round(aucs[::10], 3), "last ten: loss",
+        print(kind, "loss", np.round(losses[::10], 4), "auc", np.round(aucs[::10], 3), "last ten: loss",
               round(float(np.mean(losses[-10:])), 4), "auc", round(float(np.mean(aucs[-10:])), 4), flush=True)
         assert gt.status() == 0 and all(np.isfinite(losses))
         assert np.mean(aucs[-10:]) > 0.6, aucs
