@@ -155,6 +155,8 @@ def main():
     ap.add_argument("--cross-layers", type=int, default=2, help="cross layers of --model dcn")
     ap.add_argument("--no-cross", action="store_true",
                     help="skip the DCN cross layer timed at the main workload's shape (reported under \"cross_layer\")")
+    ap.add_argument("--no-compact", action="store_true",
+                    help="skip the in-place eviction of half of the main workload's rows, timed last (\"table_compact\")")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -552,6 +554,8 @@ def run_workload(args, index, cpu):
         out["model_step"] = model_res
     if migrate_res is not None:
         out["table_migrate"] = migrate_res
+    if index == args.config and not args.no_compact:
+        out["table_compact"] = run_compact(w, table, state_bytes_per_row)     # last: it drops half of the rows
     table.close()
     del table, batches
     return out
@@ -579,6 +583,27 @@ def run_migrate(w, table, opt, state_bytes_per_row):
     torch.cuda.empty_cache()
     assert ok
     nbytes = n * 1 + kept * (2 * state_bytes_per_row + 16)
+    return {"rows": n, "kept": kept, "ms": round(1e3 * dt, 3), "algorithmic_GBps": round(nbytes / dt / 1e9, 1)}
+
+
+def run_compact(w, table, state_bytes_per_row):
+    """Eviction of a seeded random half of the rows inside the table (des_table_compact, 1 GiB staging buffer),
+    timed on the host around the call, which synchronises.  Bytes: every kept row read and written twice (through
+    the staging buffer), one flag byte per row, the slot array cleared and one slot written per kept row."""
+    import torch
+    n = table.size()
+    gen = torch.Generator(device="cuda"); gen.manual_seed(17)
+    keep = (torch.rand(n, device="cuda", generator=gen) < 0.5).to(torch.uint8)
+    staging = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    want = int(keep.sum().item())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    kept = table.compact(keep, staging)
+    dt = time.perf_counter() - t0
+    assert table.status() == 0 and table.size() == kept == want
+    del staging, keep
+    torch.cuda.empty_cache()
+    nbytes = n * 1 + kept * (4 * state_bytes_per_row + 16) + table.slots.numel()
     return {"rows": n, "kept": kept, "ms": round(1e3 * dt, 3), "algorithmic_GBps": round(nbytes / dt / 1e9, 1)}
 
 

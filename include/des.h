@@ -147,6 +147,18 @@ des_status_t des_table_migrate_bytes(int64_t n_rows, size_t *workspace_bytes);
 des_status_t des_table_migrate(des_table_t *src, const uint8_t *keep, des_table_t *dst, const uint32_t *src_aux,
                                uint32_t *dst_aux, int64_t *n_rows_out, void *stream);
 
+/* The same eviction inside one table, for tables too large for a second copy: the rows r with
+ * keep[r] != 0 close up towards row 0 in ascending order (row i afterwards is the i-th kept row, with its
+ * key, weights and every state array; `aux`, if not null, is moved along), the row count drops to the
+ * number kept and the hash slots are rebuilt.  The result equals des_table_migrate into an empty table of
+ * the same capacity.  The arrays are walked in chunks through `staging` (device, 16-byte aligned; any size
+ * from 4096 * dim * 4 bytes up; larger means fewer launches), the row numbering uses the table's own
+ * workspace (8 bytes per row; DES_ERR_WORKSPACE if it is smaller).  keep == NULL keeps everything and is
+ * a no-op.  Synchronises with the host like des_table_migrate; n_rows_out (host, may be null) receives the
+ * new row count.  Rows found before the call are stale afterwards. */
+des_status_t des_table_compact(des_table_t *t, const uint8_t *keep, uint32_t *aux, void *staging, size_t staging_bytes,
+                               int64_t *n_rows_out, void *stream);
+
 /* Helpers for a least-recently-seen eviction policy.  last_seen: device, one uint32 per row, owned
  * and zero-initialised by the caller.  mark_seen: last_seen[rows[e]] = stamp for every e < n with
  * rows[e] >= 0 (rows as written by des_table_find).  select_recent: keep[r] = last_seen[r] >= min_stamp

@@ -5,6 +5,11 @@
 // keys: flags -> exclusive prefix sum (new row numbers) -> coalesced row copy -> parallel re-insert.
 // A maintenance operation, not part of the training step: it synchronises with the host twice to
 // size its launches and to refuse a target that is too small before anything is written.
+//
+// des_table_compact is the same eviction inside one table, for tables too large for a second copy: the kept
+// rows close up towards row 0.  A kept row never moves up, so the arrays are walked in ascending chunks of
+// rows: the kept rows of a chunk are gathered into a staging buffer and then stored at their new place, which
+// lies at or below the chunk and holds only rows that have already been moved or dropped.
 #include "des_internal.h"
 
 namespace des {
@@ -86,6 +91,59 @@ __global__ __launch_bounds__(kBlock) void k_rehash(Slot *__restrict__ slots, uin
 }
 
 __global__ void k_set_rows(Ctrl *ctrl, long long n) { ctrl->n_rows = n; }
+
+// In-place compaction of one per-row array of `upr` units of type T per row, rows [c0, c1).
+// new_row: exclusive prefix sum of the keep flags over all n rows, new_row[n] = number of kept rows.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_compact_gather(const T *__restrict__ arr, int upr,
+                                                            const uint8_t *__restrict__ keep,
+                                                            const unsigned long long *__restrict__ new_row, int64_t c0,
+                                                            int64_t c1, T *__restrict__ staging) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t r = c0 + gid / upr;
+  const int u = (int)(gid % upr);
+  if (r >= c1 || !keep[r]) return;
+  staging[(int64_t)(new_row[r] - new_row[c0]) * upr + u] = arr[r * upr + u];
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_compact_store(T *__restrict__ arr, int upr,
+                                                           const unsigned long long *__restrict__ new_row, int64_t c0,
+                                                           int64_t c1, const T *__restrict__ staging) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t i = gid / upr;
+  const int u = (int)(gid % upr);
+  const int64_t first = (int64_t)new_row[c0], kept = (int64_t)new_row[c1] - first;
+  if (i >= kept) return;
+  arr[(first + i) * upr + u] = staging[i * upr + u];
+}
+
+__global__ void k_take_rows(Ctrl *ctrl, const unsigned long long *total) { ctrl->n_rows = (long long)*total; }
+
+__global__ void k_fill_words(uint32_t *p, int64_t n, uint32_t v) {
+  for (int64_t i = threadIdx.x; i < n; i += blockDim.x) p[i] = v;
+}
+
+// empty slot = all-ones key, row -1: one 16-byte pattern of 0xFF
+__global__ __launch_bounds__(kBlock) void k_fill_slots(uint4 *__restrict__ p, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const uint4 ones = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = ones;
+}
+
+template <typename T>
+void compact_array(T *arr, int upr, const uint8_t *keep, const unsigned long long *new_row, int64_t n, void *staging,
+                   size_t staging_bytes, hipStream_t s) {
+  if (!arr) return;
+  const int64_t chunk = (int64_t)(staging_bytes / ((size_t)upr * sizeof(T)));
+  for (int64_t c0 = 0; c0 < n; c0 += chunk) {
+    const int64_t c1 = c0 + chunk < n ? c0 + chunk : n;
+    const unsigned grid = (unsigned)(((c1 - c0) * upr + kBlock - 1) / kBlock);
+    hipLaunchKernelGGL(k_compact_gather<T>, dim3(grid), dim3(kBlock), 0, s, (const T *)arr, upr, keep, new_row, c0, c1,
+                       (T *)staging);
+    hipLaunchKernelGGL(k_compact_store<T>, dim3(grid), dim3(kBlock), 0, s, arr, upr, new_row, c0, c1, (const T *)staging);
+  }
+}
 
 __global__ __launch_bounds__(kBlock) void k_mark_seen(const int32_t *__restrict__ rows, int64_t n, uint32_t stamp,
                                                        uint32_t *__restrict__ last_seen) {
@@ -200,6 +258,54 @@ des_status_t des_table_migrate(des_table_t *src, const uint8_t *keep, des_table_
   if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return DES_ERR_DEVICE;
   if (n_rows_out) *n_rows_out = kept;
   return (des_status_t)des_table_status(dst);
+}
+
+des_status_t des_table_compact(des_table_t *t, const uint8_t *keep, uint32_t *aux, void *staging, size_t staging_bytes,
+                               int64_t *n_rows_out, void *stream) {
+  if (!t || ((uintptr_t)aux & 3u)) return DES_ERR_INVALID_ARG;
+  const des_table_config_t &c = t->cfg;
+  hipStream_t s = (hipStream_t)stream;
+  int64_t n = 0;
+  des_status_t st = des_table_size(t, &n);
+  if (st != DES_OK) return st;
+  if (des_table_status(t) != DES_OK) return DES_ERR_INVALID_ARG;
+  if (n_rows_out) *n_rows_out = n;
+  t->last_stream = s;
+  t->prep.valid = false;
+  if (n == 0 || !keep) return DES_OK;                       // nothing to drop
+  // the staging buffer holds at least 4096 rows of the widest array at a time
+  if (!staging || ((uintptr_t)staging & 15u) || staging_bytes < (size_t)4096 * (size_t)c.dim * 4) return DES_ERR_WORKSPACE;
+  const size_t flags_bytes = align_up((size_t)(n + 1) * 8, 256);
+  if (t->ws_bytes < flags_bytes + scan_scratch_bytes(n + 1)) return DES_ERR_WORKSPACE;
+  unsigned long long *flags = (unsigned long long *)t->ws;
+  void *scan_scratch = t->ws + flags_bytes;
+  ProfScope ps(KID_MIGRATE, s);
+  // n + 1 values with a zero at the end: after the scan flags[n] is the number of kept rows
+  hipLaunchKernelGGL(k_keep_flags, dim3(blocks_for(n)), dim3(kBlock), 0, s, keep, n, flags);
+  hipLaunchKernelGGL(k_fill_words, dim3(1), dim3(kWave), 0, s, (uint32_t *)(flags + n), (int64_t)2, 0u);
+  exclusive_scan_u64(flags, n + 1, nullptr, scan_scratch, s);
+  compact_array<float4>((float4 *)c.emb, c.dim / 4, keep, flags, n, staging, staging_bytes, s);
+  compact_array<float4>((float4 *)c.acc_emb, c.dim / 4, keep, flags, n, staging, staging_bytes, s);
+  compact_array<float4>((float4 *)c.acc2_emb, c.dim / 4, keep, flags, n, staging, staging_bytes, s);
+  compact_array<uint32_t>((uint32_t *)c.w, 1, keep, flags, n, staging, staging_bytes, s);
+  compact_array<uint32_t>((uint32_t *)c.acc_w, 1, keep, flags, n, staging, staging_bytes, s);
+  compact_array<uint32_t>((uint32_t *)c.acc2_w, 1, keep, flags, n, staging, staging_bytes, s);
+  compact_array<uint32_t>(aux, 1, keep, flags, n, staging, staging_bytes, s);
+  compact_array<unsigned long long>((unsigned long long *)c.row_keys, 1, keep, flags, n, staging, staging_bytes, s);
+  hipLaunchKernelGGL(k_take_rows, dim3(1), dim3(1), 0, s, t->ctrl, (const unsigned long long *)(flags + n));
+  long long kept = 0;
+  if (hipMemcpyAsync(&kept, flags + n, sizeof(kept), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return DES_ERR_DEVICE;
+  // the slots are rebuilt from the kept keys
+  hipLaunchKernelGGL(k_fill_slots, dim3(blocks_for((int64_t)t->n_slots, 1 << 16)), dim3(kBlock), 0, s, (uint4 *)t->slots,
+                     (int64_t)t->n_slots);
+  if (kept > 0)
+    hipLaunchKernelGGL(k_rehash, dim3(blocks_for(kept, 1 << 16)), dim3(kBlock), 0, s, t->slots, t->n_slots - 1,
+                       (const uint64_t *)c.row_keys, (int64_t)kept, t->ctrl);
+  if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return DES_ERR_DEVICE;
+  if (n_rows_out) *n_rows_out = kept;
+  return (des_status_t)des_table_status(t);
 }
 
 des_status_t des_batch_validate(des_table_t *t, const des_batch_t *batch, const int32_t *rows, int64_t *first_bad,

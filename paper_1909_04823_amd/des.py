@@ -28,7 +28,7 @@ EXPORTS = [
     "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_aggregate_forward", "des_fm_finalize",
     "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge", "des_backward_prepare",
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
-    "des_batch_validate", "des_table_migrate_bytes", "des_table_migrate", "des_table_mark_seen", "des_table_select_recent",
+    "des_batch_validate", "des_table_migrate_bytes", "des_table_migrate", "des_table_compact", "des_table_mark_seen", "des_table_select_recent",
     "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
     "des_cross_partial", "des_cross_apply", "des_cross_backward_bytes", "des_cross_backward", "des_cross_partial_backward",
     "des_cross_net_bytes", "des_cross_net_partial", "des_cross_net_forward", "des_cross_net_backward",
@@ -99,6 +99,7 @@ _sig = {
     "des_batch_validate": [vp, C.POINTER(BatchDesc), vp, C.POINTER(i64), vp],
     "des_table_migrate_bytes": [i64, C.POINTER(C.c_size_t)],
     "des_table_migrate": [vp, vp, vp, vp, vp, C.POINTER(i64), vp],
+    "des_table_compact": [vp, vp, vp, vp, C.c_size_t, C.POINTER(i64), vp],
     "des_table_mark_seen": [vp, i64, C.c_uint32, vp, vp],
     "des_table_select_recent": [vp, i64, C.c_uint32, vp, vp],
     "des_cross_partial": [vp, vp, i64, i32, i32, i32, vp, vp],
@@ -237,6 +238,13 @@ class Table:
         n = i64(0)
         _check(_lib.des_table_migrate(self._h, _ptr(keep), dst._h, _ptr(src_aux), _ptr(dst_aux), C.byref(n), _stream()),
                "des_table_migrate")
+        return int(n.value)
+
+    def compact(self, keep: Optional[torch.Tensor], staging: torch.Tensor, aux: Optional[torch.Tensor] = None) -> int:
+        """Drop the rows with keep[r] == 0 in place (des_table_compact); returns the new row count."""
+        n = i64(0)
+        _check(_lib.des_table_compact(self._h, _ptr(keep), _ptr(aux), _ptr(staging), staging.numel() * staging.element_size(),
+                                      C.byref(n), _stream()), "des_table_compact")
         return int(n.value)
 
     def validate(self, batch: "Batch", rows: Optional[torch.Tensor] = None) -> int:

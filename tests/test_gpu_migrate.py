@@ -111,3 +111,55 @@ def test_growth_keeps_everything_and_errors(oracle, des):
         a.close(); b.close()
     finally:
         small.close(); other_dim.close(); big.close(); p.close()
+
+
+@pytest.mark.parametrize("staging_rows", [4096, 1 << 20])
+def test_compact_in_place_equals_migration_into_the_same_capacity(oracle, des, staging_rows):
+    """Eviction inside one table (des_table_compact), walked in many chunks or in one: the table afterwards
+    is the oracle's migration into a table of the same capacity, bit for bit, and training goes on in it."""
+    import torch
+    w = synth.workload(1, scale=1 / 16)
+    p = Pair(oracle, des, w.D, w.capacity, w.K, 0, des.OPT_ADAGRAD, seed=w.seed, init_scale=w.init_std, max_n=1 << 17)
+    keys0 = synth.preinsert_keys(w)
+    p.ot.insert(keys0); p.gt.insert(dev(keys0, torch))
+    ls_o = np.zeros(w.capacity, np.uint32)
+    ls_g = torch.zeros(w.capacity, dtype=torch.int32, device="cuda")
+    for step in range(3):
+        train_step(p, w, step, ls_o, ls_g, oracle, des)
+        p.sync_weights()
+    n = p.check_table("before compaction")
+    keep_o = oracle.select_recent(ls_o, n, 2)
+    keep_g = des.select_recent(ls_g, n, 2)
+    kept = int(keep_o.sum())
+    assert 0 < kept < n and n > 3 * 4096                       # several chunks with the small staging buffer
+    before = {name: getattr(p.gt, name)[:n].clone() for name in ("emb", "w", "acc_emb", "acc_w", "row_keys")}
+    ls_before = ls_g[:n].clone()
+    ot2 = p.ot.migrate(keep_o, w.capacity)
+    staging = torch.empty(staging_rows * w.D * 4, dtype=torch.uint8, device="cuda")
+    assert p.gt.compact(keep_g, staging, aux=ls_g) == kept
+    sel = torch.from_numpy(np.flatnonzero(keep_o)).cuda()
+    for name, old in before.items():
+        assert torch.equal(getattr(p.gt, name)[:kept], old[sel]), name
+    assert torch.equal(ls_g[:kept], ls_before[sel])
+    assert p.gt.size() == ot2.n_rows == kept and p.gt.status() == 0
+    assert_equal(host_u64(p.gt.row_keys[:kept]), ot2.row_keys, "row_keys after compaction")
+    # every kept key is found at its new row, every dropped key is absent
+    rows = p.gt.find(dev(p.ot.row_keys, torch), des.MISS_ZERO)
+    assert_equal(rows.cpu().numpy(), ot2.find(p.ot.row_keys), "lookups after compaction")
+    # keep == None is a no-op
+    assert p.gt.compact(None, staging) == kept
+    old_ot = p.ot
+    p.ot = ot2
+    try:
+        train_step(p, w, 3, insert=True)                         # dropped IDs come back as fresh rows
+        p.check_table("after post-compaction step")
+    finally:
+        old_ot.close(); p.close()
+    with pytest.raises(des.DesError) as e:                       # staging buffer too small
+        q = des.Table(8, 64, 1, opt=des.OPT_SGD, max_n=1024)
+        q.insert(torch.arange(1, 11, dtype=torch.int64, device="cuda"))
+        try:
+            q.compact(torch.ones(10, dtype=torch.uint8, device="cuda"), torch.empty(1024, dtype=torch.uint8, device="cuda"))
+        finally:
+            q.close()
+    assert e.value.code == des.ERR_WORKSPACE
