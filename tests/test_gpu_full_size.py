@@ -13,6 +13,7 @@ Upstream gradients and the aggregated FM vector fed to the backward pass are see
 to both sides.
 """
 import os
+import sys
 import time
 
 import numpy as np
@@ -27,11 +28,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def progress(msg):
-    """Long set-ups stay visibly alive: one line per stage in gpurun_out/ when that folder exists."""
-    d = os.path.join(ROOT, "gpurun_out")
-    if os.path.isdir(d):
+    """Long set-ups stay visibly alive: one line per stage on stderr (not captured per line by pytest's
+    default capture once the test ends) and, when DES_PROGRESS_DIR names a folder, in a log file there."""
+    line = f"{time.strftime('%H:%M:%S')} {msg}"
+    d = os.environ.get("DES_PROGRESS_DIR", "")
+    if d and os.path.isdir(d):
         with open(os.path.join(d, "full_size_progress.log"), "a") as f:
-            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+            f.write(line + "\n")
+    print(line, file=sys.stderr, flush=True)
 
 
 @pytest.fixture(scope="module")
