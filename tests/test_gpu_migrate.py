@@ -163,3 +163,26 @@ def test_compact_in_place_equals_migration_into_the_same_capacity(oracle, des, s
         finally:
             q.close()
     assert e.value.code == des.ERR_WORKSPACE
+
+
+def test_compact_keep_all_and_keep_none(des):
+    """Degenerate flag sets: everything kept (rows, keys and lookups unchanged) and nothing kept (an empty table
+    that takes new rows from 0 again)."""
+    import torch
+    t = des.Table(8, 20000, 2, opt=des.OPT_ADAGRAD, init_seed=3, max_n=1 << 15)
+    keys = torch.arange(1, 10001, dtype=torch.int64, device="cuda") * 7919
+    t.insert(keys)
+    n = t.size()
+    assert n == 10000
+    emb, rk = t.emb[:n].clone(), t.row_keys[:n].clone()
+    staging = torch.empty(4096 * 8 * 4, dtype=torch.uint8, device="cuda")
+    assert t.compact(torch.ones(n, dtype=torch.uint8, device="cuda"), staging) == n
+    assert torch.equal(t.emb[:n], emb) and torch.equal(t.row_keys[:n], rk)
+    found = t.find(keys, des.MISS_ZERO)
+    assert torch.equal(found, torch.arange(n, dtype=torch.int32, device="cuda"))
+    assert t.compact(torch.zeros(n, dtype=torch.uint8, device="cuda"), staging) == 0
+    assert t.size() == 0 and t.status() == 0
+    assert int((t.find(keys, des.MISS_ZERO) >= 0).sum()) == 0
+    again = t.find(keys[:100], des.MISS_INSERT)
+    assert torch.equal(again, torch.arange(100, dtype=torch.int32, device="cuda")) and t.size() == 100
+    t.close()
