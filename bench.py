@@ -157,6 +157,9 @@ def main():
                     help="skip the DCN cross layer timed at the main workload's shape (reported under \"cross_layer\")")
     ap.add_argument("--no-compact", action="store_true",
                     help="skip the in-place eviction of half of the main workload's rows, timed last (\"table_compact\")")
+    ap.add_argument("--only", type=str, default=None, choices=["cross", "dnn"],
+                    help="time only the cross network or only the first fully-connected layer at the workload's shape "
+                         "(no table is built; for profiling runs of those kernels)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -170,6 +173,16 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+    if args.only:
+        if args.calib_copy_mib > 0:
+            n = args.calib_copy_mib << 20
+            a, b = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1), torch.empty(n, dtype=torch.uint8, device="cuda")
+            b.copy_(a)
+            torch.cuda.synchronize()
+            del a, b
+        key = "cross_layer" if args.only == "cross" else "dnn_layer"
+        print(json.dumps({key: (run_cross_layer if args.only == "cross" else run_dnn_layer)(args, args.config)}))
+        return
     out = run_workload(args, args.config, cpu=not args.no_cpu)
     also = args.also if args.also is not None else ("2" if args.config == 4 and args.scale == 1.0 else "none")
     if also != "none":

@@ -281,6 +281,7 @@ __global__ __launch_bounds__(kBlock) void k_cross_net_kappa(const float *__restr
   __shared__ double red[kBlock];
   const int k = blockIdx.x;
   double acc = 0.0;
+#pragma unroll 8
   for (int64_t j = threadIdx.x; j < d; j += kBlock) acc += bias_prefix(bias, d, k, j) * (double)U[(int64_t)k * d + j];
   red[threadIdx.x] = acc;
   __syncthreads();
