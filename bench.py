@@ -609,11 +609,22 @@ def run_compact(w, table, state_bytes_per_row):
     keep = (torch.rand(n, device="cuda", generator=gen) < 0.5).to(torch.uint8)
     staging = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     want = int(keep.sum().item())
+    # a sample of kept rows to follow through the move: their keys and first weights, and where they must land
+    # (new row = number of kept rows below; counted with torch on the device, which is not the code under test)
+    sample = torch.nonzero(keep, as_tuple=False).flatten()
+    picks = min(2048, sample.numel())                 # evenly spaced, in integer arithmetic (indices beyond 2^24 are not exact in fp32)
+    sample = sample[(torch.arange(picks, dtype=torch.int64, device="cuda") * (sample.numel() - 1)) // max(picks - 1, 1)]
+    new_row = torch.stack([keep[:int(r)].sum(dtype=torch.int64) for r in sample[:64].tolist()]) if sample.numel() else sample
+    old_keys, old_emb = table.row_keys[sample].clone(), table.emb[sample, 0].clone()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     kept = table.compact(keep, staging)
     dt = time.perf_counter() - t0
     assert table.status() == 0 and table.size() == kept == want
+    if sample.numel():
+        found = table.find(old_keys, 0)                                  # DES_MISS_ZERO
+        assert bool((found[:64].long() == new_row).all()) and bool((found >= 0).all())
+        assert torch.equal(table.row_keys[found.long()], old_keys) and torch.equal(table.emb[found.long(), 0], old_emb)
     del staging, keep
     torch.cuda.empty_cache()
     nbytes = n * 1 + kept * (4 * state_bytes_per_row + 16) + table.slots.numel()
