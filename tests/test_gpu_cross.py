@@ -163,6 +163,17 @@ def test_cross_empty_batch_and_argument_checks(des):
     des.cross_backward(e, e, w, torch.empty(0, device="cuda"), e, e.clone(), e.clone(), False, dw, db, ws)
     torch.cuda.synchronize()
     assert float(dw.abs().sum()) == 0.0 and float(db.abs().sum()) == 0.0
+    # the whole-network calls on an empty batch: no-ops, and zero parameter gradients
+    U, nb = torch.ones((3, d), device="cuda"), torch.ones((2, d), device="cuda")
+    P3 = des.cross_net_partial(e, U, 2)
+    assert tuple(P3.shape) == (2, 0, 3)
+    nws = torch.empty(des.cross_net_bytes(0, d, 2), dtype=torch.uint8, device="cuda")
+    t0, g0, c0 = torch.empty((0, 3), device="cuda"), torch.empty((0, 3), device="cuda"), torch.empty(0, device="cuda")
+    des.cross_net_forward(t0, U, nb, g0, c0, nws)
+    dU, dB = torch.full((3, d), 7.0, device="cuda"), torch.full((2, d), 7.0, device="cuda")
+    des.cross_net_backward(e, U, nb, t0, g0, c0, e.clone(), False, dU, dB, nws)
+    torch.cuda.synchronize()
+    assert float(dU.abs().sum()) == 0.0 and float(dB.abs().sum()) == 0.0
     x = torch.ones((4, F, D), device="cuda")
     with pytest.raises(des.DesError) as err:                           # workspace too small
         des.cross_backward(x, x, w, torch.ones(4, device="cuda"), x, x.clone(), x.clone(), False, dw, db,
