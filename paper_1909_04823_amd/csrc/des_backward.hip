@@ -138,15 +138,31 @@ __device__ inline uint32_t block_excl_scan_u32(uint32_t v, uint32_t *lds, uint32
   return base + inc - v;
 }
 
+// The thread's kHeadItems consecutive sorted keys (two 16-byte loads when they all exist); missing ones read as `fill`.
+__device__ inline void load_head_keys(const uint32_t *__restrict__ keys, int64_t base, int64_t n, uint32_t fill,
+                                      uint32_t (&k)[kHeadItems]) {
+  static_assert(kHeadItems == 8, "two uint4 per thread");
+  if (base + kHeadItems <= n) {
+    const uint4 lo = *reinterpret_cast<const uint4 *>(keys + base);
+    const uint4 hi = *reinterpret_cast<const uint4 *>(keys + base + 4);
+    k[0] = lo.x; k[1] = lo.y; k[2] = lo.z; k[3] = lo.w; k[4] = hi.x; k[5] = hi.y; k[6] = hi.z; k[7] = hi.w;
+  } else {
+#pragma unroll
+    for (int i = 0; i < kHeadItems; ++i) k[i] = base + i < n ? keys[base + i] : fill;
+  }
+}
+
 __global__ __launch_bounds__(kBlock) void k_heads_count(const BwdArgs a) {
   __shared__ uint32_t lds[kWavesPerBlock];
   const int64_t base = (int64_t)blockIdx.x * kHeadTile + (int64_t)threadIdx.x * kHeadItems;
   uint32_t cnt = 0;
   uint32_t prev = base > 0 && base <= a.n ? a.key_sorted[base - 1] : 0xFFFFFFFFu;
+  uint32_t keys[kHeadItems];
+  load_head_keys(a.key_sorted, base, a.n, a.missing, keys);
 #pragma unroll
   for (int i = 0; i < kHeadItems; ++i) {
     if (base + i < a.n) {
-      const uint32_t k = a.key_sorted[base + i];
+      const uint32_t k = keys[i];
       cnt += (k != a.missing && (base + i == 0 || k != prev)) ? 1u : 0u;
       prev = k;
     }
@@ -185,12 +201,11 @@ __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
   uint32_t cnt = 0;
   uint32_t prev = base > 0 && base <= a.n ? a.key_sorted[base - 1] : 0xFFFFFFFFu;
   const uint32_t first_prev = prev;
+  load_head_keys(a.key_sorted, base, a.n, a.missing, key);
 #pragma unroll
   for (int i = 0; i < kHeadItems; ++i) {
     flag[i] = false;
-    key[i] = a.missing;
     if (base + i < a.n) {
-      key[i] = a.key_sorted[base + i];
       flag[i] = key[i] != a.missing && (base + i == 0 || key[i] != prev);
       cnt += flag[i] ? 1u : 0u;
       prev = key[i];
