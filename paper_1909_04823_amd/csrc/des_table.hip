@@ -116,8 +116,24 @@ __device__ inline uint32_t block_excl_scan_u32(uint32_t v, uint32_t *lds, uint32
 }
 
 // entry e opens a new row iff it is pending and is the first occurrence recorded in its slot
-__device__ inline bool opens_row(const Slot *slots, const int32_t *rows, const uint32_t *slot_of, int64_t e) {
-  return rows[e] == kRowPending && slots[slot_of[e]].first == (uint32_t)e;
+__device__ inline bool opens_row(const Slot *slots, int32_t row_e, const uint32_t *slot_of, int64_t e) {
+  return row_e == kRowPending && slots[slot_of[e]].first == (uint32_t)e;
+}
+
+// rows[] of the thread's kFlagItems consecutive entries (16-byte loads when they all exist and the caller's array
+// is 16-byte aligned; it only has to be 4-byte aligned); entries past n read as absent
+__device__ inline void load_flag_rows(const int32_t *__restrict__ rows, int64_t base, int64_t n, int32_t (&r)[kFlagItems]) {
+  static_assert(kFlagItems % 4 == 0, "whole int4 loads");
+  if (base + kFlagItems <= n && ((uintptr_t)rows & 15u) == 0) {
+#pragma unroll
+    for (int q = 0; q < kFlagItems / 4; ++q) {
+      const int4 v = *reinterpret_cast<const int4 *>(rows + base + q * 4);
+      r[q * 4 + 0] = v.x; r[q * 4 + 1] = v.y; r[q * 4 + 2] = v.z; r[q * 4 + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kFlagItems; ++i) r[i] = base + i < n ? rows[base + i] : kRowAbsent;
+  }
 }
 
 // Pass B1: per tile, how many entries open a new row.
@@ -127,9 +143,11 @@ __global__ __launch_bounds__(kBlock) void k_new_count(const Slot *__restrict__ s
   __shared__ uint32_t lds[kWavesPerBlock];
   const int64_t base = (int64_t)blockIdx.x * kFlagTile + (int64_t)threadIdx.x * kFlagItems;
   uint32_t cnt = 0;
+  int32_t r[kFlagItems];
+  load_flag_rows(rows, base, n, r);
 #pragma unroll
   for (int i = 0; i < kFlagItems; ++i)
-    if (base + i < n && opens_row(slots, rows, slot_of, base + i)) ++cnt;
+    if (base + i < n && opens_row(slots, r[i], slot_of, base + i)) ++cnt;
   uint32_t total;
   block_excl_scan_u32(cnt, lds, total);
   if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
@@ -168,9 +186,11 @@ __global__ __launch_bounds__(kBlock) void k_new_assign(Slot *__restrict__ slots,
   const int64_t base = (int64_t)blockIdx.x * kFlagTile + (int64_t)threadIdx.x * kFlagItems;
   bool flag[kFlagItems];
   uint32_t cnt = 0;
+  int32_t r[kFlagItems];
+  load_flag_rows(rows, base, n, r);
 #pragma unroll
   for (int i = 0; i < kFlagItems; ++i) {
-    flag[i] = base + i < n && opens_row(slots, rows, slot_of, base + i);
+    flag[i] = base + i < n && opens_row(slots, r[i], slot_of, base + i);
     cnt += flag[i] ? 1u : 0u;
   }
   uint32_t total;

@@ -478,3 +478,27 @@ def test_step_captured_in_a_hip_graph_replays_like_eager(oracle, des):
             graph.replay()
     finally:
         tg.close(); te.close()
+
+
+def test_rows_array_needs_only_four_byte_alignment(oracle, des):
+    """des_table_find / des_table_insert write rows_out wherever the caller points: an array that starts one
+    element into an allocation gives the same rows as an aligned one (the numbering kernels read it back)."""
+    import torch
+    w = synth.workload(1, scale=1 / 64)
+    results = []
+    for shift in (0, 1):
+        p = build_pair(oracle, des, w)
+        try:
+            batch = synth.gen_batch(w, 0)
+            keys = dev(batch.keys, torch)
+            buf = torch.full((batch.nnz + 4,), -7, dtype=torch.int32, device="cuda")
+            rows = buf[shift:shift + batch.nnz]
+            p.gt.find(keys, des.MISS_INSERT, rows)
+            torch.cuda.synchronize()
+            assert_equal(rows.cpu().numpy(), p.ot.find(batch.keys, insert_missing=True), f"rows (offset {shift})")
+            assert int(buf[shift + batch.nnz]) == -7 and (shift == 0 or int(buf[0]) == -7)      # nothing written outside
+            p.check_table(f"offset {shift}")
+            results.append(rows.cpu().numpy().copy())
+        finally:
+            p.close()
+    assert_equal(results[0], results[1], "rows for both alignments")
