@@ -46,14 +46,35 @@ __device__ inline T block_exclusive_scan(T v, T *lds /*[kWavesPerBlock]*/, T &to
   return base + inc - v;
 }
 
+// The thread's kScanItems consecutive values in 16-byte accesses when they all exist (the arrays scanned here are
+// the library's own, 256-byte aligned); values past n read as zero.
+template <typename T>
+__device__ inline void load_items(const T *__restrict__ data, int64_t base, int64_t n, T (&item)[kScanItems]) {
+  constexpr int kPer = 16 / sizeof(T);
+  static_assert(kScanItems % kPer == 0, "whole 16-byte accesses");
+  if (base + kScanItems <= n) {
+#pragma unroll
+    for (int q = 0; q < kScanItems / kPer; ++q) {
+      const uint4 raw = *reinterpret_cast<const uint4 *>(data + base + q * kPer);
+      const T *t = reinterpret_cast<const T *>(&raw);
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) item[q * kPer + j] = t[j];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) item[i] = base + i < n ? data[base + i] : (T)0;
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void k_scan_reduce(const T *__restrict__ data, int64_t n, T *__restrict__ sums) {
   __shared__ T lds[kWavesPerBlock];
   const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
   T v = 0;
+  T item[kScanItems];
+  load_items(data, base, n, item);
 #pragma unroll
-  for (int i = 0; i < kScanItems; ++i)
-    if (base + i < n) v += data[base + i];
+  for (int i = 0; i < kScanItems; ++i) v += item[i];
   T total;
   block_exclusive_scan(v, lds, total);
   if (threadIdx.x == 0) sums[blockIdx.x] = total;
@@ -81,17 +102,27 @@ __global__ __launch_bounds__(kBlock) void k_scan_apply(T *__restrict__ data, int
   const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
   T item[kScanItems];
   T v = 0;
+  load_items(data, base, n, item);
 #pragma unroll
-  for (int i = 0; i < kScanItems; ++i) {
-    item[i] = base + i < n ? data[base + i] : (T)0;
-    v += item[i];
-  }
+  for (int i = 0; i < kScanItems; ++i) v += item[i];
   T total;
   T run = sums[blockIdx.x] + block_exclusive_scan(v, lds, total);
+  if (base + kScanItems <= n) {
+    constexpr int kPer = 16 / sizeof(T);
 #pragma unroll
-  for (int i = 0; i < kScanItems; ++i) {
-    if (base + i < n) data[base + i] = run;
-    run += item[i];
+    for (int q = 0; q < kScanItems / kPer; ++q) {
+      uint4 raw;
+      T *t = reinterpret_cast<T *>(&raw);
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) { t[j] = run; run += item[q * kPer + j]; }
+      *reinterpret_cast<uint4 *>(data + base + q * kPer) = raw;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+      if (base + i < n) data[base + i] = run;
+      run += item[i];
+    }
   }
 }
 
