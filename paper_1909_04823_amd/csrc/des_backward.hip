@@ -250,12 +250,22 @@ __global__ __launch_bounds__(kBlock) void k_classify(const BwdArgs a) {
   if ((int64_t)blockIdx.x * kHeadTile >= U) return;          // uniform per workgroup
   uint32_t nl = 0, nc = 0;
   int len[kHeadItems];
+  if (tile0 + kHeadItems <= U) {                  // the thread's nine segment bounds: two 16-byte loads and one more
+    const int4 lo = *reinterpret_cast<const int4 *>(a.seg_off + tile0);
+    const int4 hi = *reinterpret_cast<const int4 *>(a.seg_off + tile0 + 4);
+    const int last = a.seg_off[tile0 + kHeadItems];
+    len[0] = lo.y - lo.x; len[1] = lo.z - lo.y; len[2] = lo.w - lo.z; len[3] = hi.x - lo.w;
+    len[4] = hi.y - hi.x; len[5] = hi.z - hi.y; len[6] = hi.w - hi.z; len[7] = last - hi.w;
+  } else {
 #pragma unroll
-  for (int i = 0; i < kHeadItems; ++i) {
-    const int64_t u = tile0 + i;
-    len[i] = u < U ? a.seg_off[u + 1] - a.seg_off[u] : 0;
-    if (len[i] > kShortMax) { ++nl; nc += (uint32_t)((len[i] + kChunk - 1) / kChunk); }
+    for (int i = 0; i < kHeadItems; ++i) {
+      const int64_t u = tile0 + i;
+      len[i] = u < U ? a.seg_off[u + 1] - a.seg_off[u] : 0;
+    }
   }
+#pragma unroll
+  for (int i = 0; i < kHeadItems; ++i)
+    if (len[i] > kShortMax) { ++nl; nc += (uint32_t)((len[i] + kChunk - 1) / kChunk); }
   uint32_t tot_l, tot_c;
   uint32_t ex_l = block_excl_scan_u32(nl, lds, tot_l);
   uint32_t ex_c = block_excl_scan_u32(nc, lds, tot_c);
