@@ -26,6 +26,7 @@ constexpr int kChunk = 512;                // entries per chunk of a longer segm
 constexpr int kShortGrid = 65536;          // most workgroups of the short-segment kernel (it strides over the segments)
 constexpr int kHeadItems = 8;
 constexpr int kHeadTile = kBlock * kHeadItems;
+constexpr int64_t kHeadsOneBlock = 4096;   // up to this many tiles one workgroup sums the tiles' head counts
 constexpr int kWavesPerBlock = kBlock / kWave;
 
 struct BwdArgs {
@@ -189,6 +190,15 @@ __global__ __launch_bounds__(kBlock) void k_heads_sums(const BwdArgs a, int64_t 
     a.ctrl->n_chunks = 0;
     if (a.n_uniq_out) *a.n_uniq_out = carry;
   }
+}
+
+// The same bookkeeping after a device-wide scan of the tile counts (many tiles): the scan left the total behind
+// the counts.
+__global__ void k_heads_finish(const BwdArgs a, const uint32_t *total) {
+  a.ctrl->n_uniq = *total;
+  a.ctrl->n_long = 0;
+  a.ctrl->n_chunks = 0;
+  if (a.n_uniq_out) *a.n_uniq_out = *total;
 }
 
 __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
@@ -728,7 +738,12 @@ int sort_stage(des_table *t, BwdArgs &a, const Layout &L, hipStream_t s) {
     ProfScope ps(KID_HEADS, s);
     const int64_t nb = (n + kHeadTile - 1) / kHeadTile;
     hipLaunchKernelGGL(k_heads_count, dim3((unsigned)nb), dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL(k_heads_sums, dim3(1), dim3(kBlock), 0, s, a, nb);
+    if (nb > kHeadsOneBlock) {                    // one workgroup walking the counts 256 at a time gets slow
+      exclusive_scan_u32(a.head_sums, nb, a.head_sums + nb, ws + L.sort_scratch, s);
+      hipLaunchKernelGGL(k_heads_finish, dim3(1), dim3(1), 0, s, a, (const uint32_t *)(a.head_sums + nb));
+    } else {
+      hipLaunchKernelGGL(k_heads_sums, dim3(1), dim3(kBlock), 0, s, a, nb);
+    }
     hipLaunchKernelGGL(k_heads_write, dim3((unsigned)nb), dim3(kBlock), 0, s, a);
   }
   {

@@ -63,6 +63,8 @@ struct ProfScope {
 size_t scan_scratch_bytes(int64_t n);
 size_t sort_scratch_bytes(int64_t n);
 
+// Exclusive prefix sum of 32-bit values in place; total written to *total_out (device, may be null).
+void exclusive_scan_u32(uint32_t *data, int64_t n, uint32_t *total_out, void *scratch, hipStream_t s);
 // Exclusive prefix sum of 64-bit values in place; total written to *total_out (device, may be null).
 void exclusive_scan_u64(unsigned long long *data, int64_t n, unsigned long long *total_out,
                         void *scratch, hipStream_t s);

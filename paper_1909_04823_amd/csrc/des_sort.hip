@@ -361,6 +361,10 @@ size_t sort_scratch_bytes(int64_t n) {
   return align_up((size_t)kMaxRadix * nblocks * sizeof(uint32_t), 256) + scan_scratch_bytes(kMaxRadix * nblocks);
 }
 
+void exclusive_scan_u32(uint32_t *data, int64_t n, uint32_t *total_out, void *scratch, hipStream_t s) {
+  exclusive_scan<uint32_t>(data, n, total_out, scratch, s);
+}
+
 void exclusive_scan_u64(unsigned long long *data, int64_t n, unsigned long long *total_out, void *scratch,
                         hipStream_t s) {
   exclusive_scan<unsigned long long>(data, n, total_out, scratch, s);
