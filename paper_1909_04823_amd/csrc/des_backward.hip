@@ -23,6 +23,7 @@ namespace {
 
 constexpr int kShortMax = 32;              // segments up to this many entries are reduced by one lane group
 constexpr int kChunk = 512;                // entries per chunk of a longer segment (one wave per chunk)
+constexpr int kMidFan = 64;                // chunk partials that one wave pre-sums for segments of more chunks than this
 constexpr int kShortGrid = 65536;          // most workgroups of the short-segment kernel (it strides over the segments)
 constexpr int kHeadItems = 8;
 constexpr int kHeadTile = kBlock * kHeadItems;
@@ -52,6 +53,9 @@ struct BwdArgs {
   uint32_t *head_sums;
   int32_t *long_seg;    // segment index of long segment j
   uint32_t *long_c0;    // first chunk of long segment j
+  int32_t *multi_seg;   // long segment indices j of the segments with more than one chunk
+  int32_t *group_seg;   // long segment index j of pre-summed group i (segments of more than kMidFan chunks)
+  uint32_t *group_c;    // first chunk of that group
   int32_t *chunk_owner; // long segment index of chunk c
   double *partials;     // [chunks][D+4]
   // optimizer (opt_emb == DES_OPT_NONE: merge only)
@@ -188,6 +192,8 @@ __global__ __launch_bounds__(kBlock) void k_heads_sums(const BwdArgs a, int64_t 
     a.ctrl->n_uniq = carry;
     a.ctrl->n_long = 0;
     a.ctrl->n_chunks = 0;
+    a.ctrl->n_multi = 0;
+    a.ctrl->n_groups = 0;
     if (a.n_uniq_out) *a.n_uniq_out = carry;
   }
 }
@@ -198,6 +204,8 @@ __global__ void k_heads_finish(const BwdArgs a, const uint32_t *total) {
   a.ctrl->n_uniq = *total;
   a.ctrl->n_long = 0;
   a.ctrl->n_chunks = 0;
+  a.ctrl->n_multi = 0;
+  a.ctrl->n_groups = 0;
   if (a.n_uniq_out) *a.n_uniq_out = *total;
 }
 
@@ -254,11 +262,11 @@ __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
 // ranges are handed out with one atomic pair per workgroup.
 __global__ __launch_bounds__(kBlock) void k_classify(const BwdArgs a) {
   __shared__ uint32_t lds[kWavesPerBlock];
-  __shared__ unsigned long long base_long, base_chunk;
+  __shared__ unsigned long long base_long, base_chunk, base_multi, base_group;
   const long long U = a.ctrl->n_uniq;
   const int64_t tile0 = (int64_t)blockIdx.x * kHeadTile + (int64_t)threadIdx.x * kHeadItems;
   if ((int64_t)blockIdx.x * kHeadTile >= U) return;          // uniform per workgroup
-  uint32_t nl = 0, nc = 0;
+  uint32_t nl = 0, nc = 0, nm = 0, ng = 0;
   int len[kHeadItems];
   if (tile0 + kHeadItems <= U) {                  // the thread's nine segment bounds: two 16-byte loads and one more
     const int4 lo = *reinterpret_cast<const int4 *>(a.seg_off + tile0);
@@ -274,25 +282,41 @@ __global__ __launch_bounds__(kBlock) void k_classify(const BwdArgs a) {
     }
   }
 #pragma unroll
-  for (int i = 0; i < kHeadItems; ++i)
-    if (len[i] > kShortMax) { ++nl; nc += (uint32_t)((len[i] + kChunk - 1) / kChunk); }
-  uint32_t tot_l, tot_c;
+  for (int i = 0; i < kHeadItems; ++i) {
+    if (len[i] > kShortMax) {
+      const uint32_t nch = (uint32_t)((len[i] + kChunk - 1) / kChunk);
+      ++nl; nc += nch;
+      if (nch > 1) ++nm;
+      if (nch > kMidFan) ng += (nch + kMidFan - 1) / kMidFan;
+    }
+  }
+  uint32_t tot_l, tot_c, tot_m, tot_g;
   uint32_t ex_l = block_excl_scan_u32(nl, lds, tot_l);
   uint32_t ex_c = block_excl_scan_u32(nc, lds, tot_c);
   if (tot_l == 0) return;                                    // uniform: the scans synchronised the workgroup
+  uint32_t ex_m = block_excl_scan_u32(nm, lds, tot_m);
+  uint32_t ex_g = block_excl_scan_u32(ng, lds, tot_g);
   if (threadIdx.x == 0) {
-    base_long = atomicAdd(reinterpret_cast<unsigned long long *>(&a.ctrl->n_long), (unsigned long long)tot_l);
-    base_chunk = atomicAdd(reinterpret_cast<unsigned long long *>(&a.ctrl->n_chunks), (unsigned long long)tot_c);
+    typedef unsigned long long ull;
+    base_long = atomicAdd(reinterpret_cast<ull *>(&a.ctrl->n_long), (ull)tot_l);
+    base_chunk = atomicAdd(reinterpret_cast<ull *>(&a.ctrl->n_chunks), (ull)tot_c);
+    base_multi = tot_m ? atomicAdd(reinterpret_cast<ull *>(&a.ctrl->n_multi), (ull)tot_m) : 0ull;
+    base_group = tot_g ? atomicAdd(reinterpret_cast<ull *>(&a.ctrl->n_groups), (ull)tot_g) : 0ull;
   }
   __syncthreads();
   uint32_t j = (uint32_t)base_long + ex_l, c0 = (uint32_t)base_chunk + ex_c;
+  uint32_t jm = (uint32_t)base_multi + ex_m, gi = (uint32_t)base_group + ex_g;
 #pragma unroll
   for (int i = 0; i < kHeadItems; ++i) {
     if (len[i] > kShortMax) {
+      const uint32_t nch = (uint32_t)((len[i] + kChunk - 1) / kChunk);
       a.long_seg[j] = (int32_t)(tile0 + i);
       a.long_c0[j] = c0;
+      if (nch > 1) a.multi_seg[jm++] = (int32_t)j;           // what the per-segment combine has to visit
+      if (nch > kMidFan)                                      // and the groups of chunk sums that are added up first
+        for (uint32_t k = 0; k < nch; k += kMidFan) { a.group_seg[gi] = (int32_t)j; a.group_c[gi] = c0 + k; ++gi; }
       ++j;
-      c0 += (uint32_t)((len[i] + kChunk - 1) / kChunk);
+      c0 += nch;
     }
   }
 }
@@ -595,6 +619,49 @@ __global__ __launch_bounds__(kBlock) void k_long_partial(const BwdArgs a) {
   }
 }
 
+// (4b') Segments of more than kMidFan chunks (rows that take a sizeable share of a skewed batch): one wave per
+// group of kMidFan consecutive chunk partials adds them up in place, into the group's first slot, so that the
+// per-segment combine below walks nch / kMidFan terms instead of nch.  Lane groups take the group's partials
+// in strides and are combined by the same xor tree as in k_long_partial.
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_long_mid(const BwdArgs a) {
+  constexpr int G = D / 4;
+  constexpr int NG = kWave / G;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t gi = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  if (gi >= a.ctrl->n_groups) return;                         // uniform per wave
+  const int j = a.group_seg[gi];
+  const int u = a.long_seg[j];
+  const int nch = (a.seg_off[u + 1] - a.seg_off[u] + kChunk - 1) / kChunk;
+  const int64_t c = a.group_c[gi];
+  const int rel = (int)(c - a.long_c0[j]);
+  const int cnt = min(kMidFan, nch - rel);
+  const int g = lane / G, sub = lane % G;
+  Acc acc = acc_zero();
+  for (int k = g; k < cnt; k += NG) {
+    const double *p = a.partials + (c + k) * (D + 4);
+    const double2 lo = *reinterpret_cast<const double2 *>(p + sub * 4);
+    const double2 hi = *reinterpret_cast<const double2 *>(p + sub * 4 + 2);
+    const double2 t = *reinterpret_cast<const double2 *>(p + D);
+    acc.v[0] += lo.x; acc.v[1] += lo.y; acc.v[2] += hi.x; acc.v[3] += hi.y;
+    acc.s2 += t.x; acc.gw += t.y;                             // the same two values in every lane group's sub lanes
+  }
+#pragma unroll
+  for (int m = G; m < kWave; m <<= 1) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc.v[k] += __shfl_xor(acc.v[k], m, kWave);
+    acc.s2 += __shfl_xor(acc.s2, m, kWave);
+    acc.gw += __shfl_xor(acc.gw, m, kWave);
+  }
+  // every partial of the group has been read by this wave's loads above (the shuffles waited for them)
+  if (g == 0) {
+    double *p = a.partials + c * (D + 4);
+    *reinterpret_cast<double2 *>(p + sub * 4) = make_double2(acc.v[0], acc.v[1]);
+    *reinterpret_cast<double2 *>(p + sub * 4 + 2) = make_double2(acc.v[2], acc.v[3]);
+    if (sub == 0) *reinterpret_cast<double2 *>(p + D) = make_double2(acc.s2, acc.gw);
+  }
+}
+
 // (4c) one workgroup per long segment of several chunks: lane groups stride over the chunk partials, an
 // LDS tree combines the groups, group 0 updates the row
 template <int D>
@@ -603,14 +670,15 @@ __global__ __launch_bounds__(kBlock) void k_long_final(const BwdArgs a) {
   constexpr int NGB = kBlock / G;           // lane groups per workgroup
   __shared__ double red[NGB][D + 4];
   const int grp = threadIdx.x / G, sub = threadIdx.x % G;
-  const long long NL = a.ctrl->n_long;
-  for (int64_t j = blockIdx.x; j < NL; j += gridDim.x) {
+  const long long NM = a.ctrl->n_multi;      // one-chunk segments were updated by the wave that reduced their chunk
+  for (int64_t jj = blockIdx.x; jj < NM; jj += gridDim.x) {
+    const int j = a.multi_seg[jj];
     const int u = a.long_seg[j];
     const int nch = (a.seg_off[u + 1] - a.seg_off[u] + kChunk - 1) / kChunk;
-    if (nch == 1) continue;                    // updated by the wave that reduced its only chunk (uniform per workgroup)
     const double *p0 = a.partials + (int64_t)a.long_c0[j] * (D + 4);
+    const int step = nch > kMidFan ? kMidFan : 1;      // k_long_mid left one sum per kMidFan chunks
     Acc acc = acc_zero();
-    for (int c = grp; c < nch; c += NGB) {
+    for (int c = grp * step; c < nch; c += NGB * step) {
       const double *p = p0 + (int64_t)c * (D + 4);
       const double2 lo = *reinterpret_cast<const double2 *>(p + sub * 4);
       const double2 hi = *reinterpret_cast<const double2 *>(p + sub * 4 + 2);
@@ -680,7 +748,9 @@ void launch_update(const BwdArgs &a, hipStream_t s) {
   }
   {
     ProfScope ps(KID_LONG_FINAL, s);
-    hipLaunchKernelGGL(k_long_final<D>, dim3((unsigned)(max_long < 65536 ? max_long : 65536)), dim3(kBlock), 0, s, a);
+    const int64_t max_multi = a.n / (kChunk + 1) + 1, max_groups = 3 * (a.n / ((int64_t)kChunk * kMidFan)) + 4;
+    hipLaunchKernelGGL(k_long_mid<D>, dim3(blocks_for(max_groups * kWave)), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL(k_long_final<D>, dim3((unsigned)(max_multi < 8192 ? max_multi : 8192)), dim3(kBlock), 0, s, a);
   }
 }
 
@@ -690,8 +760,8 @@ void launch_update_v(const BwdArgs &a, hipStream_t s) {
 }
 
 struct Layout {
-  size_t key_a, key_b, pay_a, pay_b, bag_of, seg_off, uniq_rows, first_pay, head_sums, long_seg, long_c0, chunk_owner, partials,
-      sort_scratch, total;
+  size_t key_a, key_b, pay_a, pay_b, bag_of, seg_off, uniq_rows, first_pay, head_sums, long_seg, long_c0, multi_seg, group_seg,
+      group_c, chunk_owner, partials, sort_scratch, total;
 };
 
 Layout layout_for(int D, int64_t n) {
@@ -705,6 +775,9 @@ Layout layout_for(int D, int64_t n) {
   L.seg_off = take((m + 1) * 4); L.uniq_rows = take(m * 4); L.first_pay = take(m * 4);
   L.head_sums = take(((m + kHeadTile - 1) / kHeadTile + 1) * 4);
   L.long_seg = take(max_long * 4); L.long_c0 = take(max_long * 4);
+  L.multi_seg = take((m / (kChunk + 1) + 1) * 4);
+  const size_t max_groups = 3 * (m / ((size_t)kChunk * kMidFan)) + 4;   // sum of ceil(chunks / kMidFan) over those segments
+  L.group_seg = take(max_groups * 4); L.group_c = take(max_groups * 4);
   L.chunk_owner = take(max_chunks * 4);
   L.partials = take(max_chunks * (size_t)(D + 4) * 8);
   L.sort_scratch = take(sort_scratch_bytes(n));
@@ -769,6 +842,8 @@ void batch_args(des_table *t, const des_batch_t *b, const int32_t *rows, const L
   a.first_pay = (uint32_t *)(ws + L.first_pay);
   a.head_sums = (uint32_t *)(ws + L.head_sums);
   a.long_seg = (int32_t *)(ws + L.long_seg); a.long_c0 = (uint32_t *)(ws + L.long_c0);
+  a.multi_seg = (int32_t *)(ws + L.multi_seg);
+  a.group_seg = (int32_t *)(ws + L.group_seg); a.group_c = (uint32_t *)(ws + L.group_c);
   a.chunk_owner = (int32_t *)(ws + L.chunk_owner); a.partials = (double *)(ws + L.partials);
 }
 

@@ -29,6 +29,8 @@ struct Ctrl {
   int status;              // sticky des_status_t
   int pad[5];
   unsigned long long first_bad;   // verdict word of des_batch_validate
+  long long n_multi;       // long segments of more than one chunk
+  long long n_groups;      // groups of chunk partials that are pre-summed for the segments of very many chunks
 };
 static_assert(sizeof(Ctrl) <= 256, "control block must fit its reserved 256 bytes");
 

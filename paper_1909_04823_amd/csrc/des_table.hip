@@ -303,6 +303,7 @@ __global__ __launch_bounds__(kBlock) void k_fill_u64x2(uint4 *__restrict__ p, in
 
 __global__ void k_zero_ctrl(Ctrl *ctrl) {
   ctrl->n_rows = 0; ctrl->n_new = 0; ctrl->n_uniq = 0; ctrl->n_long = 0; ctrl->n_chunks = 0; ctrl->status = 0;
+  ctrl->n_multi = 0; ctrl->n_groups = 0;
 }
 
 // out[i] = sum over the K shards of P[s*n + i], summed in double and rounded once

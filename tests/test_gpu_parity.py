@@ -502,3 +502,34 @@ def test_rows_array_needs_only_four_byte_alignment(oracle, des):
         finally:
             p.close()
     assert_equal(results[0], results[1], "rows for both alignments")
+
+
+@pytest.mark.parametrize("D,with_vals", [(16, True), (64, False)])
+def test_merge_rows_of_more_than_64_chunks(oracle, des, D, with_vals):
+    """Rows that occur tens of thousands of times in one batch: their chunk sums are combined in two levels
+    (groups of 64 chunks first).  65 chunks (a full group and a single chunk), 79, 137 with a ragged last
+    chunk, next to ordinary rows.  Backward only; the upstream A_sum comes from the oracle's forward."""
+    import torch
+    counts = np.array([32769, 40000, 69900, 5, 600, 1])
+    rng = np.random.default_rng(31)
+    vocab = rng.integers(1, 2**63, size=counts.size, dtype=np.uint64)
+    keys = np.repeat(vocab, counts)[rng.permutation(int(counts.sum()))]
+    B, F = 64, 5
+    cuts = np.sort(rng.integers(0, keys.size + 1, size=B * F - 1))
+    offsets = np.concatenate([[0], cuts, [keys.size]]).astype(np.int32)
+    vals = rng.uniform(0.25, 2.0, keys.size).astype(np.float32) if with_vals else None
+    batch = synth.Batch(B, F, keys, offsets, vals)
+    p = Pair(oracle, des, D, 64, 4, 0, des.OPT_ADAGRAD, seed=5, init_scale=0.1, max_n=keys.size + 64)
+    try:
+        rows = p.find(batch, insert=True)
+        P = p.ot.partial_forward(B, F, batch.keys, batch.offsets, rows, 4, 0, batch.vals, pool=False)
+        A_sum = oracle.aggregate(P["P_sum"]).astype(np.float32)
+        g_lr = rng.standard_normal(B).astype(np.float32)
+        g_fm = (1e-4 * rng.standard_normal(B)).astype(np.float32)
+        g_pool = rng.standard_normal((B, F, D)).astype(np.float32)
+        ref = p.backward(batch, g_lr, g_fm, A_sum, g_pool, opt=des.OPT_NONE)
+        assert sorted(ref["counts"].tolist()) == sorted(counts.tolist())
+        p.backward(batch, g_lr * 1e-3, g_fm * 1e-3, A_sum, g_pool * 1e-3, lr=0.05, eps=1e-8)
+        p.check_weights("giant segments adagrad")
+    finally:
+        p.close()
