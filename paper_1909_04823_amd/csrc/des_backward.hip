@@ -749,7 +749,8 @@ void launch_update(const BwdArgs &a, hipStream_t s) {
   {
     ProfScope ps(KID_LONG_FINAL, s);
     const int64_t max_multi = a.n / (kChunk + 1) + 1, max_groups = 3 * (a.n / ((int64_t)kChunk * kMidFan)) + 4;
-    hipLaunchKernelGGL(k_long_mid<D>, dim3(blocks_for(max_groups * kWave)), dim3(kBlock), 0, s, a);
+    if (a.n > (int64_t)kChunk * kMidFan)          // a smaller batch cannot hold a segment of that many chunks
+      hipLaunchKernelGGL(k_long_mid<D>, dim3(blocks_for(max_groups * kWave)), dim3(kBlock), 0, s, a);
     hipLaunchKernelGGL(k_long_final<D>, dim3((unsigned)(max_multi < 8192 ? max_multi : 8192)), dim3(kBlock), 0, s, a);
   }
 }
