@@ -33,6 +33,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_bias_act(const float *__re
     }
     // bias first or last makes no difference to the double sum beyond its last bit; the rounding to
     // fp32 happens once, below
+#pragma unroll 8
     for (int s = 0; s < K; ++s) {
       const float4 p = *reinterpret_cast<const float4 *>(P + (int64_t)s * n + i * 4);
       a[0] += (double)p.x; a[1] += (double)p.y; a[2] += (double)p.z; a[3] += (double)p.w;

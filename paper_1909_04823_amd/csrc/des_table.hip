@@ -315,6 +315,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float *__restrict__ 
     const int64_t n4 = n / 4;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
       double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+#pragma unroll 8
       for (int s = 0; s < K; ++s) {
         const float4 p = *reinterpret_cast<const float4 *>(&P[(int64_t)s * n + i * 4]);
         a0 += (double)p.x; a1 += (double)p.y; a2 += (double)p.z; a3 += (double)p.w;
@@ -324,6 +325,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float *__restrict__ 
   } else {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
       double a = 0.0;
+#pragma unroll 8
       for (int s = 0; s < K; ++s) a += (double)P[(int64_t)s * n + i];
       out[i] = (float)a;
     }
@@ -365,7 +367,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_forward(const float *__res
   if (b < B && P_sum)
     for (int d4 = sub; d4 < D / 4; d4 += 8) {
       double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-      for (int s = 0; s < K; ++s) {
+#pragma unroll 8
+      for (int s = 0; s < K; ++s) {                       // the shards' loads are independent: several in flight
         const float4 p = *reinterpret_cast<const float4 *>(P_sum + ((int64_t)s * B + b) * D + d4 * 4);
         a0 += (double)p.x; a1 += (double)p.y; a2 += (double)p.z; a3 += (double)p.w;
       }
@@ -378,12 +381,14 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_forward(const float *__res
   if (b < B && sub == 0) {
     if (P_sum) {
       double sq = 0.0;
+#pragma unroll 8
       for (int s = 0; s < K; ++s) sq += (double)P_sq[(int64_t)s * B + b];
       A_sq[b] = (float)sq;
       if (fm2) fm2[b] = (float)(0.5 * (q - sq));
     }
     if (P_lr) {
       double l = 0.0;
+#pragma unroll 8
       for (int s = 0; s < K; ++s) l += (double)P_lr[(int64_t)s * B + b];
       A_lr[b] = (float)l;
     }
