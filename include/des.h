@@ -388,6 +388,17 @@ des_status_t des_dense_workspace_bytes(int32_t H_max, size_t *workspace_bytes);
 des_status_t des_bias_act_backward(const float *A, const float *dA, int64_t rows, int32_t H, int32_t relu,
                                    float *dZ, float *dbias, void *workspace, size_t workspace_bytes, void *stream);
 
+/* des_bias_act_backward for callers that cannot allocate or hand over device memory: code under HIP graph
+ * capture, serving loops and harnesses in which hipMalloc is forbidden.  Same arguments, kernels and results,
+ * but the per-slice column partials live in a 2 MiB array inside the library's own device image instead of a
+ * workspace; the call allocates nothing.  H <= 4096, else DES_ERR_WORKSPACE (nothing is enqueued).  The first
+ * call on a GPU looks up that GPU's copy of the array (a host-side query, no allocation; make it outside a
+ * capture).  All calls on one GPU share the array: two calls that overlap in time on one GPU (different
+ * streams, no ordering) race; calls on one stream, or ordered by events, do not.  Nothing needs clearing
+ * between calls: each call writes every partial it later reads. */
+des_status_t des_bias_act_backward_static(const float *A, const float *dA, int64_t rows, int32_t H, int32_t relu,
+                                          float *dZ, float *dbias, void *stream);
+
 /* Output unit, loss and gradients for one batch:
  *     logit[b] = b0 + A_lr[b] + fm2[b] + <a[b,:], w_out>        (absent components: null pointers)
  *     p = 1/(1+exp(-logit));   loss = mean_b( -y log p - (1-y) log(1-p) ), evaluated as

@@ -5,6 +5,7 @@
 // All of it is streaming, elementwise or column-reduction work bound by HBM; sums over the batch
 // are taken in double in a fixed order (per-slice partials, then one pass over the slices), so
 // results do not depend on scheduling.
+#include <mutex>
 #include "des_internal.h"
 
 namespace des {
@@ -12,6 +13,29 @@ namespace {
 
 constexpr int kMaxSlices = 64;        // row slices of a column reduction
 constexpr int kHeadBlocks = 1024;     // workgroups of the output-unit kernel (each keeps one loss partial)
+
+// Library-owned scratch of des_bias_act_backward_static: the per-slice column partials of layers up to
+// kStaticMaxH wide (2 MiB per GPU, held until the process ends).  Every GPU has its own copy of the array at
+// its own address; in host code the array's name is only a handle for hipGetSymbolAddress, never a pointer.
+constexpr int kStaticMaxH = 4096;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) double scratch[(size_t)kMaxSlices * kStaticMaxH];
+std::mutex g_scratch_mutex;
+double *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+des_status_t static_scratch(double **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DES_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DES_ERR_DEVICE;
+    g_scratch_ptr[dev] = static_cast<double *>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return DES_OK;
+}
 
 inline unsigned blocks_for(int64_t n, int64_t cap) {
   int64_t g = (n + kBlock - 1) / kBlock;
@@ -243,6 +267,18 @@ des_status_t des_bias_act_backward(const float *A, const float *dA, int64_t rows
   if (!A || !dA || !dZ || !dbias || !workspace || !al8(workspace)) return DES_ERR_INVALID_ARG;
   if (workspace_bytes < sizeof(double) * (size_t)kMaxSlices * (size_t)H) return DES_ERR_WORKSPACE;
   return column_sums<0>(A, dA, nullptr, rows, H, relu, dZ, dbias, (double *)workspace, (hipStream_t)stream);
+}
+
+des_status_t des_bias_act_backward_static(const float *A, const float *dA, int64_t rows, int32_t H, int32_t relu,
+                                          float *dZ, float *dbias, void *stream) {
+  if (rows < 0 || H < 1) return DES_ERR_INVALID_ARG;
+  if (!A || !dA || !dZ || !dbias) return DES_ERR_INVALID_ARG;
+  if (H > kStaticMaxH) return DES_ERR_WORKSPACE;      // wider than the library's own scratch holds
+  double *partial = nullptr;
+  const des_status_t st = static_scratch(&partial);
+  if (st != DES_OK) return st;
+  // every partial the final pass reads is written by the first pass of the same call: nothing to clear
+  return column_sums<0>(A, dA, nullptr, rows, H, relu, dZ, dbias, partial, (hipStream_t)stream);
 }
 
 des_status_t des_head(const float *A_lr, const float *fm2, const float *a, const float *w_out, const float *b0,

@@ -29,7 +29,7 @@ EXPORTS = [
     "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge", "des_backward_prepare",
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
     "des_batch_validate", "des_table_migrate_bytes", "des_table_migrate", "des_table_compact", "des_table_mark_seen", "des_table_select_recent",
-    "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_head", "des_dense_update",
+    "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_bias_act_backward_static", "des_head", "des_dense_update",
     "des_cross_partial", "des_cross_apply", "des_cross_backward_bytes", "des_cross_backward", "des_cross_partial_backward",
     "des_cross_net_bytes", "des_cross_net_partial", "des_cross_net_forward", "des_cross_net_backward",
     "des_profile_enable", "des_profile_read", "des_status_string",
@@ -94,6 +94,7 @@ _sig = {
     "des_aggregate_bias_act": [vp, i32, i64, i32, vp, i32, vp, vp],
     "des_dense_workspace_bytes": [i32, C.POINTER(C.c_size_t)],
     "des_bias_act_backward": [vp, vp, i64, i32, i32, vp, vp, vp, C.c_size_t, vp],
+    "des_bias_act_backward_static": [vp, vp, i64, i32, i32, vp, vp, vp],
     "des_head": [vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp],
     "des_dense_update": [vp, vp, vp, vp, i64, C.POINTER(Optimizer), vp],
     "des_batch_validate": [vp, C.POINTER(BatchDesc), vp, C.POINTER(i64), vp],
@@ -531,6 +532,14 @@ def bias_act_backward(A: torch.Tensor, dA: torch.Tensor, relu: bool, dZ: torch.T
     rows, H = A.shape
     _check(_lib.des_bias_act_backward(_ptr(A), _ptr(dA), rows, H, int(relu), _ptr(dZ), _ptr(dbias), _ptr(workspace),
                                       _nbytes(workspace), _stream()), "des_bias_act_backward")
+    return dZ, dbias
+
+
+def bias_act_backward_static(A: torch.Tensor, dA: torch.Tensor, relu: bool, dZ: torch.Tensor, dbias: torch.Tensor):
+    """des_bias_act_backward with the library's own scratch array (allocates nothing; H <= 4096)."""
+    rows, H = A.shape
+    _check(_lib.des_bias_act_backward_static(_ptr(A), _ptr(dA), rows, H, int(relu), _ptr(dZ), _ptr(dbias), _stream()),
+           "des_bias_act_backward_static")
     return dZ, dbias
 
 
