@@ -22,11 +22,17 @@ OPT_NONE, OPT_SGD, OPT_ADAGRAD, OPT_ADAM, OPT_FTRL = 0, 1, 2, 3, 4
 OK, ERR_INVALID_ARG, ERR_INVALID_KEY, ERR_FULL = 0, 1, 2, 3
 
 
+_LIB_OMP = os.path.join(_HERE, "libdes_oracle_omp.so")
+
+
 def build(force: bool = True) -> str:
-    """Compile the oracle with gcc (-O2, no FMA contraction so fp32 steps round as written)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-std=c11", "-shared", "-fPIC",
-                               "-o", _LIB, _SRC, "-lm"])
+    """Compile the oracle with gcc (-O2, no FMA contraction so fp32 steps round as written): the plain
+    single-threaded library every test uses, and a second one with -fopenmp for the all-cores leg of the
+    benchmark's CPU baseline (same source, the marked loops split over threads)."""
+    for path, extra in ((_LIB, []), (_LIB_OMP, ["-fopenmp"])):
+        if force or not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_SRC):
+            subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-std=c11", "-shared", "-fPIC", *extra,
+                                   "-o", path, _SRC, "-lm"])
     return _LIB
 
 
@@ -38,13 +44,24 @@ class Optimizer(C.Structure):
 
 
 _lib = None
+_use_openmp = False
+
+
+def use_openmp(on: bool) -> int:
+    """Switch every later call to the OpenMP build (or back); tables created before the switch must not be
+    used after it.  Returns the number of threads the selected build runs on."""
+    global _lib, _use_openmp
+    if bool(on) != _use_openmp:
+        _use_openmp, _lib = bool(on), None
+    return int(lib().oracle_threads())
 
 
 def lib():
     global _lib
     if _lib is None:
         build(force=False)
-        L = C.CDLL(_LIB)
+        L = C.CDLL(_LIB_OMP if _use_openmp else _LIB)
+        L.oracle_threads.restype = C.c_int; L.oracle_threads.argtypes = []
         vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
         L.oracle_mix64.restype = u64; L.oracle_mix64.argtypes = [u64]
         L.oracle_shard.restype = C.c_int; L.oracle_shard.argtypes = [u64, i32, C.c_int, C.c_int]

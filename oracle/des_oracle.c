@@ -30,6 +30,21 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* The default build is single-threaded.  Compiled with -fopenmp (the all-cores leg of the benchmark's CPU
+ * baseline) the loops marked below are split over threads: lookups over entries, the forward pass over samples,
+ * merge + update over distinct rows.  Every iteration of those loops writes only its own outputs, so both
+ * builds compute the same values in the same order per output. */
+int oracle_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
 
 #define ORACLE_OK 0
 #define ORACLE_ERR_INVALID_ARG 1
@@ -37,6 +52,7 @@
 #define ORACLE_ERR_FULL 3
 
 #define ORACLE_EMPTY_KEY 0xFFFFFFFFFFFFFFFFull
+#define ORACLE_MAX_DIM 4096    /* widest row the merge keeps a gradient for */
 
 enum { SHARD_KEY_HASH = 0, SHARD_FIELD_MOD = 1 };
 enum { OPT_NONE = 0, OPT_SGD = 1, OPT_ADAGRAD = 2, OPT_ADAM = 3, OPT_FTRL = 4 };
@@ -83,7 +99,7 @@ typedef struct oracle_table {
 } oracle_table;
 
 oracle_table *oracle_table_create(int D, int64_t capacity, uint64_t seed, float init_scale) {
-  if (D <= 0 || capacity <= 0 || capacity > 2147483646ll) return NULL;
+  if (D <= 0 || D > ORACLE_MAX_DIM || capacity <= 0 || capacity > 2147483646ll) return NULL;
   oracle_table *t = (oracle_table *)calloc(1, sizeof(*t));
   if (!t) return NULL;
   t->D = D; t->capacity = capacity; t->seed = seed; t->init_scale = init_scale;
@@ -183,7 +199,12 @@ int oracle_table_insert(oracle_table *t, const uint64_t *keys, int64_t n, const 
   }
   t->n_rows += u;
   free(cand);
-  if (rows_out) for (int64_t i = 0; i < n; ++i) rows_out[i] = lookup(t, keys[i]);
+  if (rows_out) {
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t i = 0; i < n; ++i) rows_out[i] = lookup(t, keys[i]);
+  }
   return ORACLE_OK;
 }
 
@@ -194,6 +215,9 @@ int oracle_table_find(oracle_table *t, const uint64_t *keys, int64_t n, int inse
   if (!t || n < 0 || (n > 0 && (!keys || !rows_out))) return ORACLE_ERR_INVALID_ARG;
   if (insert_missing) return oracle_table_insert(t, keys, n, NULL, rows_out);
   for (int64_t i = 0; i < n; ++i) if (keys[i] == ORACLE_EMPTY_KEY) return ORACLE_ERR_INVALID_KEY;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
   for (int64_t i = 0; i < n; ++i) rows_out[i] = lookup(t, keys[i]);
   return ORACLE_OK;
 }
@@ -216,6 +240,9 @@ void oracle_partial_forward(const oracle_table *t, int64_t B, int32_t F, const u
   if (P_sum) memset(P_sum, 0, sizeof(double) * (size_t)K * B * D);
   if (P_sq) memset(P_sq, 0, sizeof(double) * (size_t)K * B);
   if (P_pool) memset(P_pool, 0, sizeof(double) * (size_t)K * B * F * D);
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
   for (int64_t b = 0; b < B; ++b)
     for (int32_t f = 0; f < F; ++f)
       for (int32_t e = offsets[b * F + f]; e < offsets[b * F + f + 1]; ++e) {
@@ -336,14 +363,22 @@ int64_t oracle_backward_update_opt(oracle_table *t, int64_t B, int32_t F, const 
       if (rows[e] >= 0) { ent[m].row = rows[e]; ent[m].e = e; ++m; }
     }
   qsort(ent, (size_t)m, sizeof(rowent_t), cmp_rowent);
-  double *G = (double *)malloc(sizeof(double) * (size_t)(D + 1));
+  /* one segment of the sorted list per distinct row: seg[u] .. seg[u+1] */
+  int64_t *seg = (int64_t *)malloc(sizeof(int64_t) * (size_t)(m + 1));
   int64_t U = 0;
-  for (int64_t i = 0; i < m;) {
-    int64_t j = i;
+  for (int64_t i = 0; i < m; ++i)
+    if (i == 0 || ent[i].row != ent[i - 1].row) seg[U++] = i;
+  seg[U] = m;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 256)
+#endif
+  for (int64_t u = 0; u < U; ++u) {
+    double G[ORACLE_MAX_DIM + 1];
+    const int64_t i = seg[u], j = seg[u + 1];
     const int32_t r = ent[i].row;
     for (int c = 0; c <= D; ++c) G[c] = 0.0;
-    for (; j < m && ent[j].row == r; ++j) {
-      const int32_t e = ent[j].e;
+    for (int64_t k = i; k < j; ++k) {
+      const int32_t e = ent[k].e;
       const int64_t bag = bag_of[e], b = bag / F;
       const double x = vals ? (double)vals[e] : 1.0;
       if (g_lr) G[D] += x * (double)g_lr[b];
@@ -354,10 +389,10 @@ int64_t oracle_backward_update_opt(oracle_table *t, int64_t B, int32_t F, const 
         G[d] += x * g;
       }
     }
-    if (uniq_rows) uniq_rows[U] = r;
-    if (uniq_keys) uniq_keys[U] = t->row_keys[r];
-    if (counts) counts[U] = (int32_t)(j - i);
-    if (merged) for (int c = 0; c <= D; ++c) merged[U * (D + 1) + c] = G[c];
+    if (uniq_rows) uniq_rows[u] = r;
+    if (uniq_keys) uniq_keys[u] = t->row_keys[r];
+    if (counts) counts[u] = (int32_t)(j - i);
+    if (merged) for (int c = 0; c <= D; ++c) merged[u * (D + 1) + c] = G[c];
     for (int c = 0; c <= D; ++c) {
       if (c < D)
         optimizer_step(o->opt_emb, o, G[c], &t->emb[(int64_t)r * D + c], &t->acc_emb[(int64_t)r * D + c],
@@ -365,10 +400,9 @@ int64_t oracle_backward_update_opt(oracle_table *t, int64_t B, int32_t F, const 
       else
         optimizer_step(o->opt_w, o, G[c], &t->w[r], &t->acc_w[r], &t->acc2_w[r]);
     }
-    ++U;
-    i = j;
   }
-  free(G); free(bag_of); free(ent);
+  free(seg);
+  free(bag_of); free(ent);
   return U;
 }
 
