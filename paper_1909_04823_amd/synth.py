@@ -247,8 +247,31 @@ class StreamingGenerator:
     def initial_keys(self) -> np.ndarray:
         return self.row_keys.copy()
 
-    def next_batch(self) -> Batch:
+    def grow_to(self, n_rows: int) -> np.ndarray:
+        """Jumps to a later state of the stream without generating the steps in between: appends seeded
+        random distinct IDs until `n_rows` rows are known and returns the appended IDs in row order (the
+        caller inserts them into the table in this order, in one or several calls)."""
+        rng = _step_rng(self.w, int(n_rows), stream=9)
+        added = np.empty(0, dtype=np.uint64)
+        while self.row_keys.shape[0] + added.shape[0] < n_rows:
+            need = n_rows - self.row_keys.shape[0] - added.shape[0]
+            cand = rng.integers(0, 2**64 - 1, size=need + need // 64 + 16, dtype=np.uint64)
+            # distinct, unseen, in order of first occurrence
+            u, first = np.unique(cand, return_index=True)
+            cand = u[np.argsort(first, kind="stable")]
+            for known in (self._known_sorted, np.sort(added)):
+                if known.size:
+                    pos = np.minimum(np.searchsorted(known, cand), known.shape[0] - 1)
+                    cand = cand[known[pos] != cand]
+            added = np.concatenate([added, cand[:need]])
+        self.row_keys = np.concatenate([self.row_keys, added])
+        self._known_sorted = np.sort(self.row_keys)
+        return added
+
+    def next_batch(self, p_new: Optional[float] = None) -> Batch:
+        """The next batch; `p_new` overrides the workload's probability of a brand-new ID for this batch."""
         w = self.w
+        p_new = w.p_new if p_new is None else float(p_new)
         rng = _step_rng(w, self.step, stream=1)
         lens = bag_lengths(rng, w)
         offsets = np.zeros(w.B * w.F + 1, dtype=np.int64)
@@ -258,7 +281,7 @@ class StreamingGenerator:
         ranks = zipf_truncated(rng, w.zipf_a, n_rows, nnz)
         rows = (ranks * self._PERM_MULT) % n_rows
         keys = self.row_keys[rows]
-        fresh = rng.random(nnz) < w.p_new
+        fresh = rng.random(nnz) < p_new
         n_fresh = int(fresh.sum())
         keys[fresh] = rng.integers(0, 2**64 - 1, size=n_fresh, dtype=np.uint64)  # excludes the reserved ID
         # mirror of the table: unseen distinct IDs become new rows in order of first occurrence

@@ -60,6 +60,43 @@ def test_init_value_is_uniform_with_requested_std(oracle):
     assert np.float32(oracle.init_value(5, 3, 77, scale)) == np.float32((np.float32(u24) / np.float32(2**24) - np.float32(0.5)) * width)
 
 
+def _py_mix64(z: int) -> int:
+    """The published SplitMix64 finalizer in Python integers (independent of the C oracle)."""
+    m = (1 << 64) - 1
+    z &= m
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & m
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & m
+    return z ^ (z >> 31)
+
+
+def test_init_value_exact_form_on_many_triples(oracle):
+    """The initialiser, evaluated independently in Python integers and exact rationals for several
+    hundred (ID, column, seed) triples: the top 24 bits of the hash as u = n/2^24, u - 1/2 (exact in
+    fp32), times the fp32 width, rounded once.  A variant that keeps 23 or 25 bits, shifts by another
+    amount, centres differently or mixes seed and column another way fails here."""
+    from fractions import Fraction
+    rng = np.random.default_rng(2024)
+    assert _py_mix64(0x9E3779B97F4A7C15) == 0xE220A8397B1DCDAF         # the Python copy is the published function
+    checked = 0
+    for scale in (0.01, 0.5, 1.0 / 3.0):
+        width = np.float32(2.0 * np.sqrt(3.0) * np.float64(np.float32(scale)))
+        keys = np.concatenate([rng.integers(0, 2**64 - 1, 60, dtype=np.uint64),
+                               np.array([0, 1, 2**63, 2**64 - 2, 0xFFFFFFFF, 1 << 40], dtype=np.uint64)])
+        for key in keys.tolist():
+            for c in (0, 1, 7, 63, 64, 256):
+                for seed in (0, 77, 190904823_03, 2**64 - 1):
+                    n24 = _py_mix64(key ^ _py_mix64(seed + c)) >> 40
+                    exact = (Fraction(n24, 1 << 24) - Fraction(1, 2)) * Fraction(float(width))
+                    expect = np.float32(float(exact))       # 24-bit x 24-bit product: exact in double, one rounding to fp32
+                    got = np.float32(oracle.init_value(key, c, seed, scale))
+                    assert got == expect, (key, c, seed, scale, got, expect)
+                    checked += 1
+    assert checked > 4000
+    # all 24 bits matter: some value has its lowest fraction bit set
+    odd = [(_py_mix64(k ^ _py_mix64(77 + 0)) >> 40) & 1 for k in range(1, 50)]
+    assert 0 < sum(odd) < 49
+
+
 def test_shard_policies(oracle):
     K = 7
     for f in range(20):
@@ -228,6 +265,32 @@ def test_partial_sizes_reproduce_printed_comm_saving_table(oracle):
         s_fm = (P["P_sum"][0].size + P["P_sq"][0].size) * 4
         assert f"{100 * (1 - 2 * s_lr / (U * (8 + 4))):.3f}" == r_lr
         assert f"{100 * (1 - 2 * s_fm / (U * (8 + 4 * d))):.3f}" == r_fm
+
+
+def test_partial_buffers_written_by_the_c_oracle_have_the_printed_sizes(oracle):
+    """The same sizes taken from what the C function itself writes, not from the wrapper's array shapes: the
+    partial buffers are handed over inside larger NaN-filled arrays, and exactly K*B (LR M1), K*B*d (FM M1) and
+    K*B (FM M2) elements must come back written, none beyond.  With them the first printed row reproduces."""
+    import ctypes as C
+    d, K, B = 8, 4, 512
+    t = oracle.Table(d, 8); t.insert(np.arange(1, 5, dtype=np.uint64))
+    keys = (np.arange(B, dtype=np.uint64) % np.uint64(4)) + np.uint64(1)
+    off = np.arange(B + 1, dtype=np.int32)
+    rows = t.find(keys)
+    pad = 64
+    bufs = {n: np.full(sz + pad, np.nan) for n, sz in (("lr", K * B), ("sum", K * B * d), ("sq", K * B))}
+    p = lambda a: a.ctypes.data_as(C.c_void_p)
+    oracle.lib().oracle_partial_forward(t._h, B, 1, p(keys), p(off), None, p(rows), K, 0, p(bufs["lr"]), p(bufs["sum"]),
+                                        p(bufs["sq"]), None)
+    written = {n: int(np.isfinite(a).sum()) for n, a in bufs.items()}
+    assert written == {"lr": K * B, "sum": K * B * d, "sq": K * B}
+    for a in bufs.values():
+        assert np.isnan(a[-pad:]).all() and np.isfinite(a[:-pad]).all()
+    U = 147664                                   # first row of the printed table: batch 512
+    s_lr = written["lr"] // K * 4
+    s_fm = (written["sum"] + written["sq"]) // K * 4
+    assert f"{100 * (1 - 2 * s_lr / (U * (8 + 4))):.3f}" == "99.769"
+    assert f"{100 * (1 - 2 * s_fm / (U * (8 + 4 * d))):.3f}" == "99.376"
 
 
 # --------------------------------------------------------------------------- DNN layer -----
@@ -837,3 +900,36 @@ def test_migrate_against_python_dict(oracle):
         t.migrate(None, new_capacity=keys.size - 1)
     e = t.migrate(np.zeros(keys.size, bool))
     assert e.n_rows == 0 and e.find(keys[:3]).tolist() == [-1, -1, -1]
+
+
+def test_last_seen_helpers_hand_examples(oracle):
+    """mark_seen / select_recent against values worked out by hand: absent entries (row -1) mark nothing, a
+    repeated row is marked once, unmarked rows keep their stamp, and the boundary stamp == min_stamp is kept."""
+    last = np.array([0, 5, 0, 2, 9, 0], dtype=np.uint32)
+    oracle.mark_seen(last, np.array([3, -1, 1, 3, -1], dtype=np.int32), 7)
+    assert last.tolist() == [0, 7, 0, 7, 9, 0]                    # rows 1 and 3 stamped; -1 did not touch the last row
+    oracle.mark_seen(last, np.array([], dtype=np.int32), 8)
+    assert last.tolist() == [0, 7, 0, 7, 9, 0]
+    assert oracle.select_recent(last, 6, 7).tolist() == [0, 1, 0, 1, 1, 0]     # 7 >= 7 is kept
+    assert oracle.select_recent(last, 6, 8).tolist() == [0, 0, 0, 0, 1, 0]
+    assert oracle.select_recent(last, 6, 0).tolist() == [1, 1, 1, 1, 1, 1]
+    assert oracle.select_recent(last, 4, 9).tolist() == [0, 0, 0, 0]            # only the first n_rows rows
+    assert oracle.select_recent(last, 5, 10).dtype == np.uint8
+    # stamps are unsigned 32-bit: the largest stamp is recent, not negative
+    last[0] = np.uint32(2**32 - 1)
+    assert oracle.select_recent(last, 2, 2**31).tolist() == [1, 0]
+
+
+def test_streaming_generator_jump_and_insert_fraction():
+    w = synth.workload(3, scale=1 / 512)
+    gen = synth.StreamingGenerator(w)
+    n0 = gen.row_keys.size
+    added = gen.grow_to(7 * n0)
+    assert added.size == 6 * n0 and gen.row_keys.size == 7 * n0 and np.unique(gen.row_keys).size == 7 * n0
+    assert not (gen.row_keys == synth.RESERVED_KEY).any()
+    np.testing.assert_array_equal(gen.row_keys[n0:], added)
+    b = gen.next_batch(p_new=0.30)                                  # the literal "30 % unseen" reading of the workload
+    new = gen.row_keys.size - 7 * n0
+    assert abs(new / b.nnz - 0.30) < 0.02
+    b2 = gen.next_batch()
+    assert abs((gen.row_keys.size - 7 * n0 - new) / b2.nnz - w.p_new) < 0.01
