@@ -18,9 +18,11 @@
  *     enqueue work and return, except des_table_create/size/status/destroy/migrate and
  *     des_profile_read, which synchronise.
  *   - Errors the host can see (null pointers, bad sizes, buffers too small) return at once
- *     and enqueue nothing.  Errors only the device can see (table full, reserved key) set a
- *     sticky status word in device memory: des_table_status returns it, and every later
- *     table-modifying call on that table becomes a no-op.
+ *     and enqueue nothing.  Errors only the device can see live in device memory and are read
+ *     by des_table_status.  "Table full" is sticky: the call that would exceed the capacity
+ *     inserts nothing, and every later insert on that table degrades to a lookup, until
+ *     des_table_clear_status.  A reserved key is not: that entry is treated as absent (row -1),
+ *     the rest of the call proceeds, and the table keeps a note that des_table_status reports.
  *   - Calls on one table must be ordered (same stream, or externally synchronised); two
  *     tables are independent.
  *   - Supported shapes: dim a power of two in [4, 256]; 1 <= num_shards <= 256;
@@ -41,7 +43,7 @@
  *   initialiser   column c of a row inserted without values is
  *                 ((mix64(key ^ mix64(seed+c)) >> 40) * 2^-24 - 0.5) * (float)(2*sqrt(3)*init_scale)
  *                 (c < dim latent, c == dim the LR weight); optimizer state starts at 0.
- *   reserved key  0xFFFFFFFFFFFFFFFF marks an empty slot and is rejected.
+ *   reserved key  0xFFFFFFFFFFFFFFFF marks an empty slot; as an ID it is never found and never inserted.
  */
 #ifndef DES_H_
 #define DES_H_
@@ -58,7 +60,7 @@ typedef struct des_table des_table_t;   /* opaque host handle */
 typedef enum {
   DES_OK = 0,
   DES_ERR_INVALID_ARG = 1,   /* null / negative / unsupported shape / misaligned            */
-  DES_ERR_INVALID_KEY = 2,   /* the reserved key was passed (device-detected, sticky)       */
+  DES_ERR_INVALID_KEY = 2,   /* the reserved key was passed (device-detected, not blocking) */
   DES_ERR_FULL = 3,          /* capacity_rows or the slot array exhausted (sticky)          */
   DES_ERR_WORKSPACE = 4,     /* slots or workspace smaller than des_table_query_bytes says  */
   DES_ERR_DEVICE = 5         /* a HIP runtime call failed                                   */
@@ -74,7 +76,10 @@ typedef struct {
   int64_t capacity_rows;       /* fixed for the table's life; to grow, des_table_migrate      */
   int32_t num_shards;          /* K logical DES workers                                      */
   int32_t shard_policy;        /* des_shard_policy_t                                         */
-  int32_t opt;                 /* des_opt_t; ADAGRAD requires acc_emb and acc_w              */
+  int32_t opt;                 /* des_opt_t the table is meant for; only checked at creation: the state
+                                  arrays that optimizer needs must be given (ADAGRAD acc_*, ADAM acc_* and
+                                  acc2_*, FTRL acc_w and acc2_w).  DES_OPT_NONE skips the check.  The optimizer
+                                  itself comes with every update call, which checks its own arrays again   */
   uint64_t init_seed;
   float init_scale;            /* standard deviation of the initialiser                      */
   float *emb;                  /* device [capacity, D]   latent vectors v                    */
@@ -125,7 +130,23 @@ des_status_t des_table_find(des_table_t *t, const uint64_t *keys, int64_t n, int
                             int32_t *rows_out, void *stream);
 
 des_status_t des_table_size(des_table_t *t, int64_t *n_rows_host);   /* synchronises */
+
+/* Device-side condition of the table (synchronises): DES_ERR_FULL (or DES_ERR_DEVICE) if the sticky status is
+ * set, else DES_ERR_INVALID_KEY if a reserved key was passed since the last des_table_clear_status, else DES_OK. */
 des_status_t des_table_status(des_table_t *t);
+
+/* Starts the status over (synchronises).  After DES_ERR_FULL the table is exactly as before the failed call
+ * except that the keys that call tried to add hold a hash slot without a row; they get their row the next time
+ * they are inserted.  The table is still as full as it was: make room with des_table_compact, or move to a
+ * larger table with des_table_migrate (both rebuild the slots and drop such leftovers), then insert again.
+ * Also forgets the reserved keys seen so far. */
+des_status_t des_table_clear_status(des_table_t *t);
+
+/* Third table operation besides lookup and insert (Section 5, "Dynamic Hash Table"): the IDs the table holds.
+ * Copies row_keys[0 .. min(n_rows, max_rows)) to row_keys_out (device, 8-byte aligned, max_rows entries);
+ * entry r is the ID of row r.  The row count is read on the device, so no synchronisation; size the buffer from
+ * des_table_size or the capacity.  (des_table_config_t.row_keys is the same map, owned by the caller.) */
+des_status_t des_table_export_keys(des_table_t *t, uint64_t *row_keys_out, int64_t max_rows, void *stream);
 
 /* ---- Growth and eviction (Section 1, "Dynamic Features": the parameter set of a streaming
  * recommender changes and grows over time; Section 5).  The paper gives the requirement, not a
@@ -235,7 +256,7 @@ des_status_t des_dnn_backward(const float *pool, const float *W, const float *dY
 
 /* Backward (Section 3.2.2, back-propagation phase: the gradient of each aggregate goes
  * unchanged to every shard's sub-operator; no exchange), duplicate-key merge and optimizer
- * update (Section 5: "given the gradient of a weight, we apply it locally, and then update").
+ * update (Section 5, "Dynamic Hash Table": a weight's gradient is applied where the weight lives).
  * Entry e of bag (b,f), value x, row r:   d/dw_r = x*g_lr[b]
  *     d/dv_r = x*( g_fm[b]*(A_sum[b,:] - x*v_r) + g_pool[b,f,:] )
  * summed over the entries of a row; rows are visited in ascending row order; the update reads
@@ -260,8 +281,8 @@ typedef struct {
  * second stream while the forward pass and the loss head run on the first.  The sorted form stays in
  * the table's workspace; the next des_backward_update* / des_backward_merge call for the same batch
  * (same offsets, vals and rows pointers, same sizes) skips that half, any other call recomputes it.
- * A des_table_insert or a des_table_find with DES_MISS_INSERT in between discards it (same
- * workspace).  The caller orders the streams: prepare after the find that wrote `rows`, the update
+ * Any des_table_insert or des_table_find on the table in between discards it (an insert reuses the
+ * workspace; a lookup may be refilling the rows array).  The caller orders the streams: prepare after the find that wrote `rows`, the update
  * after prepare.  Results are identical with and without this call. */
 des_status_t des_backward_prepare(des_table_t *t, const des_batch_t *batch, const int32_t *rows, void *stream);
 

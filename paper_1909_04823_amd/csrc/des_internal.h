@@ -26,8 +26,9 @@ struct Ctrl {
   long long n_uniq;        // distinct rows of the running backward call
   long long n_long;        // segments longer than the short-segment limit
   long long n_chunks;      // chunks those long segments were cut into
-  int status;              // sticky des_status_t
-  int pad[5];
+  int status;              // sticky des_status_t (table full): inserts stop until it is cleared
+  int bad_keys;            // reserved keys seen since the status was last cleared (reported, not blocking)
+  int pad[4];
   unsigned long long first_bad;   // verdict word of des_batch_validate
   long long n_multi;       // long segments of more than one chunk
   long long n_groups;      // groups of chunk partials that are pre-summed for the segments of very many chunks
@@ -108,5 +109,8 @@ des_status_t backward_launch(des_table *t, const des_batch_t *b, const int32_t *
                              const des_optimizer_t *opt, hipStream_t s);
 des_status_t backward_prepare_launch(des_table *t, const des_batch_t *b, const int32_t *rows, hipStream_t s);
 size_t backward_ws_bytes(int D, int64_t max_n);
+// The sticky status alone (table full, HIP error): what stops a table from growing or being reorganised.  Reserved keys
+// that were passed are reported by des_table_status but block nothing.  Synchronises like des_table_status.
+des_status_t blocking_status(des_table *t);
 size_t insert_ws_bytes(int64_t max_n);
 }  // namespace des

@@ -212,7 +212,7 @@ des_status_t des_table_migrate(des_table_t *src, const uint8_t *keep, des_table_
   if (st != DES_OK) return st;
   st = des_table_size(dst, &n_dst);
   if (st != DES_OK) return st;
-  if (n_dst != 0 || des_table_status(dst) != DES_OK || des_table_status(src) != DES_OK) return DES_ERR_INVALID_ARG;
+  if (n_dst != 0 || blocking_status(dst) != DES_OK || blocking_status(src) != DES_OK) return DES_ERR_INVALID_ARG;
   const size_t row_bytes = (size_t)sc.dim * 4;
   if (overlap(sc.emb, (size_t)sc.capacity_rows * row_bytes, dc.emb, (size_t)dc.capacity_rows * row_bytes) ||
       overlap(sc.row_keys, (size_t)sc.capacity_rows * 8, dc.row_keys, (size_t)dc.capacity_rows * 8) ||
@@ -257,7 +257,7 @@ des_status_t des_table_migrate(des_table_t *src, const uint8_t *keep, des_table_
                        (const uint64_t *)dc.row_keys, (int64_t)kept, dst->ctrl);
   if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return DES_ERR_DEVICE;
   if (n_rows_out) *n_rows_out = kept;
-  return (des_status_t)des_table_status(dst);
+  return blocking_status(dst);
 }
 
 des_status_t des_table_compact(des_table_t *t, const uint8_t *keep, uint32_t *aux, void *staging, size_t staging_bytes,
@@ -268,7 +268,7 @@ des_status_t des_table_compact(des_table_t *t, const uint8_t *keep, uint32_t *au
   int64_t n = 0;
   des_status_t st = des_table_size(t, &n);
   if (st != DES_OK) return st;
-  if (des_table_status(t) != DES_OK) return DES_ERR_INVALID_ARG;
+  if (blocking_status(t) != DES_OK) return DES_ERR_INVALID_ARG;
   if (n_rows_out) *n_rows_out = n;
   t->last_stream = s;
   t->prep.valid = false;
@@ -305,7 +305,7 @@ des_status_t des_table_compact(des_table_t *t, const uint8_t *keep, uint32_t *au
                        (const uint64_t *)c.row_keys, (int64_t)kept, t->ctrl);
   if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return DES_ERR_DEVICE;
   if (n_rows_out) *n_rows_out = kept;
-  return (des_status_t)des_table_status(t);
+  return blocking_status(t);
 }
 
 des_status_t des_batch_validate(des_table_t *t, const des_batch_t *batch, const int32_t *rows, int64_t *first_bad,

@@ -9,6 +9,7 @@
 // the entries that ARE the first occurrence of a new key are counted with a prefix sum in
 // entry order, row = n_rows + prefix.
 #include <math.h>
+#include <stddef.h>
 #include <string.h>
 #include <new>
 #include <vector>
@@ -47,8 +48,8 @@ __global__ __launch_bounds__(kBlock) void k_probe(Slot *__restrict__ slots, uint
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) {
     const uint64_t key = keys[e];
     int32_t out = kRowAbsent;
-    if (key == kEmptyKey) {
-      set_status(ctrl, DES_ERR_INVALID_KEY);
+    if (key == kEmptyKey) {                        // the reserved key is nobody's ID: absent, counted, nothing else is held up
+      atomicAdd(&ctrl->bad_keys, 1);
       rows[e] = out;
       continue;
     }
@@ -303,7 +304,26 @@ __global__ __launch_bounds__(kBlock) void k_fill_u64x2(uint4 *__restrict__ p, in
 
 __global__ void k_zero_ctrl(Ctrl *ctrl) {
   ctrl->n_rows = 0; ctrl->n_new = 0; ctrl->n_uniq = 0; ctrl->n_long = 0; ctrl->n_chunks = 0; ctrl->status = 0;
-  ctrl->n_multi = 0; ctrl->n_groups = 0;
+  ctrl->n_multi = 0; ctrl->n_groups = 0; ctrl->bad_keys = 0;
+}
+
+// des_table_clear_status: the status words start over, and the slots that a failed insert claimed without
+// giving them a row forget that call's entry numbers, so that the next insert of their key numbers them afresh.
+__global__ __launch_bounds__(kBlock) void k_clear_status(Slot *__restrict__ slots, uint64_t n_slots, Ctrl *ctrl) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < (int64_t)n_slots; i += stride) {
+    const Slot s = load_slot(&slots[i]);
+    if (s.key != kEmptyKey && s.row < 0 && s.first != 0xFFFFFFFFu) slots[i].first = 0xFFFFFFFFu;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) { ctrl->status = 0; ctrl->bad_keys = 0; ctrl->n_new = 0; }
+}
+
+// Copy of the row -> key map for the rows in use (the count lives on the device).
+__global__ __launch_bounds__(kBlock) void k_export_keys(const Ctrl *__restrict__ ctrl, const uint64_t *__restrict__ row_keys,
+                                                         uint64_t *__restrict__ out, int64_t max_rows) {
+  const int64_t n = min((int64_t)ctrl->n_rows, max_rows);
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) out[i] = row_keys[i];
 }
 
 // out[i] = sum over the K shards of P[s*n + i], summed in double and rounded once
@@ -453,6 +473,13 @@ const char *kKernelNames[KID_COUNT] = {
     "cross_partial", "cross_apply", "cross_backward"};
 }  // namespace
 
+des_status_t blocking_status(des_table *t) {
+  int v = 0;
+  if (hipStreamSynchronize(t->last_stream) != hipSuccess) return DES_ERR_DEVICE;
+  if (hipMemcpy(&v, &t->ctrl->status, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return DES_ERR_DEVICE;
+  return (des_status_t)v;
+}
+
 void prof_begin(int kid, hipStream_t s) {
   if (!g_prof_on) return;
   hipEvent_t e;
@@ -478,7 +505,7 @@ const char *des_status_string(des_status_t s) {
   switch (s) {
     case DES_OK: return "ok";
     case DES_ERR_INVALID_ARG: return "invalid argument";
-    case DES_ERR_INVALID_KEY: return "reserved key passed";
+    case DES_ERR_INVALID_KEY: return "reserved key passed (treated as absent)";
     case DES_ERR_FULL: return "table full";
     case DES_ERR_WORKSPACE: return "slots or workspace too small";
     case DES_ERR_DEVICE: return "HIP runtime error";
@@ -576,7 +603,9 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
   if (!t || n < 0 || n >= 2147483647ll || (n > 0 && !keys)) return DES_ERR_INVALID_ARG;
   if (((uintptr_t)keys & 7u) || ((uintptr_t)rows_out & 3u) || ((uintptr_t)values & 3u)) return DES_ERR_INVALID_ARG;
   t->last_stream = s;
-  if (insert) t->prep.valid = false;             // inserts and a prepared batch share the workspace
+  // a prepared (row-sorted) batch does not survive any lookup: an insert reuses its workspace, and a lookup may
+  // be refilling the very rows array the sorted form was built from
+  t->prep.valid = false;
   if (n == 0) return DES_OK;
   if (insert && insert_ws_bytes(n) > t->ws_bytes) return DES_ERR_WORKSPACE;
   const uint64_t mask = t->n_slots - 1;
@@ -649,10 +678,34 @@ des_status_t des_table_size(des_table_t *t, int64_t *n_rows_host) {
 
 des_status_t des_table_status(des_table_t *t) {
   if (!t) return DES_ERR_INVALID_ARG;
-  int v = 0;
+  int v[2] = {0, 0};                               // status, bad_keys: adjacent in the control block
+  static_assert(offsetof(Ctrl, bad_keys) == offsetof(Ctrl, status) + sizeof(int), "read as one pair");
   if (hipStreamSynchronize(t->last_stream) != hipSuccess) return DES_ERR_DEVICE;
-  if (hipMemcpy(&v, &t->ctrl->status, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return DES_ERR_DEVICE;
-  return (des_status_t)v;
+  if (hipMemcpy(v, &t->ctrl->status, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return DES_ERR_DEVICE;
+  if (v[0] != 0) return (des_status_t)v[0];
+  return v[1] != 0 ? DES_ERR_INVALID_KEY : DES_OK;
+}
+
+des_status_t des_table_clear_status(des_table_t *t) {
+  if (!t) return DES_ERR_INVALID_ARG;
+  hipStream_t s = t->last_stream;
+  t->prep.valid = false;
+  hipLaunchKernelGGL(k_clear_status, dim3(grid_for((int64_t)t->n_slots, kBlock, 65536)), dim3(kBlock), 0, s, t->slots,
+                     t->n_slots, t->ctrl);
+  if (hipStreamSynchronize(s) != hipSuccess || hipGetLastError() != hipSuccess) return DES_ERR_DEVICE;
+  return DES_OK;
+}
+
+des_status_t des_table_export_keys(des_table_t *t, uint64_t *row_keys_out, int64_t max_rows, void *stream) {
+  if (!t || max_rows < 0 || (max_rows > 0 && !row_keys_out) || ((uintptr_t)row_keys_out & 7u)) return DES_ERR_INVALID_ARG;
+  if (max_rows == 0) return DES_OK;
+  hipStream_t s = (hipStream_t)stream;
+  t->last_stream = s;
+  ProfScope ps(KID_EXPORT, s);
+  const int64_t most = max_rows < t->cfg.capacity_rows ? max_rows : t->cfg.capacity_rows;
+  hipLaunchKernelGGL(k_export_keys, dim3(grid_for(most, kBlock, 65536)), dim3(kBlock), 0, s, t->ctrl, t->cfg.row_keys,
+                     row_keys_out, max_rows);
+  return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
 }
 
 des_status_t des_aggregate_partials(const float *P, int32_t K, int64_t n, float *out, void *stream) {

@@ -24,7 +24,7 @@ MISS_ZERO, MISS_INSERT = 0, 1
 
 EXPORTS = [
     "des_table_query_bytes", "des_table_create", "des_table_destroy", "des_table_insert", "des_table_find",
-    "des_table_size", "des_table_status", "des_partial_forward_lr", "des_partial_forward_fm",
+    "des_table_size", "des_table_status", "des_table_clear_status", "des_table_export_keys", "des_partial_forward_lr", "des_partial_forward_fm",
     "des_partial_forward_pool", "des_partial_forward", "des_aggregate_partials", "des_aggregate_forward", "des_fm_finalize",
     "des_backward_update_sgd", "des_backward_update_adagrad", "des_backward_update", "des_backward_merge", "des_backward_prepare",
     "des_dnn_partial_forward", "des_dnn_backward_bytes", "des_dnn_backward",
@@ -76,6 +76,8 @@ _sig = {
     "des_table_find": [vp, vp, i64, i32, vp, vp],
     "des_table_size": [vp, C.POINTER(i64)],
     "des_table_status": [vp],
+    "des_table_clear_status": [vp],
+    "des_table_export_keys": [vp, vp, i64, vp],
     "des_partial_forward_lr": [vp, C.POINTER(BatchDesc), vp, vp, vp],
     "des_partial_forward_fm": [vp, C.POINTER(BatchDesc), vp, vp, vp, vp],
     "des_partial_forward_pool": [vp, C.POINTER(BatchDesc), vp, vp, i32, vp],
@@ -264,6 +266,16 @@ class Table:
 
     def status(self) -> int:
         return int(_lib.des_table_status(self._h))
+
+    def clear_status(self):
+        _check(_lib.des_table_clear_status(self._h), "des_table_clear_status")
+
+    def export_keys(self, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """IDs of the rows in use, in row order (int64 tensor holding the uint64 bit patterns)."""
+        if out is None:
+            out = torch.empty(self.size(), dtype=torch.int64, device=self.emb.device)
+        _check(_lib.des_table_export_keys(self._h, _ptr(out), out.numel(), _stream()), "des_table_export_keys")
+        return out
 
     # ---- forward ----------------------------------------------------------------------------
     def partial_forward_lr(self, batch: Batch, rows, P_lr):

@@ -66,15 +66,22 @@ def expected_rows(keys, known_keys):
     return rows.astype(np.int32), new_keys
 
 
-def run_full_size(oracle, des, index, n_fwd_samples, n_bwd_keys):
+def run_full_size(oracle, des, index, n_fwd_samples, n_bwd_keys, grown_rows=None, p_new=None):
+    """`grown_rows`: streaming workload only, the table holds that many rows before the checked step (the stream's
+    later state; the rows beyond the initial ones are the generator's seeded random IDs, inserted in bulk).
+    `p_new`: probability of a brand-new ID per entry in the checked step (default: the workload's)."""
     import torch
     w = synth.workload(index)
-    tag = f"workload {index}"
+    tag = f"workload {index}" + (f" at {grown_rows} rows" if grown_rows else "") + (f", p_new {p_new}" if p_new else "")
     progress(f"{tag}: generating batch")
+    n_known = w.preinsert
     if w.p_new:
         gen = synth.StreamingGenerator(w)
+        if grown_rows:
+            gen.grow_to(grown_rows)
         known = gen.initial_keys()
-        batch = gen.next_batch()
+        n_known = known.size
+        batch = gen.next_batch(p_new)
     else:
         known = None
         batch = synth.gen_batch(w, 0)
@@ -84,16 +91,17 @@ def run_full_size(oracle, des, index, n_fwd_samples, n_bwd_keys):
     if free < 1.15 * need:
         pytest.skip(f"needs about {need / 2**30:.0f} GiB of free HBM")
 
-    progress(f"{tag}: building the table ({w.preinsert} rows)")
+    progress(f"{tag}: building the table ({n_known} rows)")
     chunk = 1 << 22
     t = des.Table(D, w.capacity, K, des.SHARD_KEY_HASH, des.OPT_ADAGRAD, init_seed=w.seed, init_scale=w.init_std,
-                  max_n=max(nnz, min(chunk, w.preinsert)))
+                  max_n=max(nnz, min(chunk, n_known)))
     if known is not None:
-        t.insert(dev(known, torch))
+        for lo in range(0, n_known, chunk):
+            t.insert(dev(known[lo:lo + chunk], torch))
     else:
         for lo in range(0, w.preinsert, chunk):
             t.insert(dev(synth.preinsert_keys(w, lo, min(w.preinsert, lo + chunk)), torch))
-    assert t.status() == 0 and t.size() == w.preinsert
+    assert t.status() == 0 and t.size() == n_known
 
     # ---- find: all integers ------------------------------------------------------------------
     progress(f"{tag}: find + integer checks")
@@ -117,8 +125,10 @@ def run_full_size(oracle, des, index, n_fwd_samples, n_bwd_keys):
         exp_rows = exp_rows.astype(np.int32)
     assert_equal(rows_h, exp_rows, "rows")
     n_rows = t.size()
-    assert n_rows == w.preinsert + new_keys.size and t.status() == 0
-    assert_equal(host_u64(t.row_keys[w.preinsert:n_rows]), new_keys, "row_keys of the new rows")
+    assert n_rows == n_known + new_keys.size and t.status() == 0
+    assert_equal(host_u64(t.row_keys[n_known:n_rows]), new_keys, "row_keys of the new rows")
+    if p_new:
+        assert abs(new_keys.size / nnz - p_new) < 0.01, "the step does not insert the intended share of new IDs"
     sel = np.random.default_rng(7).integers(0, nnz, 4096)
     assert_equal(host_u64(t.row_keys[torch.from_numpy(rows_h[sel].astype(np.int64)).cuda()]), batch.keys[sel], "row_keys[rows]")
 
@@ -203,7 +213,7 @@ def run_full_size(oracle, des, index, n_fwd_samples, n_bwd_keys):
         assert float(t.emb[int(untouched[0]), 1]) == np.float32(oracle.init_value(k0, 1, w.seed, w.init_std))
     ot.close()
     t.close()
-    progress(f"{tag}: done (nnz={nnz}, U={U}, hottest count={int(counts.max())})")
+    progress(f"{tag}: done (nnz={nnz}, U={U}, new rows={new_keys.size}, rows={n_rows}, hottest count={int(counts.max())})")
 
 
 def test_full_size_deepfm(oracle, des):
@@ -212,6 +222,21 @@ def test_full_size_deepfm(oracle, des):
 
 def test_full_size_streaming_first_step(oracle, des):
     run_full_size(oracle, des, 3, n_fwd_samples=256, n_bwd_keys=3000)
+
+
+def test_full_size_streaming_grown_table(oracle, des):
+    """The streaming workload in the state it is about (Section 5, dynamic hash table; Section 1, dynamic
+    features): 4.9e7 of the 5.2e7 rows in use (slot load 0.73), one step that looks up, inserts ~245,000 unseen
+    IDs and updates with Adagrad.  Row numbers, the new rows' keys, the table size and the merged order are
+    checked in full, the fp32 results on samples."""
+    run_full_size(oracle, des, 3, n_fwd_samples=256, n_bwd_keys=3000, grown_rows=49_000_000)
+
+
+def test_full_size_streaming_insert_heavy_step(oracle, des):
+    """The same grown table with a step in which 30 % of the entries are brand-new IDs (2.4e6 inserts in one
+    call: the literal reading of the workload's description, which cannot be kept up for 200 steps inside
+    5e7 rows but can for one)."""
+    run_full_size(oracle, des, 3, n_fwd_samples=128, n_bwd_keys=2000, grown_rows=49_000_000, p_new=0.30)
 
 
 def test_full_size_large_table(oracle, des):
