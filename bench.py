@@ -67,13 +67,16 @@ PROFILE_TAG = {0: "tiny_lr_fm", 1: "dlrm_pooled", 2: "deepfm", 3: "streaming", 4
 
 
 def measured_traffic(index: int, label: str):
-    """HBM bytes per launch of kernel `label` from the committed rocprofv3 counter summary of this
-    workload (profiles/<tag>_hbm_traffic.md, columns fetch MB / write MB), or None."""
+    """(HBM bytes per launch of kernel `label`, commit the counters were collected at) from the committed
+    rocprofv3 counter summary of this workload (profiles/<tag>_hbm_traffic.md: columns fetch MB / write MB, and a
+    line "Measured at commit: <id>"), or (None, None)."""
     path = os.path.join(ROOT, "profiles", f"{PROFILE_TAG[index]}_hbm_traffic.md")
     if not os.path.exists(path):
-        return None
-    total, seen = 0.0, False
+        return None, None
+    total, seen, commit = 0.0, False, None
     for line in open(path):
+        if line.lower().startswith("measured at commit:"):
+            commit = line.split(":", 1)[1].strip().strip("`")
         cells = [c.strip() for c in line.split("|")]
         if len(cells) >= 6 and cells[2] == label:
             try:
@@ -81,43 +84,63 @@ def measured_traffic(index: int, label: str):
                 seen = True
             except ValueError:
                 pass
-    return int(total) if seen else None
+    return (int(total), commit) if seen else (None, commit)
 
 
 def cpu_baseline(w, batch, sample_B, opt_code):
     """The oracle, as it stands, on the first `sample_B` samples of batch 0 with a table that
     holds exactly the IDs those samples touch (pre-inserted head with initialiser weights; the
-    rest is inserted by the timed lookup, as on the GPU)."""
+    rest is inserted by the timed lookup, as on the GPU).  Two legs: the plain single-threaded
+    build on half of the sample, then the OpenMP build of the same source (lookups split over entries,
+    forward over samples, merge + update over distinct rows) on the whole sample with the threads
+    the box gives this process."""
     import oracle
     F, D = w.F, w.D
-    nb = min(sample_B, w.B)
-    end = int(batch.offsets[nb * F])
-    keys, offsets = batch.keys[:end].copy(), batch.offsets[:nb * F + 1].copy()
-    if batch.ranks is not None:
-        head = np.unique(keys[batch.ranks[:end] <= w.preinsert])
-    else:
-        head = np.unique(keys)
-    t = oracle.Table(D, head.size + np.unique(keys).size + 16, seed=w.seed, init_scale=w.init_std)
-    t.insert(head)
     rng = np.random.default_rng(1)
-    g_lr = (rng.standard_normal(nb) / w.B).astype(np.float32)
-    g_fm = (rng.standard_normal(nb) / w.B).astype(np.float32)
-    g_pool = (rng.standard_normal((nb, F, D)) / w.B).astype(np.float32)
-    t0 = time.perf_counter()
-    rows = t.find(keys, insert_missing=True)
-    P = t.partial_forward(nb, F, keys, offsets, rows, w.K, 0, None, pool=False)
-    pool = t.partial_forward(nb, F, keys, offsets, rows, 1, 0, None, lr=False, fm=False, pool=True)["P_pool"]
-    A_sum = oracle.aggregate(P["P_sum"]); A_sq = oracle.aggregate(P["P_sq"]); oracle.aggregate(P["P_lr"])
-    oracle.aggregate(pool)
-    oracle.fm_finalize(A_sum, A_sq)
-    t.backward_update(nb, F, offsets, rows, g_lr, g_fm, A_sum.astype(np.float32), g_pool, opt_code, w.lr,
-                      w.eps if w.eps else 1e-8)
-    dt = time.perf_counter() - t0
-    t.close()
-    return {"value": end / dt, "unit": "lookups/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {nb} of {w.B} samples of batch 0 ({end} lookups, {dt:.2f} s); table holds only the "
-                      f"{head.size} pre-inserted IDs these samples touch, initialiser weights",
-            "samples_per_s": nb / dt}
+    host_cores = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = host_cores
+
+    def leg(openmp, nb):
+        threads = oracle.use_openmp(openmp)
+        end = int(batch.offsets[nb * F])
+        keys, offsets = batch.keys[:end].copy(), batch.offsets[:nb * F + 1].copy()
+        if batch.ranks is not None:
+            head = np.unique(keys[batch.ranks[:end] <= w.preinsert])
+        else:
+            head = np.unique(keys)
+        t = oracle.Table(D, head.size + np.unique(keys).size + 16, seed=w.seed, init_scale=w.init_std)
+        t.insert(head)
+        g_lr = (rng.standard_normal(nb) / w.B).astype(np.float32)
+        g_fm = (rng.standard_normal(nb) / w.B).astype(np.float32)
+        g_pool = (rng.standard_normal((nb, F, D)) / w.B).astype(np.float32)
+        t0 = time.perf_counter()
+        rows = t.find(keys, insert_missing=True)
+        P = t.partial_forward(nb, F, keys, offsets, rows, w.K, 0, None, pool=False)
+        pool = t.partial_forward(nb, F, keys, offsets, rows, 1, 0, None, lr=False, fm=False, pool=True)["P_pool"]
+        A_sum = oracle.aggregate(P["P_sum"]); A_sq = oracle.aggregate(P["P_sq"]); oracle.aggregate(P["P_lr"])
+        oracle.aggregate(pool)
+        oracle.fm_finalize(A_sum, A_sq)
+        t.backward_update(nb, F, offsets, rows, g_lr, g_fm, A_sum.astype(np.float32), g_pool, opt_code, w.lr,
+                          w.eps if w.eps else 1e-8)
+        dt = time.perf_counter() - t0
+        t.close()
+        return {"value": end / dt, "unit": "lookups/s", "cores": threads, "samples_per_s": nb / dt,
+                "sample": f"first {nb} of {w.B} samples of batch 0 ({end} lookups, {dt:.2f} s); table holds only the "
+                          f"{head.size} pre-inserted IDs these samples touch, initialiser weights"}
+
+    nb = min(sample_B, w.B)
+    single = leg(False, max(1, nb // 2))
+    try:
+        multi = leg(True, nb)
+    finally:
+        oracle.use_openmp(False)
+    out = dict(multi)
+    out.update({"kind": "oracle", "host_cores": host_cores, "usable_cores": usable,
+                "build": "oracle/des_oracle.c, gcc -O2 -fopenmp", "single_thread": single})
+    return out
 
 
 def main():
@@ -128,11 +151,13 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="index into the benchmark configurations (0-4)")
     ap.add_argument("--also", type=str, default=None,
                     help="comma-separated further configurations measured after the main one and reported under "
-                         "\"also\" (default: 2 when the main one is 4; \"none\" to skip)")
+                         "\"also\" (default: 0,1,2,3 when the main one is 4, so that one line carries all five; "
+                         "\"none\" to skip)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--batches", type=int, default=0, help="distinct pre-generated batches (default 8, fewer for huge ones)")
     ap.add_argument("--cpu-lookups", type=float, default=1e7,
-                    help="size of the oracle's timed sample, in lookups (about 10 s of single-thread CPU work)")
+                    help="size of the oracle's timed sample, in lookups (all-cores leg; the single-thread leg takes "
+                         "half of it: about 7 s of CPU work each)")
     ap.add_argument("--dnn-hidden", type=int, default=256,
                     help="width H of the first fully-connected layer measured after the sparse step and reported "
                          "under \"dnn_layer\" (0 to skip)")
@@ -184,14 +209,15 @@ def main():
         print(json.dumps({key: (run_cross_layer if args.only == "cross" else run_dnn_layer)(args, args.config)}))
         return
     out = run_workload(args, args.config, cpu=not args.no_cpu)
-    also = args.also if args.also is not None else ("2" if args.config == 4 and args.scale == 1.0 else "none")
+    also = args.also if args.also is not None else ("0,1,2,3" if args.config == 4 and args.scale == 1.0 else "none")
     if also != "none":
         out["also"] = []
         for idx in [int(x) for x in also.split(",") if x.strip()]:
             torch.cuda.empty_cache()
             r = run_workload(args, idx, cpu=False)
             out["also"].append({k: r[k] for k in ("value", "unit", "samples_per_s", "ms_per_step", "steps", "warmup",
-                                                  "config", "roofline", "kernels", "table_migrate") if k in r})
+                                                  "config", "roofline", "kernels", "table_migrate", "insert_heavy_step")
+                                if k in r})
     if args.dnn_hidden > 0:
         torch.cuda.empty_cache()
         out["dnn_layer"] = run_dnn_layer(args, args.config)
@@ -381,9 +407,16 @@ def run_workload(args, index, cpu):
             host_batches.append(gen.next_batch())
             if i % 10 == 9:                       # long set-ups stay visibly alive
                 print(f"bench.py: generated {i + 1} of {n_batches} streaming batches", file=sys.stderr, flush=True)
+        # one more step in which 30 % of the entries are brand-new IDs (the literal reading of the workload's
+        # description; it cannot be sustained inside the stated final size, one step of it can), timed on its own
+        heavy_batch = None
+        if gen.row_keys.shape[0] + int(0.33 * host_batches[-1].nnz) <= w.capacity:
+            heavy_batch = gen.next_batch(p_new=0.30)
     else:
         host_batches = [synth.gen_batch(w, i) for i in range(n_batches)]
     max_nnz = max(b.nnz for b in host_batches)
+    if streaming and heavy_batch is not None:
+        max_nnz = max(max_nnz, heavy_batch.nnz)
     chunk = 1 << 22
     policy = des.SHARD_KEY_HASH if args.policy == "key" else des.SHARD_FIELD_MOD
     table = des.Table(w.D, w.capacity, w.K, policy, opt, init_seed=w.seed, init_scale=w.init_std,
@@ -522,14 +555,32 @@ def run_workload(args, index, cpu):
         per_launch_bytes = model[dom] / lps
         per_launch_s = kernels[dom]["ms_per_step"] * 1e-3 / lps
         achieved = per_launch_bytes / per_launch_s / 1e9
+        traffic, traffic_commit = measured_traffic(w.index, dom) if args.scale == 1.0 else (None, None)
         roof = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(w.index, dom) if args.scale == 1.0 else None,
+                "traffic": traffic,
                 "algorithmic_bytes_per_launch": int(per_launch_bytes), "avg_launch_ms": round(per_launch_s * 1e3, 4),
                 "distinct_rows_per_step": st["U"], "kernel_ms_sum_per_step": round(sum(v["ms_per_step"] for v in kernels.values()), 4)}
 
-        if roof["traffic"]:          # measured bytes (committed counter summary) over the live launch time
+        if roof["traffic"]:          # counted bytes (committed counter summary of a separate run) over the live launch time
             roof["traffic_GBps"] = round(roof["traffic"] / per_launch_s / 1e9, 1)
+            roof["traffic_source"] = {"file": f"profiles/{PROFILE_TAG[w.index]}_hbm_traffic.md", "measured_at_commit": traffic_commit}
+
+    heavy_res = None
+    if streaming and heavy_batch is not None and not args.no_kernel_pass:
+        # the table is exactly in the state the generator's mirror expects: every generated batch has been run once
+        batches.append(des.Batch.from_numpy(heavy_batch))
+        rows_was = table.size()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(main)
+        step(len(batches) - 1)
+        e1.record(main)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        assert table.status() == 0
+        heavy_res = {"p_new": 0.30, "ms": round(ms, 4), "nnz": heavy_batch.nnz, "new_rows": table.size() - rows_was,
+                     "lookups_per_s": heavy_batch.nnz / (ms * 1e-3), "table_rows_before": rows_was}
 
     cpu_res = None
     if cpu:
@@ -561,6 +612,8 @@ def run_workload(args, index, cpu):
                    "hip_graph": bool(graphs)},
         "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
+    if heavy_res is not None:
+        out["insert_heavy_step"] = heavy_res
     if series is not None:
         out["series_ms"] = series
     if model_res is not None:
