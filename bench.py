@@ -185,6 +185,9 @@ def main():
     ap.add_argument("--only", type=str, default=None, choices=["cross", "dnn"],
                     help="time only the cross network or only the first fully-connected layer at the workload's shape "
                          "(no table is built; for profiling runs of those kernels)")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the access-pattern ceilings (row gather and row read-modify-write alone on the workload's "
+                         "index streams), reported under \"ceilings\"")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the per-kernel timing pass (profiling runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -216,7 +219,7 @@ def main():
             torch.cuda.empty_cache()
             r = run_workload(args, idx, cpu=False)
             out["also"].append({k: r[k] for k in ("value", "unit", "samples_per_s", "ms_per_step", "steps", "warmup",
-                                                  "config", "roofline", "kernels", "table_migrate", "insert_heavy_step")
+                                                  "config", "roofline", "kernels", "table_migrate", "insert_heavy_step", "ceilings")
                                 if k in r})
     if args.dnn_hidden > 0:
         torch.cuda.empty_cache()
@@ -566,6 +569,45 @@ def run_workload(args, index, cpu):
             roof["traffic_GBps"] = round(roof["traffic"] / per_launch_s / 1e9, 1)
             roof["traffic_source"] = {"file": f"profiles/{PROFILE_TAG[w.index]}_hbm_traffic.md", "measured_at_commit": traffic_commit}
 
+    # ---- access-pattern ceilings: the forward gather's row reads and the update's row read-modify-writes alone,
+    # on this workload's own index streams (des_ceiling_*), beside the real kernels' times of the pass above
+    ceil_res = None
+    if not args.no_kernel_pass and not args.no_ceiling and w.opt != "sgd":
+        b = batches[(total_steps if streaming else args.warmup) % len(batches)]
+        r = rows[:b.nnz]
+        table.find(b.keys, des.MISS_ZERO, r)
+        uniq = torch.empty(b.nnz, dtype=torch.int32, device=dev)
+        n_u = torch.zeros(1, dtype=torch.int64, device=dev)
+        table.backward_merge(b, r, g_lr=g_lr, dbg={"uniq_rows": uniq, "n_uniq": n_u})      # merged order only, no update
+        U = int(n_u.item())
+        sink = des.ceiling_gather(table.emb, r)
+        des.ceiling_update(table.emb, table.acc_emb, uniq[:U])
+        torch.cuda.synchronize()
+        reps = 5
+        des.profile_enable(True)
+        for _ in range(reps):
+            des.ceiling_gather(table.emb, r, sink)
+            des.ceiling_update(table.emb, table.acc_emb, uniq[:U])
+        prof = des.profile_read()
+        des.profile_enable(False)
+        g_ms, u_ms = prof["ceiling_gather"][1] / reps, prof["ceiling_update"][1] / reps
+        present = int((r >= 0).sum().item())
+        ceil_res = {
+            "batch_entries": b.nnz, "distinct_rows": U,
+            "gather": {"ms": round(g_ms, 4), "logical_GB": round(present * D * 4 / 1e9, 3),
+                       "logical_GBps": round(present * D * 4 / (g_ms * 1e-3) / 1e9, 1)},
+            "update": {"ms": round(u_ms, 4), "logical_GB": round(U * D * 16 / 1e9, 3),
+                       "logical_GBps": round(U * D * 16 / (u_ms * 1e-3) / 1e9, 1)},
+        }
+        if "forward_gather_pool" in kernels:
+            ceil_res["forward_gather_pool_ms"] = kernels["forward_gather_pool"]["ms_per_step"]
+            ceil_res["gather_ceiling_over_forward"] = round(g_ms / kernels["forward_gather_pool"]["ms_per_step"], 3)
+        upd = sum(kernels[k]["ms_per_step"] for k in ("backward_short_update", "backward_long_partial", "backward_long_final") if k in kernels)
+        if upd > 0:
+            ceil_res["merge_and_update_ms"] = round(upd, 4)
+            ceil_res["update_ceiling_over_merge_and_update"] = round(u_ms / upd, 3)
+        del uniq, sink
+
     heavy_res = None
     if streaming and heavy_batch is not None and not args.no_kernel_pass:
         # the table is exactly in the state the generator's mirror expects: every generated batch has been run once
@@ -612,6 +654,8 @@ def run_workload(args, index, cpu):
                    "hip_graph": bool(graphs)},
         "roofline": roof, "cpu_baseline": cpu_res, "kernels": kernels,
     }
+    if ceil_res is not None:
+        out["ceilings"] = ceil_res
     if heavy_res is not None:
         out["insert_heavy_step"] = heavy_res
     if series is not None:

@@ -449,6 +449,24 @@ des_status_t des_dense_update(float *theta, const float *grad, float *s1, float 
 des_status_t des_batch_validate(des_table_t *t, const des_batch_t *batch, const int32_t *rows, int64_t *first_bad,
                                 void *stream);
 
+/* Measurement aids (used by the benchmark, not by a training step): kernels that perform only the table accesses
+ * of the forward gather and of the row update, on the caller's own index streams, with the lane mapping and the
+ * load / store instructions of the real kernels and nothing else.  Their rates are the ceilings of this GPU for
+ * these access patterns, against which the real kernels' times are read where the streaming figure of 8 TB/s is
+ * not the limit that applies.
+ * des_ceiling_gather: every entry e < n with 0 <= rows[e] < n_rows reads the dim floats of row rows[e] of emb
+ *   (row r starts at emb + r * stride floats; stride = dim for a dense array) and, if w is not null, the one float
+ *   w[r * w_stride], as the forward pass does for the first-order weight; one float per wave is left in `sink`
+ *   (device, des_ceiling_gather_bytes bytes) so that the loads are live.  Logical bytes: 4 * dim (+ 4) per entry.
+ * des_ceiling_update: for every u < n_uniq, row uniq_rows[u] (0 <= row < n_rows, else skipped) of emb and of acc
+ *   (both with `stride` floats between rows) is read and written back unchanged.  Logical bytes: 16 * dim per row.
+ * dim as for a table; stride a multiple of 4, >= dim; pointers device, emb / acc 16-byte aligned. */
+des_status_t des_ceiling_gather_bytes(size_t *sink_bytes);
+des_status_t des_ceiling_gather(const float *emb, int32_t dim, int64_t stride, const float *w, int64_t w_stride, int64_t n_rows,
+                                const int32_t *rows, int64_t n, float *sink, size_t sink_bytes, void *stream);
+des_status_t des_ceiling_update(float *emb, float *acc, int32_t dim, int64_t stride, int64_t n_rows, const int32_t *uniq_rows,
+                                int64_t n_uniq, void *stream);
+
 /* Per-kernel timing with HIP events recorded on the caller's stream around every launch.
  * enable != 0 starts collecting and clears earlier records.  des_profile_read synchronises,
  * then fills up to `max` records (kernel name, launches, total milliseconds) and returns the

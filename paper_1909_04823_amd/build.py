@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdes.so")
-SOURCES = ["des_sort.hip", "des_table.hip", "des_forward.hip", "des_backward.hip", "des_dnn.hip", "des_dense.hip", "des_migrate.hip", "des_cross.hip"]
+SOURCES = ["des_sort.hip", "des_table.hip", "des_forward.hip", "des_backward.hip", "des_dnn.hip", "des_dense.hip", "des_migrate.hip", "des_cross.hip", "des_ceiling.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

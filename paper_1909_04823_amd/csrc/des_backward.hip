@@ -27,7 +27,7 @@ constexpr int kMidFan = 64;                // chunk partials that one wave pre-s
 constexpr int kShortGrid = 65536;          // most workgroups of the short-segment kernel (it strides over the segments)
 constexpr int kHeadItems = 8;
 constexpr int kHeadTile = kBlock * kHeadItems;
-constexpr int64_t kHeadsOneBlock = 4096;   // up to this many tiles one workgroup sums the tiles' head counts
+constexpr int64_t kHeadsSelfPrefix = 4096;  // up to this many tiles every workgroup sums the earlier tiles' head counts itself
 constexpr int kWavesPerBlock = kBlock / kWave;
 
 struct BwdArgs {
@@ -159,14 +159,15 @@ __device__ inline void load_head_keys(const uint32_t *__restrict__ keys, int64_t
 
 __global__ __launch_bounds__(kBlock) void k_heads_count(const BwdArgs a) {
   __shared__ uint32_t lds[kWavesPerBlock];
+  const int64_t n = a.n;
   const int64_t base = (int64_t)blockIdx.x * kHeadTile + (int64_t)threadIdx.x * kHeadItems;
   uint32_t cnt = 0;
-  uint32_t prev = base > 0 && base <= a.n ? a.key_sorted[base - 1] : 0xFFFFFFFFu;
+  uint32_t prev = base > 0 && base <= n ? a.key_sorted[base - 1] : 0xFFFFFFFFu;
   uint32_t keys[kHeadItems];
-  load_head_keys(a.key_sorted, base, a.n, a.missing, keys);
+  load_head_keys(a.key_sorted, base, n, a.missing, keys);
 #pragma unroll
   for (int i = 0; i < kHeadItems; ++i) {
-    if (base + i < a.n) {
+    if (base + i < n) {
       const uint32_t k = keys[i];
       cnt += (k != a.missing && (base + i == 0 || k != prev)) ? 1u : 0u;
       prev = k;
@@ -177,66 +178,59 @@ __global__ __launch_bounds__(kBlock) void k_heads_count(const BwdArgs a) {
   if (threadIdx.x == 0) a.head_sums[blockIdx.x] = total;
 }
 
-__global__ __launch_bounds__(kBlock) void k_heads_sums(const BwdArgs a, int64_t nb) {
-  __shared__ uint32_t lds[kWavesPerBlock];
-  uint32_t carry = 0;
-  for (int64_t base = 0; base < nb; base += kBlock) {
-    const int64_t i = base + threadIdx.x;
-    const uint32_t v = i < nb ? a.head_sums[i] : 0u;
-    uint32_t total;
-    const uint32_t ex = block_excl_scan_u32(v, lds, total);
-    if (i < nb) a.head_sums[i] = carry + ex;
-    carry += total;
-  }
-  if (threadIdx.x == 0) {
-    a.ctrl->n_uniq = carry;
-    a.ctrl->n_long = 0;
-    a.ctrl->n_chunks = 0;
-    a.ctrl->n_multi = 0;
-    a.ctrl->n_groups = 0;
-    if (a.n_uniq_out) *a.n_uniq_out = carry;
-  }
-}
-
-// The same bookkeeping after a device-wide scan of the tile counts (many tiles): the scan left the total behind
-// the counts.
-__global__ void k_heads_finish(const BwdArgs a, const uint32_t *total) {
-  a.ctrl->n_uniq = *total;
+// Bookkeeping after a device-wide scan of the tile counts (many tiles): the scan left the total behind the counts.
+__device__ inline void heads_bookkeeping(const BwdArgs &a, uint32_t n_uniq) {
+  a.ctrl->n_uniq = n_uniq;
   a.ctrl->n_long = 0;
   a.ctrl->n_chunks = 0;
   a.ctrl->n_multi = 0;
   a.ctrl->n_groups = 0;
-  if (a.n_uniq_out) *a.n_uniq_out = *total;
+  if (a.n_uniq_out) *a.n_uniq_out = n_uniq;
 }
 
+__global__ void k_heads_finish(const BwdArgs a, const uint32_t *total) { heads_bookkeeping(a, *total); }
+
+// kSelfPrefix: head_sums still holds the tiles' counts and every workgroup adds up the counts of the tiles before
+// its own (few tiles: cheaper than a launch that does it once); the last workgroup then also publishes the
+// number of segments and resets the counters of the classify pass.
+template <bool kSelfPrefix>
 __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
   __shared__ uint32_t lds[kWavesPerBlock];
   __shared__ uint32_t l_key[kHeadTile];
   __shared__ int32_t l_idx[kHeadTile];
+  const int64_t n = a.n;
   const int64_t base = (int64_t)blockIdx.x * kHeadTile + (int64_t)threadIdx.x * kHeadItems;
   uint32_t key[kHeadItems];
   bool flag[kHeadItems];
   uint32_t cnt = 0;
-  uint32_t prev = base > 0 && base <= a.n ? a.key_sorted[base - 1] : 0xFFFFFFFFu;
+  uint32_t prev = base > 0 && base <= n ? a.key_sorted[base - 1] : 0xFFFFFFFFu;
   const uint32_t first_prev = prev;
-  load_head_keys(a.key_sorted, base, a.n, a.missing, key);
+  load_head_keys(a.key_sorted, base, n, a.missing, key);
 #pragma unroll
   for (int i = 0; i < kHeadItems; ++i) {
     flag[i] = false;
-    if (base + i < a.n) {
+    if (base + i < n) {
       flag[i] = key[i] != a.missing && (base + i == 0 || key[i] != prev);
       cnt += flag[i] ? 1u : 0u;
       prev = key[i];
     }
   }
   uint32_t total;
-  const uint32_t u0 = a.head_sums[blockIdx.x];          // heads before this tile
+  uint32_t u0;                                          // heads before this tile
+  if (kSelfPrefix) {
+    uint32_t part = 0;
+    for (uint32_t i = threadIdx.x; i < blockIdx.x; i += kBlock) part += a.head_sums[i];
+    block_excl_scan_u32(part, lds, u0);
+  } else {
+    u0 = a.head_sums[blockIdx.x];
+  }
   uint32_t loc = block_excl_scan_u32(cnt, lds, total);  // heads before this thread inside the tile
+  if (kSelfPrefix && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) heads_bookkeeping(a, u0 + total);
   prev = first_prev;
 #pragma unroll
   for (int i = 0; i < kHeadItems; ++i) {
     const int64_t idx = base + i;
-    if (idx < a.n) {
+    if (idx < n) {
       if (flag[i]) {
         l_key[loc] = key[i];
         l_idx[loc] = (int32_t)idx;
@@ -244,7 +238,7 @@ __global__ __launch_bounds__(kBlock) void k_heads_write(const BwdArgs a) {
       }
       // end of the last segment: first entry without a row, or the end of the array
       if (key[i] == a.missing && (idx == 0 || prev != a.missing)) a.seg_off[u0 + loc] = (int32_t)idx;
-      if (idx == a.n - 1 && key[i] != a.missing) a.seg_off[u0 + loc] = (int32_t)a.n;
+      if (idx == n - 1 && key[i] != a.missing) a.seg_off[u0 + loc] = (int32_t)n;
       prev = key[i];
     }
   }
@@ -523,10 +517,14 @@ __device__ inline void add_entry(const BwdArgs &a, uint32_t p, int sub, Acc &acc
 // (4a) one lane group per segment; long segments are left to the chunked path.  The segment's
 // bounds, row and first payload arrive together; the row state and the first entry's upstream
 // gradients are then fetched together, so a one-entry segment costs two memory round trips.
+// The kernel waits on memory for most of its time, so a fifth wave per SIMD is worth more than registers: it is
+// compiled for five (96 vector registers; at the 120 it would take by itself four fit), and gathers two entries'
+// gradient rows at a time instead of four, which is what lets it fit almost without spilling.  Measured at the large
+// table: 18.2 -> 16.5 ms; six waves (80 registers, 68 bytes of spill) lose that again.
 template <int D, bool kHasVals>
-__global__ __launch_bounds__(kBlock) void k_short_update(const BwdArgs a) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) void k_short_update(const BwdArgs a) {
   constexpr int G = D / 4;
-  constexpr int U = 4;
+  constexpr int U = 2;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int sub = (int)(gid % G);
   const int64_t ngroups = (int64_t)gridDim.x * blockDim.x / G;
@@ -801,8 +799,9 @@ int sort_stage(des_table *t, BwdArgs &a, const Layout &L, hipStream_t s) {
   uint32_t *key_a = (uint32_t *)(ws + L.key_a), *pay_a = (uint32_t *)(ws + L.pay_a);
   {
     ProfScope ps(KID_EXPAND, s);
-    if (a.vals) hipLaunchKernelGGL(k_expand<true>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);
-    else hipLaunchKernelGGL(k_expand<false>, dim3(blocks_for(a.nbags, 1 << 20)), dim3(kBlock), 0, s, a, key_a, pay_a);  // one workgroup per kBlock bags
+    const dim3 grid(blocks_for(a.nbags, 1 << 20)), block(kBlock);     // one workgroup per kBlock bags
+    if (a.vals) hipLaunchKernelGGL(k_expand<true>, grid, block, 0, s, a, key_a, pay_a);
+    else hipLaunchKernelGGL(k_expand<false>, grid, block, 0, s, a, key_a, pay_a);
   }
   SortBuffers sb{key_a, (uint32_t *)(ws + L.key_b), pay_a, (uint32_t *)(ws + L.pay_b)};
   const int side = radix_sort_u32_pairs(sb, n, bits_for((uint64_t)t->cfg.capacity_rows), ws + L.sort_scratch, s);
@@ -812,13 +811,13 @@ int sort_stage(des_table *t, BwdArgs &a, const Layout &L, hipStream_t s) {
     ProfScope ps(KID_HEADS, s);
     const int64_t nb = (n + kHeadTile - 1) / kHeadTile;
     hipLaunchKernelGGL(k_heads_count, dim3((unsigned)nb), dim3(kBlock), 0, s, a);
-    if (nb > kHeadsOneBlock) {                    // one workgroup walking the counts 256 at a time gets slow
+    if (nb > kHeadsSelfPrefix) {                  // many tiles: one device-wide scan of the counts
       exclusive_scan_u32(a.head_sums, nb, a.head_sums + nb, ws + L.sort_scratch, s);
       hipLaunchKernelGGL(k_heads_finish, dim3(1), dim3(1), 0, s, a, (const uint32_t *)(a.head_sums + nb));
+      hipLaunchKernelGGL(k_heads_write<false>, dim3((unsigned)nb), dim3(kBlock), 0, s, a);
     } else {
-      hipLaunchKernelGGL(k_heads_sums, dim3(1), dim3(kBlock), 0, s, a, nb);
+      hipLaunchKernelGGL(k_heads_write<true>, dim3((unsigned)nb), dim3(kBlock), 0, s, a);
     }
-    hipLaunchKernelGGL(k_heads_write, dim3((unsigned)nb), dim3(kBlock), 0, s, a);
   }
   {
     ProfScope ps(KID_CLASSIFY, s);

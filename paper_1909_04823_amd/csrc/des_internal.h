@@ -51,7 +51,7 @@ enum KernelId {
   KID_HEADS, KID_CLASSIFY, KID_SHORT_UPDATE, KID_LONG_PARTIAL, KID_LONG_FINAL, KID_EXPORT,
   KID_FILL, KID_DNN_FORWARD, KID_DNN_GPOOL, KID_DNN_DW,
   KID_AGG_BIAS_ACT, KID_COLUMN_PARTIALS, KID_COLUMN_FINAL, KID_HEAD, KID_DENSE_UPDATE, KID_MIGRATE,
-  KID_CROSS_PARTIAL, KID_CROSS_APPLY, KID_CROSS_GRAD, KID_COUNT
+  KID_CROSS_PARTIAL, KID_CROSS_APPLY, KID_CROSS_GRAD, KID_CEILING_GATHER, KID_CEILING_UPDATE, KID_COUNT
 };
 void prof_begin(int kid, hipStream_t s);
 void prof_end(int kid, hipStream_t s);

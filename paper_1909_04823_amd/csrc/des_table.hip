@@ -22,6 +22,7 @@ namespace {
 constexpr int kFlagItems = 8;                       // entries per thread in the numbering kernels
 constexpr int kFlagTile = kBlock * kFlagItems;
 constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int64_t kSelfPrefixTiles = 4096;          // up to this many tiles the numbering kernel sums the tile counts itself
 
 __device__ inline void set_status(Ctrl *c, int st) { atomicCAS(&c->status, 0, st); }
 
@@ -175,14 +176,38 @@ __global__ __launch_bounds__(kBlock) void k_new_sums(uint32_t *__restrict__ tile
 }
 
 // Pass B3: number the new rows in entry order; the slot learns its row.
+// kSelfPrefix: tile_sums still holds the tiles' counts; every workgroup adds up all of them itself (few tiles:
+// cheaper than a launch that does it once), which gives it the rows before its tile, the number of new rows and the
+// capacity verdict, the same in every workgroup.  The first workgroup publishes the latter two.
+template <bool kSelfPrefix>
 __global__ __launch_bounds__(kBlock) void k_new_assign(Slot *__restrict__ slots, const int32_t *__restrict__ rows,
                                                         const uint32_t *__restrict__ slot_of,
                                                         const uint64_t *__restrict__ keys, int64_t n,
                                                         const uint32_t *__restrict__ tile_sums,
-                                                        const Ctrl *__restrict__ ctrl, uint64_t *__restrict__ row_keys,
-                                                        int32_t *__restrict__ first_idx) {
+                                                        Ctrl *__restrict__ ctrl, uint64_t *__restrict__ row_keys,
+                                                        int32_t *__restrict__ first_idx, int64_t capacity) {
   __shared__ uint32_t lds[kWavesPerBlock];
-  if (ctrl->status != 0) return;                    // uniform: includes "would exceed the capacity"
+  uint32_t tile_base;
+  if (kSelfPrefix) {
+    uint32_t before = 0, rest = 0;
+    for (uint32_t i = threadIdx.x; i < gridDim.x; i += kBlock) {
+      const uint32_t v = tile_sums[i];
+      if (i < blockIdx.x) before += v; else rest += v;
+    }
+    uint32_t rest_total;
+    block_excl_scan_u32(before, lds, tile_base);
+    block_excl_scan_u32(rest, lds, rest_total);
+    const long long n_new = (long long)tile_base + rest_total;
+    const bool full = ctrl->n_rows + n_new > capacity;            // n_rows does not change before the commit
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      ctrl->n_new = n_new;
+      if (full) set_status(ctrl, DES_ERR_FULL);
+    }
+    if (full || ctrl->status != 0) return;            // uniform over the grid: a status set earlier, or by a peer just now
+  } else {
+    if (ctrl->status != 0) return;                    // uniform: includes "would exceed the capacity"
+    tile_base = tile_sums[blockIdx.x];
+  }
   const long long n_rows = ctrl->n_rows;
   const int64_t base = (int64_t)blockIdx.x * kFlagTile + (int64_t)threadIdx.x * kFlagItems;
   bool flag[kFlagItems];
@@ -195,7 +220,7 @@ __global__ __launch_bounds__(kBlock) void k_new_assign(Slot *__restrict__ slots,
     cnt += flag[i] ? 1u : 0u;
   }
   uint32_t total;
-  uint32_t rank = tile_sums[blockIdx.x] + block_excl_scan_u32(cnt, lds, total);
+  uint32_t rank = tile_base + block_excl_scan_u32(cnt, lds, total);
 #pragma unroll
   for (int i = 0; i < kFlagItems; ++i) {
     if (flag[i]) {
@@ -249,13 +274,20 @@ __global__ __launch_bounds__(kBlock) void k_init_rows(const Ctrl *__restrict__ c
 }
 
 // Pass D.  Entries that saw a pending key read the row from the slot they remembered.
+// It is also the last kernel of an insert, so its first thread makes the new rows part of the table (no kernel of
+// the call reads the row count after this one was launched).
 __global__ __launch_bounds__(kBlock) void k_patch(const Slot *__restrict__ slots, int64_t n,
-                                                   int32_t *__restrict__ rows, const uint32_t *__restrict__ slot_of) {
+                                                   int32_t *__restrict__ rows, const uint32_t *__restrict__ slot_of,
+                                                   Ctrl *__restrict__ ctrl, int64_t capacity) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) {
     if (rows[e] != kRowPending) continue;
     const int32_t row = slots[slot_of[e]].row;
     rows[e] = row >= 0 ? row : kRowAbsent;         // negative only after a failed call
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (ctrl->status == 0 && ctrl->n_rows + ctrl->n_new <= capacity) ctrl->n_rows += ctrl->n_new;
+    ctrl->n_new = 0;
   }
 }
 
@@ -289,12 +321,6 @@ __global__ __launch_bounds__(kBlock) void k_copy_values(const Ctrl *__restrict__
       if (acc2_w) acc2_w[row] = 0.f;
     }
   }
-}
-
-// Last kernel of an insert: the new rows become part of the table.
-__global__ void k_commit(Ctrl *ctrl, int64_t capacity) {
-  if (ctrl->status == 0 && ctrl->n_rows + ctrl->n_new <= capacity) ctrl->n_rows += ctrl->n_new;
-  ctrl->n_new = 0;
 }
 
 __global__ __launch_bounds__(kBlock) void k_fill_u64x2(uint4 *__restrict__ p, int64_t n16, uint4 v) {
@@ -470,7 +496,7 @@ const char *kKernelNames[KID_COUNT] = {
     "backward_long_final", "backward_export", "fill",
     "dnn_forward", "dnn_grad_pool", "dnn_grad_weights",
     "aggregate_bias_act", "column_partials", "column_final", "output_unit", "dense_update", "table_migrate",
-    "cross_partial", "cross_apply", "cross_backward"};
+    "cross_partial", "cross_apply", "cross_backward", "ceiling_gather", "ceiling_update"};
 }  // namespace
 
 des_status_t blocking_status(des_table *t) {
@@ -633,9 +659,14 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
   {
     ProfScope ps(KID_ASSIGN, s);
     hipLaunchKernelGGL(k_new_count, dim3((unsigned)nb), dim3(kBlock), 0, s, t->slots, rows, slot_of, n, tile_sums);
-    hipLaunchKernelGGL(k_new_sums, dim3(1), dim3(kBlock), 0, s, tile_sums, nb, t->ctrl, c.capacity_rows);
-    hipLaunchKernelGGL(k_new_assign, dim3((unsigned)nb), dim3(kBlock), 0, s, t->slots, rows, slot_of, keys, n,
-                       tile_sums, t->ctrl, c.row_keys, first_idx);
+    if (nb > kSelfPrefixTiles) {
+      hipLaunchKernelGGL(k_new_sums, dim3(1), dim3(kBlock), 0, s, tile_sums, nb, t->ctrl, c.capacity_rows);
+      hipLaunchKernelGGL(k_new_assign<false>, dim3((unsigned)nb), dim3(kBlock), 0, s, t->slots, rows, slot_of, keys, n,
+                         tile_sums, t->ctrl, c.row_keys, first_idx, c.capacity_rows);
+    } else {
+      hipLaunchKernelGGL(k_new_assign<true>, dim3((unsigned)nb), dim3(kBlock), 0, s, t->slots, rows, slot_of, keys, n,
+                         tile_sums, t->ctrl, c.row_keys, first_idx, c.capacity_rows);
+    }
   }
   {
     ProfScope ps(KID_INIT_ROWS, s);
@@ -649,8 +680,7 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
   }
   {
     ProfScope ps(KID_PATCH, s);
-    hipLaunchKernelGGL(k_patch, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, n, rows, slot_of);
-    hipLaunchKernelGGL(k_commit, dim3(1), dim3(1), 0, s, t->ctrl, c.capacity_rows);
+    hipLaunchKernelGGL(k_patch, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, n, rows, slot_of, t->ctrl, c.capacity_rows);
   }
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
 }

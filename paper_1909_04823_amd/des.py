@@ -32,6 +32,7 @@ EXPORTS = [
     "des_aggregate_bias_act", "des_dense_workspace_bytes", "des_bias_act_backward", "des_bias_act_backward_static", "des_head", "des_dense_update",
     "des_cross_partial", "des_cross_apply", "des_cross_backward_bytes", "des_cross_backward", "des_cross_partial_backward",
     "des_cross_net_bytes", "des_cross_net_partial", "des_cross_net_forward", "des_cross_net_backward",
+    "des_ceiling_gather_bytes", "des_ceiling_gather", "des_ceiling_update",
     "des_profile_enable", "des_profile_read", "des_status_string",
 ]
 
@@ -114,6 +115,9 @@ _sig = {
     "des_cross_net_partial": [vp, vp, i64, i32, i32, i32, i32, vp, vp],
     "des_cross_net_forward": [vp, vp, vp, i64, i64, i32, vp, vp, vp, C.c_size_t, vp],
     "des_cross_net_backward": [vp, vp, vp, vp, vp, vp, i64, i64, i32, vp, i32, vp, vp, vp, C.c_size_t, vp],
+    "des_ceiling_gather_bytes": [C.POINTER(C.c_size_t)],
+    "des_ceiling_gather": [vp, i32, i64, vp, i64, i64, vp, i64, vp, C.c_size_t, vp],
+    "des_ceiling_update": [vp, vp, i32, i64, i64, vp, i64, vp],
     "des_profile_enable": [i32],
     "des_profile_read": [C.POINTER(KernelTime), i32, C.POINTER(i32)],
 }
@@ -568,6 +572,24 @@ def head(labels: torch.Tensor, g_logit: torch.Tensor, workspace: torch.Tensor, A
 def dense_update(theta: torch.Tensor, grad: torch.Tensor, optimizer: Optimizer, s1=None, s2=None):
     _check(_lib.des_dense_update(_ptr(theta), _ptr(grad), _ptr(s1), _ptr(s2), theta.numel(), C.byref(optimizer),
                                  _stream()), "des_dense_update")
+
+
+def ceiling_gather(emb: torch.Tensor, rows: torch.Tensor, sink: Optional[torch.Tensor] = None,
+                   w: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """des_ceiling_gather on the rows of a table's emb array, optionally with the LR weight fetch (measurement aid)."""
+    if sink is None:
+        n = C.c_size_t(0)
+        _check(_lib.des_ceiling_gather_bytes(C.byref(n)), "des_ceiling_gather_bytes")
+        sink = torch.empty(n.value // 4, dtype=torch.float32, device=emb.device)
+    _check(_lib.des_ceiling_gather(_ptr(emb), emb.shape[1], emb.shape[1], _ptr(w), 1, emb.shape[0], _ptr(rows),
+                                   rows.numel(), _ptr(sink), _nbytes(sink), _stream()), "des_ceiling_gather")
+    return sink
+
+
+def ceiling_update(emb: torch.Tensor, acc: torch.Tensor, uniq_rows: torch.Tensor):
+    """des_ceiling_update: read and write back the listed rows of both arrays (measurement aid)."""
+    _check(_lib.des_ceiling_update(_ptr(emb), _ptr(acc), emb.shape[1], emb.shape[1], emb.shape[0], _ptr(uniq_rows),
+                                   uniq_rows.numel(), _stream()), "des_ceiling_update")
 
 
 def profile_enable(on: bool):

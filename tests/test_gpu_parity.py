@@ -285,6 +285,108 @@ def test_free_running_steps_on_own_outputs(oracle, des, opt, lr, eps, strict):
         p.close()
 
 
+def update_without_merged_outputs(p, des, torch, batch, g_lr, g_fm, A_sum, g_pool, optimizer, prepare_stream=None):
+    """One backward call on both sides in the form production callers use (no merged outputs, nothing
+    materialised); returns the oracle's merge result and the library's distinct-row count."""
+    ref = p.ot.backward_update(batch.B, batch.F, batch.offsets, p.rows_o, g_lr, g_fm, A_sum, g_pool,
+                               optimizer=p.oracle.Optimizer(**optimizer))
+    n_uniq = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    if prepare_stream is not None:
+        main = torch.cuda.current_stream()
+        found, sorted_ = torch.cuda.Event(), torch.cuda.Event()
+        found.record(main)
+        prepare_stream.wait_event(found)
+        with torch.cuda.stream(prepare_stream):
+            p.gt.backward_prepare(p.gb, p.rows_g)
+            sorted_.record(prepare_stream)
+        main.wait_event(sorted_)
+    p.gt.backward_update(p.gb, p.rows_g, des.Optimizer(**optimizer), g_lr=dev(g_lr, torch), g_fm=dev(g_fm, torch),
+                         A_sum=dev(A_sum, torch), g_pool=dev(g_pool, torch), dbg={"n_uniq": n_uniq})
+    torch.cuda.synchronize()
+    return ref, int(n_uniq.item())
+
+
+@pytest.mark.parametrize("index,scale,opt", [(2, 1 / 64, "adagrad"), (1, 1 / 8, "sgd"), (3, 1 / 64, "adam")])
+def test_backward_in_production_form(oracle, des, index, scale, opt):
+    """The backward call as production callers (and the benchmark) issue it: no merged outputs, only the
+    distinct-row count, every other step with the sort prepared on a second stream.  Updated weights and state
+    against the oracle after every one of four steps on skewed batches of >= 65536 entries."""
+    import torch
+    w = synth.workload(index, scale=scale)
+    code = {"sgd": des.OPT_SGD, "adagrad": des.OPT_ADAGRAD, "adam": des.OPT_ADAM}[opt]
+    optimizer = dict(opt_emb=code, opt_w=code, lr=w.lr, eps=1e-8, beta1=0.9, beta2=0.999, step=1)
+    nnz_hint = int(w.B * w.F * (w.mean_bag() * 1.3 + 2)) + 1024
+    p = Pair(oracle, des, w.D, w.capacity, w.K, 0, code, seed=w.seed, init_scale=w.init_std,
+             max_n=max(nnz_hint, w.preinsert + 16))
+    gen = synth.StreamingGenerator(w) if w.p_new else None
+    keys0 = gen.initial_keys() if gen else synth.preinsert_keys(w)
+    p.ot.insert(keys0); p.gt.insert(dev(keys0, torch))
+    aux = torch.cuda.Stream()
+    try:
+        for step in range(4):
+            batch = gen.next_batch() if gen else synth.gen_batch(w, step)
+            assert batch.nnz >= 65536
+            p.find(batch, insert=True)
+            A_sum = p.forward(batch)
+            g_lr, g_fm, g_pool = synth.upstream_gradients(w, step)
+            optimizer["step"] = step + 1
+            ref, n_uniq = update_without_merged_outputs(p, des, torch, batch, g_lr, g_fm, A_sum, g_pool, optimizer,
+                                                        prepare_stream=aux if step % 2 else None)
+            assert n_uniq == ref["uniq_rows"].size, (step, n_uniq, ref["uniq_rows"].size)
+            p.check_weights(f"{opt} step {step}")
+    finally:
+        p.close()
+
+
+def test_batches_with_many_absent_ids(oracle, des):
+    """Batches of 65536 entries in which a share of the IDs (1 %, half, all, none) is not in the table (lookup without
+    insert), with empty bags, three IDs that hold 20 % of the entries each, and Adam (an absent or untouched row
+    must keep its moments): the entries without a row take no part in the merge."""
+    import torch
+    D, B, F = 16, 2048, 8
+    rng = np.random.default_rng(99)
+    vocab = np.unique(rng.integers(1, 2**63, 3000, dtype=np.uint64))
+    hot_keys = vocab[[5, 700, 2500]]
+    p = Pair(oracle, des, D, 4096, 3, 0, des.OPT_ADAM, seed=3, init_scale=0.05, max_n=1 << 17)
+    p.ot.insert(vocab); p.gt.insert(dev(vocab, torch))
+    optimizer = dict(opt_emb=des.OPT_ADAM, opt_w=des.OPT_ADAM, lr=0.01, eps=1e-8, beta1=0.9, beta2=0.99, step=1)
+    w_like = synth.workload(1, scale=1 / 2, B=B, F=F, D=D)
+
+    def make_batch(present, absent_share, seed):
+        r = np.random.default_rng(seed)
+        lens = r.integers(0, 9, size=B * F)                      # empty bags included
+        lens[-1] += 65536 - lens.sum() if lens.sum() < 65536 else 0
+        while lens.sum() > 65536:
+            i = r.integers(0, B * F); lens[i] = max(0, lens[i] - 1)
+        off = np.zeros(B * F + 1, np.int32); off[1:] = np.cumsum(lens)
+        cold = np.setdiff1d(vocab, hot_keys)                      # the hot IDs occur only where placed below
+        keys = cold[r.integers(0, cold.size, 65536)]
+        u = r.random(65536)
+        for i, k in enumerate(hot_keys):
+            if present[i]:
+                keys[(u >= 0.2 * i) & (u < 0.2 * (i + 1))] = k
+        gone = r.random(65536) < absent_share
+        keys[gone] = np.uint64(2**63) + r.integers(1, 1000, int(gone.sum())).astype(np.uint64)   # IDs the table does not hold
+        return synth.Batch(B, F, keys, off)
+
+    try:
+        for n, (present, share) in enumerate([([1, 1, 1], 0.01), ([1, 0, 1], 0.5), ([0, 0, 0], 1.0), ([1, 1, 0], 0.0)]):
+            batch = make_batch(present, share, n + 1)
+            rows = p.find(batch, insert=False)
+            assert (rows < 0).mean() == pytest.approx(share, abs=0.02)
+            A_sum = p.forward(batch)
+            g_lr, g_fm, g_pool = synth.upstream_gradients(w_like, n)
+            optimizer["step"] = n + 1
+            ref, n_uniq = update_without_merged_outputs(p, des, torch, batch, g_lr, g_fm, A_sum, g_pool, optimizer,
+                                                        torch.cuda.Stream() if n == 1 else None)
+            assert n_uniq == ref["uniq_rows"].size
+            p.check_weights(f"batch {n}: {share:.0%} of the entries without a row")
+            p.backward(batch, g_lr, g_fm, A_sum, g_pool, optimizer=optimizer)          # and with the merged outputs
+            p.check_weights(f"batch {n}, merged outputs")
+    finally:
+        p.close()
+
+
 @pytest.mark.parametrize("D,K,policy,with_vals", [(4, 1, 0, False), (8, 3, 0, True), (16, 7, 1, True),
                                                     (32, 16, 1, False), (128, 5, 0, True), (256, 2, 0, False)])
 def test_shapes_policies_and_feature_values(oracle, des, D, K, policy, with_vals):
