@@ -65,7 +65,8 @@ __device__ inline double group_sum(double q) {
 // kByKey: shard of an entry = hash of its ID (entries of a bag scatter over the shards: one LDS update per
 // entry).  Otherwise the field partition of Section 5: a bag belongs to shard f mod K as a whole, so its sums
 // are formed in registers and the shard's accumulators take one update per bag.
-template <int D, bool kByKey>
+// kHasVals: the batch carries feature values; without them every x is 1 and the products with x are left out.
+template <int D, bool kByKey, bool kHasVals>
 __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   extern __shared__ __align__(16) double lds[];
   constexpr int G = D / 4;                 // lanes per row = entries per chunk
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
       if (my < e1) {
         r_n = a.rows[my];
         if (by_key) key_n = a.keys[my];
-        if (a.vals) x_n = a.vals[my];
+        if (kHasVals) x_n = a.vals[my];
       }
     }
     for (int e = e0; e < e1; e += G) {
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
         if (nx < e1) {
           r_n = a.rows[nx];
           if (by_key) key_n = a.keys[nx];
-          if (a.vals) x_n = a.vals[nx];
+          if (kHasVals) x_n = a.vals[nx];
         }
       }
       // bag of this lane's entry: the largest f with offs[f] <= my.  Entries are walked in order,
@@ -198,9 +199,9 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
                 ++cur;
               }
               if (md[i].x >= 0) {
-                const double xd = (double)__int_as_float(md[i].w);
-                const double xv[4] = {xd * (double)v[i].x, xd * (double)v[i].y, xd * (double)v[i].z,
-                                      xd * (double)v[i].w};
+                const double xd = kHasVals ? (double)__int_as_float(md[i].w) : 1.0;
+                const double xv[4] = {kHasVals ? xd * (double)v[i].x : (double)v[i].x, kHasVals ? xd * (double)v[i].y : (double)v[i].y,
+                                      kHasVals ? xd * (double)v[i].z : (double)v[i].z, kHasVals ? xd * (double)v[i].w : (double)v[i].w};
 #pragma unroll
                 for (int k = 0; k < 4; ++k) acc[k] += xv[k];
                 if (!kByKey) {
@@ -281,6 +282,17 @@ __global__ __launch_bounds__(kBlock) void k_pool_dense(const FwdArgs a, float *_
   }
 }
 
+template <int D>
+void launch_forward(bool by_key, bool has_vals, dim3 grid, dim3 block, size_t shmem, hipStream_t s, const FwdArgs &a) {
+  if (by_key) {
+    if (has_vals) hipLaunchKernelGGL((k_forward<D, true, true>), grid, block, shmem, s, a);
+    else hipLaunchKernelGGL((k_forward<D, true, false>), grid, block, shmem, s, a);
+  } else {
+    if (has_vals) hipLaunchKernelGGL((k_forward<D, false, true>), grid, block, shmem, s, a);
+    else hipLaunchKernelGGL((k_forward<D, false, false>), grid, block, shmem, s, a);
+  }
+}
+
 FwdArgs make_args(des_table *t, const des_batch_t *b, const int32_t *rows) {
   FwdArgs a;
   a.emb = t->cfg.emb; a.w = t->cfg.w;
@@ -318,13 +330,13 @@ des_status_t forward_launch(des_table *t, const des_batch_t *b, const int32_t *r
   const bool by_key = a.policy == DES_SHARD_KEY_HASH;
   ProfScope ps(KID_FORWARD, s);
   switch (D) {
-    case 4: if (by_key) hipLaunchKernelGGL((k_forward<4, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<4, false>), grid, block, shmem, s, a); break;
-    case 8: if (by_key) hipLaunchKernelGGL((k_forward<8, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<8, false>), grid, block, shmem, s, a); break;
-    case 16: if (by_key) hipLaunchKernelGGL((k_forward<16, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<16, false>), grid, block, shmem, s, a); break;
-    case 32: if (by_key) hipLaunchKernelGGL((k_forward<32, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<32, false>), grid, block, shmem, s, a); break;
-    case 64: if (by_key) hipLaunchKernelGGL((k_forward<64, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<64, false>), grid, block, shmem, s, a); break;
-    case 128: if (by_key) hipLaunchKernelGGL((k_forward<128, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<128, false>), grid, block, shmem, s, a); break;
-    case 256: if (by_key) hipLaunchKernelGGL((k_forward<256, true>), grid, block, shmem, s, a); else hipLaunchKernelGGL((k_forward<256, false>), grid, block, shmem, s, a); break;
+    case 4: launch_forward<4>(by_key, a.vals != nullptr, grid, block, shmem, s, a); break;
+    case 8: launch_forward<8>(by_key, a.vals != nullptr, grid, block, shmem, s, a); break;
+    case 16: launch_forward<16>(by_key, a.vals != nullptr, grid, block, shmem, s, a); break;
+    case 32: launch_forward<32>(by_key, a.vals != nullptr, grid, block, shmem, s, a); break;
+    case 64: launch_forward<64>(by_key, a.vals != nullptr, grid, block, shmem, s, a); break;
+    case 128: launch_forward<128>(by_key, a.vals != nullptr, grid, block, shmem, s, a); break;
+    case 256: launch_forward<256>(by_key, a.vals != nullptr, grid, block, shmem, s, a); break;
     default: return DES_ERR_INVALID_ARG;
   }
   return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
