@@ -43,6 +43,18 @@ class Optimizer(C.Structure):
                 ("ftrl_alpha", C.c_float), ("ftrl_beta", C.c_float), ("ftrl_l1", C.c_float), ("ftrl_l2", C.c_float)]
 
 
+_LIB_UBSAN = os.path.join(_HERE, "libdes_oracle_ubsan.so")
+
+
+def build_ubsan() -> str:
+    """A third build with gcc's undefined-behaviour sanitizer (signed overflow, bad shifts, misaligned or
+    out-of-bounds accesses it can see, ...), every finding fatal.  Used by one test, which runs the oracle's
+    whole interface through it in a child process (DES_ORACLE_LIB selects the library to load)."""
+    subprocess.check_call(["gcc", "-O1", "-g", "-ffp-contract=off", "-std=c11", "-shared", "-fPIC",
+                           "-fsanitize=undefined", "-fno-sanitize-recover=all", "-o", _LIB_UBSAN, _SRC, "-lm"])
+    return _LIB_UBSAN
+
+
 _lib = None
 _use_openmp = False
 
@@ -60,7 +72,7 @@ def lib():
     global _lib
     if _lib is None:
         build(force=False)
-        L = C.CDLL(_LIB_OMP if _use_openmp else _LIB)
+        L = C.CDLL(os.environ.get("DES_ORACLE_LIB") or (_LIB_OMP if _use_openmp else _LIB))
         L.oracle_threads.restype = C.c_int; L.oracle_threads.argtypes = []
         vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
         L.oracle_mix64.restype = u64; L.oracle_mix64.argtypes = [u64]

@@ -408,7 +408,8 @@ struct RowState {
   float w, aw, aw2;     // LR weight and its state
 };
 
-template <int D>
+// kSecond = false: the caller knows that no second state array is in use (SGD, Adagrad), which frees its registers.
+template <int D, bool kSecond = true>
 __device__ inline RowState load_row(const BwdArgs &a, int row, int sub) {
   RowState st;
   st.v = ld4_stream(a.emb + (int64_t)row * D + sub * 4);
@@ -417,11 +418,11 @@ __device__ inline RowState load_row(const BwdArgs &a, int row, int sub) {
   st.w = st.aw = st.aw2 = 0.f;
   if (a.opt_emb == DES_OPT_ADAGRAD || a.opt_emb == DES_OPT_ADAM)
     st.s = ld4_stream(a.acc_emb + (int64_t)row * D + sub * 4);
-  if (a.opt_emb == DES_OPT_ADAM) st.s2 = ld4_stream(a.acc2_emb + (int64_t)row * D + sub * 4);
+  if (kSecond && a.opt_emb == DES_OPT_ADAM) st.s2 = ld4_stream(a.acc2_emb + (int64_t)row * D + sub * 4);
   if (sub == 0 && a.opt_w != DES_OPT_NONE) {
     st.w = a.w[row];
     if (a.opt_w != DES_OPT_SGD) st.aw = a.acc_w[row];
-    if (a.opt_w == DES_OPT_ADAM || a.opt_w == DES_OPT_FTRL) st.aw2 = a.acc2_w[row];
+    if (kSecond && (a.opt_w == DES_OPT_ADAM || a.opt_w == DES_OPT_FTRL)) st.aw2 = a.acc2_w[row];
   }
   return st;
 }
@@ -435,7 +436,7 @@ __device__ inline float adam_step(const BwdArgs &a, float g, float &m, float &v)
 // Apply the merged gradient of one row.  The merged gradient is formed in double and rounded
 // once; the optimizer arithmetic itself is well conditioned and runs in fp32 (FTRL, one scalar
 // per row with a difference of square roots, in double).
-template <int D>
+template <int D, bool kSecond = true>
 __device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, const RowState &st, const Acc &acc) {
   const float4 v = st.v;
   const float4 G = make_float4((float)(acc.v[0] - (double)v.x * acc.s2), (float)(acc.v[1] - (double)v.y * acc.s2),
@@ -455,7 +456,7 @@ __device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, 
     st4_stream(a.acc_emb + (int64_t)row * D + sub * 4, s);
     st4_stream(vp, make_float4(v.x - a.lr * G.x / (sqrtf(s.x) + a.eps), v.y - a.lr * G.y / (sqrtf(s.y) + a.eps),
                                v.z - a.lr * G.z / (sqrtf(s.z) + a.eps), v.w - a.lr * G.w / (sqrtf(s.w) + a.eps)));
-  } else if (a.opt_emb == DES_OPT_ADAM) {
+  } else if (kSecond && a.opt_emb == DES_OPT_ADAM) {
     float4 m = st.s, q = st.s2;
     const float dx = adam_step(a, G.x, m.x, q.x), dy = adam_step(a, G.y, m.y, q.y);
     const float dz = adam_step(a, G.z, m.z, q.z), dw = adam_step(a, G.w, m.w, q.w);
@@ -470,13 +471,13 @@ __device__ inline void apply_row(const BwdArgs &a, int64_t u, int row, int sub, 
       const float aw = st.aw + gw * gw;
       a.acc_w[row] = aw;
       a.w[row] = st.w - a.lr * gw / (sqrtf(aw) + a.eps);
-    } else if (a.opt_w == DES_OPT_ADAM) {
+    } else if (kSecond && a.opt_w == DES_OPT_ADAM) {
       float m = st.aw, q = st.aw2;
       const float d = adam_step(a, gw, m, q);
       a.acc_w[row] = m;
       a.acc2_w[row] = q;
       a.w[row] = st.w - d;
-    } else if (a.opt_w == DES_OPT_FTRL) {
+    } else if (kSecond && a.opt_w == DES_OPT_FTRL) {
       const double g = acc.gw, n0 = (double)st.aw, alpha = (double)a.f_alpha;
       const double n1 = n0 + g * g;
       const double sigma = (sqrt(n1) - sqrt(n0)) / alpha;
@@ -521,7 +522,8 @@ __device__ inline void add_entry(const BwdArgs &a, uint32_t p, int sub, Acc &acc
 // compiled for five (96 vector registers; at the 120 it would take by itself four fit), and gathers two entries'
 // gradient rows at a time instead of four, which is what lets it fit almost without spilling.  Measured at the large
 // table: 18.2 -> 16.5 ms; six waves (80 registers, 68 bytes of spill) lose that again.
-template <int D, bool kHasVals>
+// kSecond: an optimizer with a second state array (Adam, FTRL) may be in use.
+template <int D, bool kHasVals, bool kSecond>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) void k_short_update(const BwdArgs a) {
   constexpr int G = D / 4;
   constexpr int U = 2;
@@ -529,11 +531,21 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) 
   const int sub = (int)(gid % G);
   const int64_t ngroups = (int64_t)gridDim.x * blockDim.x / G;
   const int64_t n_uniq = a.ctrl->n_uniq;
-  // grid-stride over the segments: the grid is sized on the host for the chip, not for the (device-side) segment count
-  for (int64_t u = gid / G; u < n_uniq; u += ngroups) {
-    const int i0 = a.seg_off[u], i1 = a.seg_off[u + 1];
-    const int row = a.uniq_rows[u];
-    const uint32_t p0 = a.first_pay[u];
+  // grid-stride over the segments: the grid is sized on the host for the chip, not for the (device-side) segment count.
+  // The bounds, row and first payload of the lane group's next segment are requested while the current one is being
+  // worked on, which takes one of the two dependent round trips per segment off the critical path.
+  int64_t u = gid / G;
+  int i0_n = 0, i1_n = 0, row_n = 0;
+  uint32_t p0_n = 0;
+  if (u < n_uniq) { i0_n = a.seg_off[u]; i1_n = a.seg_off[u + 1]; row_n = a.uniq_rows[u]; p0_n = a.first_pay[u]; }
+  for (; u < n_uniq; u += ngroups) {
+    const int i0 = i0_n, i1 = i1_n;
+    const int row = row_n;
+    const uint32_t p0 = p0_n;
+    {
+      const int64_t un = u + ngroups;
+      if (un < n_uniq) { i0_n = a.seg_off[un]; i1_n = a.seg_off[un + 1]; row_n = a.uniq_rows[un]; p0_n = a.first_pay[un]; }
+    }
     const int len = i1 - i0;
     if (len > kShortMax) continue;
     Acc acc = acc_zero();
@@ -542,7 +554,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) 
       // the first entry's gradients, so a segment of up to G+1 entries costs 2 + ceil((len-1)/U) round trips.
       uint32_t mine = (1 + sub < len) ? a.pay_sorted[i0 + 1 + sub] : 0u;
       float myx = 1.f;
-      const RowState st = load_row<D>(a, row, sub);
+      const RowState st = load_row<D, kSecond>(a, row, sub);
       add_entry<D, kHasVals>(a, p0, sub, acc);
       const int glane = (int)(threadIdx.x & (kWave - 1)) - sub;       // first lane of this group in the wave
       for (int base = 1; base < len; base += G) {
@@ -566,12 +578,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) 
           accumulate_batch<D, U>(a, bag, live, x, sub, acc);
         }
       }
-      apply_row<D>(a, u, row, sub, st, acc);
+      apply_row<D, kSecond>(a, u, row, sub, st, acc);
     } else {
-      const RowState st = load_row<D>(a, row, sub);
+      const RowState st = load_row<D, kSecond>(a, row, sub);
       add_entry<D, kHasVals>(a, p0, sub, acc);
       reduce_entries<D, kHasVals, 2>(a, i0 + 1, i1, sub, acc);
-      apply_row<D>(a, u, row, sub, st, acc);
+      apply_row<D, kSecond>(a, u, row, sub, st, acc);
     }
   }
 }
@@ -738,7 +750,10 @@ void launch_update(const BwdArgs &a, hipStream_t s) {
   const int64_t max_chunks = a.n / kChunk + max_long + 1;
   {
     ProfScope ps(KID_SHORT_UPDATE, s);
-    hipLaunchKernelGGL((k_short_update<D, kHasVals>), dim3(blocks_for(a.n * G, kShortGrid)), dim3(kBlock), 0, s, a);
+    const bool second = a.opt_emb == DES_OPT_ADAM || a.opt_w == DES_OPT_ADAM || a.opt_w == DES_OPT_FTRL;
+    const dim3 grid(blocks_for(a.n * G, kShortGrid)), block(kBlock);
+    if (second) hipLaunchKernelGGL((k_short_update<D, kHasVals, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_short_update<D, kHasVals, false>), grid, block, 0, s, a);
   }
   {
     ProfScope ps(KID_LONG_PARTIAL, s);

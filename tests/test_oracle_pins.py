@@ -933,3 +933,51 @@ def test_streaming_generator_jump_and_insert_fraction():
     assert abs(new / b.nnz - 0.30) < 0.02
     b2 = gen.next_batch()
     assert abs((gen.row_keys.size - 7 * n0 - new) / b2.nnz - w.p_new) < 0.01
+
+
+def test_oracle_runs_clean_under_the_undefined_behaviour_sanitizer(oracle, tmp_path):
+    """The whole interface of the C oracle once more in a child process that loads a build with
+    -fsanitize=undefined -fno-sanitize-recover: any signed overflow, bad shift, misaligned access or
+    out-of-bounds index the sanitizer can see aborts the child."""
+    import subprocess
+    import sys
+    lib = oracle.build_ubsan()
+    script = tmp_path / "drive.py"
+    script.write_text('''
+import numpy as np, oracle
+from paper_1909_04823_amd import synth
+rng = np.random.default_rng(5)
+w = synth.workload(1, scale=1 / 256, D=8, K=3)
+t = oracle.Table(w.D, w.capacity, seed=w.seed, init_scale=0.05)
+keys0 = synth.preinsert_keys(w)
+t.insert(keys0, synth.host_values(w, keys0.shape[0]))
+for step in range(2):
+    b = synth.gen_batch(w, step, with_vals=bool(step))
+    rows = t.find(b.keys, insert_missing=True)
+    for policy in (0, 1):
+        P = t.partial_forward(w.B, w.F, b.keys, b.offsets, rows, w.K, policy, b.vals)
+    A = oracle.aggregate(P["P_sum"]); oracle.fm_finalize(A, oracle.aggregate(P["P_sq"]))
+    g_lr, g_fm, g_pool = synth.upstream_gradients(w, step)
+    for opt in (oracle.Optimizer(opt_emb=2, opt_w=4, lr=0.05, eps=1e-8, ftrl_alpha=0.1, ftrl_beta=1.0, ftrl_l1=1e-3, ftrl_l2=1e-3),
+                oracle.Optimizer(opt_emb=3, opt_w=3, lr=0.01, eps=1e-8, beta1=0.9, beta2=0.99, step=step + 1),
+                oracle.Optimizer(opt_emb=1, opt_w=1, lr=0.01)):
+        t.backward_update(w.B, w.F, b.offsets, rows, g_lr, g_fm, A.astype(np.float32), g_pool, vals=b.vals, optimizer=opt)
+assert t.find(np.array([2**64 - 2, 0, 2**63], np.uint64)).tolist() == [-1, -1, -1]
+m = t.migrate(rng.random(t.n_rows) < 0.5, new_capacity=t.n_rows)
+m.find(keys0[:50], insert_missing=True)
+pool = rng.standard_normal((6, 5, 4)).astype(np.float32); W = rng.standard_normal((20, 8)).astype(np.float32)
+Y = oracle.dnn_partial_forward(pool, W, 3); oracle.dnn_backward(pool, W, rng.standard_normal((6, 8)).astype(np.float32))
+x0 = rng.standard_normal((6, 5, 4)).astype(np.float32); wl = rng.standard_normal(20).astype(np.float32)
+s = oracle.aggregate(oracle.cross_partial(x0, wl, 2)).astype(np.float32)
+y = oracle.cross_apply(x0, x0, s, wl); oracle.cross_backward(x0, x0, wl, s, x0); oracle.cross_partial_backward(x0, wl, s)
+Z = rng.standard_normal((6, 8)); A2 = oracle.bias_act(Z, wl[:8], True); oracle.bias_act_backward(A2.astype(np.float32), A2, True)
+oracle.head((rng.random(6) < 0.3).astype(np.float32), A_lr=s, fm2=s, a=A2.astype(np.float32), w_out=wl[:8], b0=0.1)
+th = wl.copy(); oracle.dense_update(th, wl, oracle.Optimizer(opt_emb=4, ftrl_alpha=0.1, ftrl_beta=1.0), np.zeros(20, np.float32), np.zeros(20, np.float32))
+print("sanitized run complete", oracle.mix64(2**64 - 1), oracle.shard(2**64 - 2, 3, 7), oracle.init_value(2**64 - 2, 255, 2**64 - 1, 0.01))
+''')
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, DES_ORACLE_LIB=lib, UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1",
+               PYTHONPATH=root + ":" + os.environ.get("PYTHONPATH", ""))
+    res = subprocess.run([sys.executable, str(script)], env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True,
+                         timeout=120)
+    assert res.returncode == 0 and "sanitized run complete" in res.stdout and "runtime error" not in res.stdout, res.stdout[-3000:]
