@@ -37,6 +37,10 @@ __device__ inline Slot load_slot(const Slot *p) {
 
 // Pass A.  rows[e] = row (>= 0), kRowAbsent, or kRowPending for keys claimed in this call; for
 // pending entries slot_of[e] remembers the slot so later passes need not probe again.
+// A probe is one dependent chain (key -> hash -> slot), so every thread works on kProbeKeys keys at a time: all their
+// keys are requested, then all their first slots, and only then is each chain resolved (later slots of a collision
+// chain one by one; they mostly sit in the line already fetched).  That multiplies the random lines in flight.
+constexpr int kProbeKeys = 4;
 template <bool kInsert>
 __global__ __launch_bounds__(kBlock) void k_probe(Slot *__restrict__ slots, uint64_t slot_mask,
                                                    const uint64_t *__restrict__ keys, int64_t n,
@@ -45,48 +49,67 @@ __global__ __launch_bounds__(kBlock) void k_probe(Slot *__restrict__ slots, uint
   // after a sticky error the table no longer grows: the call degrades to a pure lookup, so
   // rows[] is still fully written with valid rows or kRowAbsent
   const bool can_insert = kInsert && ctrl->status == 0;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) {
-    const uint64_t key = keys[e];
-    int32_t out = kRowAbsent;
-    if (key == kEmptyKey) {                        // the reserved key is nobody's ID: absent, counted, nothing else is held up
-      atomicAdd(&ctrl->bad_keys, 1);
-      rows[e] = out;
-      continue;
+  const int64_t tile_stride = (int64_t)gridDim.x * kBlock * kProbeKeys;
+  for (int64_t tile = (int64_t)blockIdx.x * kBlock * kProbeKeys; tile < n; tile += tile_stride) {
+    uint64_t key[kProbeKeys], idx[kProbeKeys];
+    Slot first[kProbeKeys];
+#pragma unroll
+    for (int i = 0; i < kProbeKeys; ++i) {
+      const int64_t e = tile + (int64_t)i * kBlock + threadIdx.x;
+      key[i] = e < n ? keys[e] : kEmptyKey;
     }
-    uint64_t idx = mix64(key) & slot_mask;
-    bool done = false, pending = false;
-    for (uint64_t probe = 0; probe <= slot_mask && !done; ++probe) {
-      const Slot s = load_slot(&slots[idx]);
-      if (s.key == key) {
-        // a negative row under a key is a claim of the running call, or the leftover of a
-        // call that failed: only a call that can insert resolves it
-        if (s.row >= 0) out = s.row; else pending = can_insert;
-        done = true;
-      } else if (s.key == kEmptyKey) {
-        if (!can_insert) {
+#pragma unroll
+    for (int i = 0; i < kProbeKeys; ++i) {
+      idx[i] = mix64(key[i]) & slot_mask;
+      first[i].key = kEmptyKey; first[i].row = kRowAbsent; first[i].first = 0u;
+      if (key[i] != kEmptyKey) first[i] = load_slot(&slots[idx[i]]);
+    }
+#pragma unroll
+    for (int i = 0; i < kProbeKeys; ++i) {
+      const int64_t e = tile + (int64_t)i * kBlock + threadIdx.x;
+      if (e >= n) continue;
+      int32_t out = kRowAbsent;
+      if (key[i] == kEmptyKey) {                     // the reserved key is nobody's ID: absent, counted, nothing else is held up
+        atomicAdd(&ctrl->bad_keys, 1);
+        rows[e] = out;
+        continue;
+      }
+      const uint64_t k = key[i];
+      uint64_t at = idx[i];
+      Slot s = first[i];
+      bool done = false, pending = false;
+      for (uint64_t probe = 0; probe <= slot_mask && !done; ++probe) {
+        if (probe > 0) s = load_slot(&slots[at]);
+        if (s.key == k) {
+          // a negative row under a key is a claim of the running call, or the leftover of a
+          // call that failed: only a call that can insert resolves it
+          if (s.row >= 0) out = s.row; else pending = can_insert;
           done = true;
-        } else {
-          const unsigned long long old =
-              atomicCAS(reinterpret_cast<unsigned long long *>(&slots[idx].key), kEmptyKey, key);
-          if (old == kEmptyKey || old == key) {   // claimed here, or by another entry of the same key
-            pending = true;
+        } else if (s.key == kEmptyKey) {
+          if (!can_insert) {
             done = true;
           } else {
-            idx = (idx + 1) & slot_mask;          // lost the slot to a different key
+            const unsigned long long old =
+                atomicCAS(reinterpret_cast<unsigned long long *>(&slots[at].key), kEmptyKey, k);
+            if (old == kEmptyKey || old == k) {   // claimed here, or by another entry of the same key
+              pending = true;
+              done = true;
+            } else {
+              at = (at + 1) & slot_mask;          // lost the slot to a different key
+            }
           }
+        } else {
+          at = (at + 1) & slot_mask;
         }
-      } else {
-        idx = (idx + 1) & slot_mask;
       }
+      if (!done) set_status(ctrl, DES_ERR_FULL);     // every slot visited
+      if (pending) {
+        atomicMin(&slots[at].first, (uint32_t)e);
+        slot_of[e] = (uint32_t)at;
+        out = kRowPending;
+      }
+      rows[e] = out;
     }
-    if (!done) set_status(ctrl, DES_ERR_FULL);     // every slot visited
-    if (pending) {
-      atomicMin(&slots[idx].first, (uint32_t)e);
-      slot_of[e] = (uint32_t)idx;
-      out = kRowPending;
-    }
-    rows[e] = out;
   }
 }
 
@@ -638,7 +661,7 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
   if (!insert) {
     if (!rows_out) return DES_ERR_INVALID_ARG;
     ProfScope ps(KID_PROBE, s);
-    hipLaunchKernelGGL(k_probe<false>, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows_out,
+    hipLaunchKernelGGL(k_probe<false>, dim3(grid_for(n, kBlock * kProbeKeys)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows_out,
                        t->ctrl, (uint32_t *)nullptr);
     return hipGetLastError() == hipSuccess ? DES_OK : DES_ERR_DEVICE;
   }
@@ -653,7 +676,7 @@ static des_status_t insert_impl(des_table_t *t, const uint64_t *keys, int64_t n,
   const int64_t nb = (n + kFlagTile - 1) / kFlagTile;
   {
     ProfScope ps(KID_PROBE, s);
-    hipLaunchKernelGGL(k_probe<true>, dim3(grid_for(n)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows, t->ctrl,
+    hipLaunchKernelGGL(k_probe<true>, dim3(grid_for(n, kBlock * kProbeKeys)), dim3(kBlock), 0, s, t->slots, mask, keys, n, rows, t->ctrl,
                        slot_of);
   }
   {
