@@ -470,8 +470,10 @@ des_status_t des_ceiling_update(float *emb, float *acc, int32_t dim, int64_t str
 /* Per-kernel timing with HIP events recorded on the caller's stream around every launch.
  * enable != 0 starts collecting and clears earlier records.  des_profile_read synchronises,
  * then fills up to `max` records (kernel name, launches, total milliseconds) and returns the
- * number of distinct kernels through n_out.  Names are static strings.  The collector is
- * process-wide and not thread-safe; it is meant for benchmarks. */
+ * number of distinct kernels through n_out.  Names are static strings.  There is one collector
+ * per process, shared by all tables; library calls from several threads may record into it at
+ * the same time, and enable / read may be called from any thread.  It is meant for benchmarks:
+ * while it is on every launch costs two event records. */
 typedef struct { const char *name; int64_t launches; double total_ms; } des_kernel_time_t;
 des_status_t des_profile_enable(int32_t enable);
 des_status_t des_profile_read(des_kernel_time_t *host_out, int32_t max, int32_t *n_out);

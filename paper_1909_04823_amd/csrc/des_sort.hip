@@ -206,6 +206,20 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict
   if (tile >= n_eff) return;                         // uniform per workgroup
   const int tile_n = (int)min((int64_t)kSortTile, n_eff - tile);
   const int radix = 1 << bits;
+  const uint32_t mask = (1u << bits) - 1u;
+  const unsigned long long lane_lt = (1ull << lane) - 1ull;
+  const int64_t wbase = tile + (int64_t)wave * (kSortItems * kWave);
+  KeyT key[kSortItems];
+  uint32_t pay[kSortItems];
+  uint32_t rank[kSortItems];
+  // the tile's items are requested first, so that their latency overlaps the fetch of the run offsets
+#pragma unroll
+  for (int r = 0; r < kSortItems; ++r) {
+    const int64_t idx = wbase + r * kWave + lane;
+    const bool live = idx < n_eff;
+    key[r] = live ? keys_in[idx] : (KeyT)0;
+    if (kHasPayload) pay[r] = live ? pay_in[idx] : 0u;
+  }
   for (int d = threadIdx.x; d < radix; d += kBlock) {
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w) cnt[w][d] = 0;
@@ -213,18 +227,10 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const KeyT *__restrict
   }
   __syncthreads();
 
-  const uint32_t mask = (1u << bits) - 1u;
-  const unsigned long long lane_lt = (1ull << lane) - 1ull;
-  const int64_t wbase = tile + (int64_t)wave * (kSortItems * kWave);
-  KeyT key[kSortItems];
-  uint32_t pay[kSortItems];
-  uint32_t rank[kSortItems];
 #pragma unroll
   for (int r = 0; r < kSortItems; ++r) {
     const int64_t idx = wbase + r * kWave + lane;
     const bool live = idx < n_eff;
-    key[r] = live ? keys_in[idx] : (KeyT)0;
-    if (kHasPayload) pay[r] = live ? pay_in[idx] : 0u;
     const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
     // lanes of this wave holding the same digit
     unsigned long long peers = __ballot(live);

@@ -11,6 +11,8 @@
 #include <math.h>
 #include <stddef.h>
 #include <string.h>
+#include <atomic>
+#include <mutex>
 #include <new>
 #include <vector>
 #include "des_internal.h"
@@ -508,9 +510,12 @@ size_t insert_ws_bytes(int64_t n) {
 // ---- profiler ------------------------------------------------------------------------------
 namespace {
 struct ProfRec { int kid; hipEvent_t a, b; };
-bool g_prof_on = false;
+// Collector shared by all tables and threads of the process: the switch is atomic, the record list is guarded by a
+// mutex, and the event that opens a launch is kept per thread (a launch is opened and closed by the same call).
+std::atomic<bool> g_prof_on{false};
+std::mutex g_prof_mutex;
 std::vector<ProfRec> g_prof;
-hipEvent_t g_open[KID_COUNT];
+thread_local hipEvent_t g_open[KID_COUNT];
 const char *kKernelNames[KID_COUNT] = {
     "table_probe", "table_number_new_rows", "table_patch_rows", "table_init_rows",
     "forward_gather_pool", "forward_pool_dense", "aggregate_partials", "fm_finalize",
@@ -530,7 +535,7 @@ des_status_t blocking_status(des_table *t) {
 }
 
 void prof_begin(int kid, hipStream_t s) {
-  if (!g_prof_on) return;
+  if (!g_prof_on.load(std::memory_order_relaxed)) return;
   hipEvent_t e;
   if (hipEventCreate(&e) != hipSuccess) return;
   (void)hipEventRecord(e, s);
@@ -538,11 +543,14 @@ void prof_begin(int kid, hipStream_t s) {
 }
 
 void prof_end(int kid, hipStream_t s) {
-  if (!g_prof_on || !g_open[kid]) return;
+  if (!g_open[kid]) return;
   hipEvent_t e;
   if (hipEventCreate(&e) != hipSuccess) return;
   (void)hipEventRecord(e, s);
-  g_prof.push_back({kid, g_open[kid], e});
+  {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    g_prof.push_back({kid, g_open[kid], e});
+  }
   g_open[kid] = nullptr;
 }
 
@@ -563,10 +571,10 @@ const char *des_status_string(des_status_t s) {
 }
 
 des_status_t des_profile_enable(int32_t enable) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
   for (auto &r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   g_prof.clear();
-  for (int i = 0; i < KID_COUNT; ++i) g_open[i] = nullptr;
-  g_prof_on = enable != 0;
+  g_prof_on.store(enable != 0);
   return DES_OK;
 }
 
@@ -575,6 +583,7 @@ des_status_t des_profile_read(des_kernel_time_t *out, int32_t max, int32_t *n_ou
   if (hipDeviceSynchronize() != hipSuccess) return DES_ERR_DEVICE;
   double ms[KID_COUNT] = {0};
   int64_t cnt[KID_COUNT] = {0};
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
   for (auto &r : g_prof) {
     float t = 0.f;
     if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) { ms[r.kid] += t; cnt[r.kid]++; }
