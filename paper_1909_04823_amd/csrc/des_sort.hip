@@ -152,11 +152,10 @@ __global__ __launch_bounds__(kBlock) void k_radix_hist(const KeyT *__restrict__ 
   __shared__ uint32_t cnt[kHistTiles][kMaxRadix];
   const int64_t n_eff = n_dev ? (int64_t)min((long long)n, *n_dev) : n;
   const int radix = 1 << bits;
-  for (int i = threadIdx.x; i < kHistTiles * kMaxRadix; i += kBlock) (&cnt[0][0])[i] = 0;
-  __syncthreads();
   const int blk0 = blockIdx.x * kHistTiles;
   const uint32_t mask = (1u << bits) - 1u;
   KeyT key[kHistTiles][kSortItems];
+  // the keys are requested before the counters are cleared, so that the barrier is passed while they travel
 #pragma unroll
   for (int j = 0; j < kHistTiles; ++j) {
     const int64_t base = (int64_t)(blk0 + j) * kSortTile;
@@ -166,6 +165,8 @@ __global__ __launch_bounds__(kBlock) void k_radix_hist(const KeyT *__restrict__ 
       key[j][i] = idx < n_eff ? keys[idx] : (KeyT)0;
     }
   }
+  for (int i = threadIdx.x; i < kHistTiles * kMaxRadix; i += kBlock) (&cnt[0][0])[i] = 0;
+  __syncthreads();
 #pragma unroll
   for (int j = 0; j < kHistTiles; ++j) {
     const int64_t base = (int64_t)(blk0 + j) * kSortTile;
