@@ -381,13 +381,61 @@ __device__ inline void load_batch_meta(const BwdArgs &a, int i, int i1, uint32_t
   }
 }
 
+// Per-sample values of the entry processed last by a lane group: entries of one row arrive in batch order, so a
+// row that occurs many times in one sample (the hot IDs of a skewed batch) brings runs of entries with the same
+// sample, which then reuse these instead of fetching them again.
+struct SampleRun {
+  uint32_t b;
+  float4 as;
+  float gf, gl;
+};
+
+// accumulate_batch for such runs: the A_sum row, g_fm and g_lr of an entry are fetched only if its sample differs
+// from the previous entry's.  Same values, same order of additions as accumulate_batch.
+template <int D, int U>
+__device__ inline void accumulate_batch_runs(const BwdArgs &a, const uint32_t (&bag)[U], const bool (&live)[U],
+                                             const float (&x)[U], int sub, Acc &acc, SampleRun &run) {
+  float gf[U], gl[U];
+  float4 gp[U], as[U];
+  uint32_t b[U];
+  bool same[U];
+  uint32_t prev = run.b;
+#pragma unroll
+  for (int k = 0; k < U; ++k) {
+    b[k] = bag[k] / (uint32_t)a.F;
+    same[k] = live[k] && b[k] == prev;
+    if (live[k]) prev = b[k];
+    gp[k] = (live[k] && a.g_pool) ? ld4(a.g_pool + (int64_t)bag[k] * D + sub * 4) : f4zero();
+    as[k] = (live[k] && !same[k] && a.g_fm) ? ld4(a.A_sum + (int64_t)b[k] * D + sub * 4) : f4zero();
+    gf[k] = (live[k] && !same[k] && a.g_fm) ? a.g_fm[b[k]] : 0.f;
+    gl[k] = (live[k] && !same[k] && a.g_lr) ? a.g_lr[b[k]] : 0.f;
+  }
+#pragma unroll
+  for (int k = 0; k < U; ++k) {
+    if (!live[k]) continue;
+    if (same[k]) { as[k] = run.as; gf[k] = run.gf; gl[k] = run.gl; }
+    run.b = b[k]; run.as = as[k]; run.gf = gf[k]; run.gl = gl[k];
+    const double xd = (double)x[k];
+    const double xg = xd * (double)gf[k];
+    acc.v[0] += xd * (double)gp[k].x + xg * (double)as[k].x;
+    acc.v[1] += xd * (double)gp[k].y + xg * (double)as[k].y;
+    acc.v[2] += xd * (double)gp[k].z + xg * (double)as[k].z;
+    acc.v[3] += xd * (double)gp[k].w + xg * (double)as[k].w;
+    acc.s2 += xd * xg;
+    acc.gw += xd * (double)gl[k];
+  }
+}
+
 // Sums over the sorted entries [i0, i1), U at a time; the payloads of the next U entries are requested
 // before the gradient rows of the current ones, so a batch costs one memory round trip, not two.
-template <int D, bool kHasVals, int U>
+// kRuns: reuse the per-sample values along runs of entries of one sample (long segments).
+template <int D, bool kHasVals, int U, bool kRuns = false>
 __device__ inline void reduce_entries(const BwdArgs &a, int i0, int i1, int sub, Acc &acc) {
   uint32_t nbag[U];
   bool nlive[U];
   float nx[U];
+  SampleRun run;
+  run.b = 0xFFFFFFFFu; run.as = f4zero(); run.gf = 0.f; run.gl = 0.f;
   if (i0 < i1) load_batch_meta<kHasVals, U>(a, i0, i1, nbag, nlive, nx);
   for (int i = i0; i < i1; i += U) {
     uint32_t bag[U];
@@ -396,7 +444,8 @@ __device__ inline void reduce_entries(const BwdArgs &a, int i0, int i1, int sub,
 #pragma unroll
     for (int k = 0; k < U; ++k) { bag[k] = nbag[k]; live[k] = nlive[k]; x[k] = nx[k]; }
     if (i + U < i1) load_batch_meta<kHasVals, U>(a, i + U, i1, nbag, nlive, nx);
-    accumulate_batch<D, U>(a, bag, live, x, sub, acc);
+    if (kRuns) accumulate_batch_runs<D, U>(a, bag, live, x, sub, acc, run);
+    else accumulate_batch<D, U>(a, bag, live, x, sub, acc);
   }
 }
 
@@ -607,7 +656,7 @@ __global__ __launch_bounds__(kBlock) void k_long_partial(const BwdArgs a) {
   const int per = (c_hi - c_lo + NG - 1) / NG;
   const int i0 = min(c_lo + g * per, c_hi), i1 = min(i0 + per, c_hi);
   Acc acc = acc_zero();
-  reduce_entries<D, kHasVals, 4>(a, i0, i1, sub, acc);
+  reduce_entries<D, kHasVals, 4, true>(a, i0, i1, sub, acc);
 #pragma unroll
   for (int m = G; m < kWave; m <<= 1) {
 #pragma unroll
