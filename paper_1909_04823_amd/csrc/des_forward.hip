@@ -2,9 +2,9 @@
 //   LR  M1 (Section 4.1, Eq. lr_m1), FM M1 and M2 (Section 4.2, Eq. fm_m1m2) and the per-field
 //   pooled embeddings (Section 4.3).
 //
-// Mapping: 1, 2 or 4 wave64s per sample.  A row of D floats is read by G = D/C adjacent lanes (C = 4 floats
-// per lane as one 16-byte load, or 8 as two), so a wave holds 64/G "lane groups" that each fetch a different
-// row at the same time.  Every group owns a contiguous range of the sample's bags and walks its
+// Mapping: 1, 2 or 4 wave64s per sample.  A row of D floats is read by G = D/4 adjacent lanes
+// as one 16-byte load each, so a wave holds 64/G "lane groups" that each fetch a different row
+// at the same time.  Every group owns a contiguous range of the sample's bags and walks its
 // entries in CSR order in chunks of G: lane i of the group loads the metadata of entry i of
 // the chunk (row, key -> shard, value, bag found in the sample's offsets staged in LDS) and
 // publishes it in LDS, from where the group reads entry j with one broadcast read; the row
@@ -12,9 +12,9 @@
 // pooled output is written once per bag, already summed over shards).  The per-shard FM / LR
 // partials of the sample live in LDS ([K][D+2] doubles per sample: D columns, then the sum of
 // squares and the LR sum) and are updated with LDS atomics, because the entries of one shard are
-// scattered over all groups.  The LDS copy is stored column-permuted (element m of lane sub at m*G+sub)
-// with a row pitch of D+2 doubles, so that the 64 lanes of one atomic instruction spread over the LDS
-// banks instead of piling onto a few.
+// scattered over all groups.  A lane owns columns 4*sub..4*sub+3 of a row but the LDS copy is
+// stored column-permuted (column 4*sub+k at k*G+sub) with a row pitch of D+2 doubles, so that the
+// 64 lanes of one atomic instruction spread over the LDS banks instead of piling onto a few.
 //
 // Accumulation is in double, inputs and outputs are fp32: a sample's sum of several hundred
 // signed terms cancels, and fp32 accumulation alone would exceed the 1e-5 relative bound
@@ -66,20 +66,12 @@ __device__ inline double group_sum(double q) {
 // entry).  Otherwise the field partition of Section 5: a bag belongs to shard f mod K as a whole, so its sums
 // are formed in registers and the shard's accumulators take one update per bag.
 // kHasVals: the batch carries feature values; without them every x is 1 and the products with x are left out.
-// C: floats of a row per lane, 4 or 8 (G = D/C lanes per row).  With 8 a lane holds two 16-byte pieces of the
-// row, columns 4*sub.. and D/2 + 4*sub.. (each load instruction still reads the row's lanes contiguously), and
-// the work per entry that does not depend on the row length (addresses, metadata, bag bookkeeping, the
-// cross-lane sum of squares) is spent once per 8 floats instead of once per 4.
-template <int D, int C, bool kByKey, bool kHasVals>
+template <int D, bool kByKey, bool kHasVals>
 __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   extern __shared__ __align__(16) double lds[];
-  static_assert(C == 4 || C == 8, "one or two 16-byte pieces per lane");
-  constexpr int G = D / C;                 // lanes per row = entries per chunk
-  constexpr int NQ = C / 4;                // 16-byte pieces of a row per lane
-  constexpr int QS = D / NQ;               // floats between a lane's pieces
+  constexpr int G = D / 4;                 // lanes per row = entries per chunk
   constexpr int NG = kWave / G;            // lane groups per wave
-  constexpr int U = C == 8 ? 4 : (G >= 16 ? 8 : (G < 4 ? G : 4));   // rows in flight per lane (measured: 8 pays from D = 64 on)
-  static_assert(U <= G, "a batch of gathers lies inside one chunk");
+  constexpr int U = G >= 16 ? 8 : (G < 4 ? G : 4);   // row gathers in flight per lane (measured: 8 pays from D = 64 on)
   constexpr int kLrLane = G > 1 ? 1 : 0;   // lane of a group that fetches and adds the LR weight
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / G, sub = lane % G;
@@ -107,26 +99,20 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
     const int f0 = (int)(((int64_t)F * gg) / ngt), f1 = (int)(((int64_t)F * (gg + 1)) / ngt);
     const int e0 = offs[f0], e1 = offs[f1];
     int cur = f0;                                         // bag whose sum is being accumulated
-    double acc[C];                                        // element m = 4*q + k is column q*QS + 4*sub + k
-#pragma unroll
-    for (int m = 0; m < C; ++m) acc[m] = 0.0;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
     double bag_sq = 0.0, bag_lr = 0.0;                    // field partition: this lane's share of the bag's scalars
     bool bag_dirty = false;
     float *pool_row = need_pool ? a.pool + (b * F) * (int64_t)D + sub * 4 : nullptr;
     // closes bag `cur`: pooled sum out; under the field partition also the bag's contribution to its shard
     auto close_bag = [&]() {
-      if (need_pool) {
-#pragma unroll
-        for (int q = 0; q < NQ; ++q)
-          st4(pool_row + (int64_t)cur * D + q * QS,
-              make_float4((float)acc[4 * q], (float)acc[4 * q + 1], (float)acc[4 * q + 2], (float)acc[4 * q + 3]));
-      }
+      if (need_pool)
+        st4(pool_row + (int64_t)cur * D, make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]));
       if (!kByKey && bag_dirty) {
         const int s = cur % K;
         if (need_fm) {
           double *dst = sum + s * P + sub;
 #pragma unroll
-          for (int m = 0; m < C; ++m) atomicAdd(dst + m * G, acc[m]);
+          for (int k = 0; k < 4; ++k) atomicAdd(dst + k * G, acc[k]);
           const double q = group_sum<G>(bag_sq);
           if (sub == 0) atomicAdd(sum + s * P + D, q);
         }
@@ -135,8 +121,7 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
         bag_lr = 0.0;
         bag_dirty = false;
       }
-#pragma unroll
-      for (int m = 0; m < C; ++m) acc[m] = 0.0;
+      acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
     };
 
     // metadata of entry e0 + sub of the first chunk; later chunks are fetched one chunk ahead
@@ -193,19 +178,15 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
       for (int j0 = 0; j0 < G; j0 += U) {
         if (j0 < cnt) {
           int4 md[U];
-          float4 v[U][NQ];
+          float4 v[U];
           float wv[U];
 #pragma unroll
           for (int i = 0; i < U; ++i) {
             md[i] = meta[g * G + j0 + i];
-#pragma unroll
-            for (int q = 0; q < NQ; ++q) v[i][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
             wv[i] = 0.f;
             if (j0 + i < cnt && md[i].x >= 0) {
-              if (need_v) {
-#pragma unroll
-                for (int q = 0; q < NQ; ++q) v[i][q] = ld4(a.emb + (int64_t)md[i].x * D + q * QS + sub * 4);
-              }
+              if (need_v) v[i] = ld4(a.emb + (int64_t)md[i].x * D + sub * 4);
               if (need_lr && sub == kLrLane) wv[i] = a.w[md[i].x];
             }
           }
@@ -219,22 +200,12 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
               }
               if (md[i].x >= 0) {
                 const double xd = kHasVals ? (double)__int_as_float(md[i].w) : 1.0;
-                double xv[C];
+                const double xv[4] = {kHasVals ? xd * (double)v[i].x : (double)v[i].x, kHasVals ? xd * (double)v[i].y : (double)v[i].y,
+                                      kHasVals ? xd * (double)v[i].z : (double)v[i].z, kHasVals ? xd * (double)v[i].w : (double)v[i].w};
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) {
-                  xv[4 * q] = kHasVals ? xd * (double)v[i][q].x : (double)v[i][q].x;
-                  xv[4 * q + 1] = kHasVals ? xd * (double)v[i][q].y : (double)v[i][q].y;
-                  xv[4 * q + 2] = kHasVals ? xd * (double)v[i][q].z : (double)v[i][q].z;
-                  xv[4 * q + 3] = kHasVals ? xd * (double)v[i][q].w : (double)v[i][q].w;
-                }
-                double sq = 0.0;
-#pragma unroll
-                for (int m = 0; m < C; ++m) {
-                  acc[m] += xv[m];
-                  sq += xv[m] * xv[m];
-                }
+                for (int k = 0; k < 4; ++k) acc[k] += xv[k];
                 if (!kByKey) {
-                  bag_sq += sq;
+                  bag_sq += xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
                   bag_lr += xd * (double)wv[i];
                   bag_dirty = true;
                   continue;
@@ -243,8 +214,8 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
                 if (need_fm) {
                   double *dst = sum + s * P + sub;
 #pragma unroll
-                  for (int m = 0; m < C; ++m) atomicAdd(dst + m * G, xv[m]);
-                  q = group_sum<G>(sq);
+                  for (int k = 0; k < 4; ++k) atomicAdd(dst + k * G, xv[k]);
+                  q = group_sum<G>(xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3]);
                 }
                 // one LDS instruction for both scalars: lane 0 adds the sum of squares, lane kLrLane
                 // the LR term (the same lane when a row is a single lane wide)
@@ -270,8 +241,8 @@ __global__ __launch_bounds__(kBlock) void k_forward(const FwdArgs a) {
   if (active) {
     if (need_fm) {
       for (int idx = tis * 4; idx < K * D; idx += nts * 4) {
-        const int s = idx / D, d = idx % D;                 // columns d..d+3: piece d / QS, lane (d % QS) / 4
-        const double *row = sum + s * P + (d / QS) * 4 * G + (d % QS) / 4;
+        const int s = idx / D, d = idx % D;                 // d = 4*sub: columns d..d+3 sit at k*G + sub
+        const double *row = sum + s * P + d / 4;
         st4(a.P_sum + ((int64_t)s * a.B + b) * D + d,
             make_float4((float)row[0], (float)row[G], (float)row[2 * G], (float)row[3 * G]));
       }
@@ -311,23 +282,15 @@ __global__ __launch_bounds__(kBlock) void k_pool_dense(const FwdArgs a, float *_
   }
 }
 
-template <int D, int C>
-void launch_forward_cols(bool by_key, bool has_vals, dim3 grid, dim3 block, size_t shmem, hipStream_t s, const FwdArgs &a) {
-  if (by_key) {
-    if (has_vals) hipLaunchKernelGGL((k_forward<D, C, true, true>), grid, block, shmem, s, a);
-    else hipLaunchKernelGGL((k_forward<D, C, true, false>), grid, block, shmem, s, a);
-  } else {
-    if (has_vals) hipLaunchKernelGGL((k_forward<D, C, false, true>), grid, block, shmem, s, a);
-    else hipLaunchKernelGGL((k_forward<D, C, false, false>), grid, block, shmem, s, a);
-  }
-}
-
 template <int D>
 void launch_forward(bool by_key, bool has_vals, dim3 grid, dim3 block, size_t shmem, hipStream_t s, const FwdArgs &a) {
-  // Eight floats per lane from D = 64 on: 7.29 -> 7.00 ms at the large table (D = 64), no change at the streaming
-  // workload (D = 64); at D = 32 it is slower than four (253 vs 236 us at the DeepFM-shaped workload).
-  if constexpr (D >= 64) launch_forward_cols<D, 8>(by_key, has_vals, grid, block, shmem, s, a);
-  else launch_forward_cols<D, 4>(by_key, has_vals, grid, block, shmem, s, a);
+  if (by_key) {
+    if (has_vals) hipLaunchKernelGGL((k_forward<D, true, true>), grid, block, shmem, s, a);
+    else hipLaunchKernelGGL((k_forward<D, true, false>), grid, block, shmem, s, a);
+  } else {
+    if (has_vals) hipLaunchKernelGGL((k_forward<D, false, true>), grid, block, shmem, s, a);
+    else hipLaunchKernelGGL((k_forward<D, false, false>), grid, block, shmem, s, a);
+  }
 }
 
 FwdArgs make_args(des_table *t, const des_batch_t *b, const int32_t *rows) {
