@@ -538,6 +538,45 @@ def test_integers_are_deterministic_run_to_run(oracle, des):
         assert_equal(a, b, "run-to-run")
 
 
+def test_kernel_timer_counts_launches_from_two_threads(des):
+    """Two host threads drive two tables on two streams while the kernel timer is on (ctypes releases the
+    interpreter lock during the calls): every launch is recorded once, and each thread's results are right."""
+    import threading
+    import torch
+    n_calls, n_keys = 40, 4096
+    tables = [des.Table(8, 1 << 14, 2, max_n=n_keys) for _ in range(2)]
+    keys = [torch.arange(1 + i * 100000, 1 + i * 100000 + n_keys, dtype=torch.int64, device="cuda") for i in range(2)]
+    for t, k in zip(tables, keys):
+        t.insert(k)
+    torch.cuda.synchronize()
+    results, errors = [None, None], []
+
+    def work(i):
+        try:
+            with torch.cuda.stream(torch.cuda.Stream()):
+                for _ in range(n_calls):
+                    rows = tables[i].find(keys[i])
+                torch.cuda.current_stream().synchronize()
+                results[i] = rows.cpu().numpy()
+        except Exception as e:                                # surfaced by the assertion below
+            errors.append(e)
+
+    des.profile_enable(True)
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    prof = des.profile_read()
+    des.profile_enable(False)
+    assert not errors, errors
+    assert prof["table_probe"][0] == 2 * n_calls and prof["table_probe"][1] > 0.0
+    for r in results:
+        assert_equal(r, np.arange(n_keys, dtype=np.int32), "rows seen by a thread")
+    for t in tables:
+        t.close()
+
+
 def test_host_side_argument_checks(des):
     import ctypes as C
     import torch
